@@ -1,0 +1,167 @@
+/*
+ * qp.h -- C ABI of the QuickPrefill hot path for AMD MI355X (gfx950).
+ *
+ * QuickPrefill (Sec. 3.2 of the QuickVideo paper) prefills the video tokens of one
+ * transformer layer group by group of frames. For each group:
+ *   1. the group's queries attend to the pruned KV cache kept from earlier groups plus
+ *      the group's own keys/values under a causal mask        -> qp_group_attend
+ *   2. every new KV entry gets an importance score per KV head (Key Norms (small),
+ *      Value Norms or Attention Scores, listed under Eq. 2)   -> qp_score_kv
+ *   3. TopK keeps k = ceil(rho * N_g) entries per head and the survivors
+ *      K_g[I_g], V_g[I_g] (Eq. 2) are appended to the cache   -> qp_topk_compact
+ * qp_prefill_video runs the three steps over all groups of a layer.
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer (HIP global memory) unless it says "host".
+ *     All tensors are dense, row-major, 16-byte aligned. The qp_layout / qp_cache
+ *     structs themselves live in HOST memory.
+ *   - Tokens are the slow axis: activations are [tokens][heads][head_dim]. Query head qh
+ *     reads KV head qh / (n_q_heads / n_kv_heads) (grouped-query attention).
+ *   - The library allocates nothing and keeps no pointer after a call returns; scratch
+ *     memory is the caller's `workspace` (size from qp_workspace_bytes, 256-byte aligned).
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream). No call synchronises with the host or reads anything back:
+ *     `cache->len` is host arithmetic and is already updated when a call returns, while
+ *     the copies it describes may still be in flight on the stream.
+ *   - Errors are returned as qp_status; nothing throws or aborts. Argument errors are
+ *     detected on the host before anything is launched and leave `cache` untouched.
+ *   - Same inputs give bit-identical kept indices, positions and cache contents.
+ *   - Supported: dtype f32 or bf16, head_dim 64 or 128, n_q_heads a multiple of
+ *     n_kv_heads, group size <= QP_MAX_GROUP_TOKENS.
+ */
+#ifndef QP_H_
+#define QP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QP_MAX_GROUP_TOKENS 32768
+
+typedef enum {
+  QP_OK = 0,
+  QP_ERR_INVALID_ARG = 1, /* NULL / misaligned pointer, non-positive size, bad enum          */
+  QP_ERR_UNSUPPORTED = 2, /* dtype / head_dim / group size this build has no kernel for      */
+  QP_ERR_CAPACITY = 3,    /* cache capacity or workspace too small                           */
+  QP_ERR_HIP = 4          /* a launch failed; qp_last_hip_error() holds the hipError_t value */
+} qp_status;
+
+typedef enum { QP_F32 = 0, QP_BF16 = 1 } qp_dtype;
+
+/* The three importance functions listed under Eq. 2 (Sec. 3.2). Larger score = kept first. */
+typedef enum {
+  QP_SCORE_KEY_NORM_SMALL = 0, /* s = -||K_g[j,h,:]||_2  (the paper's default)                  */
+  QP_SCORE_VALUE_NORM = 1,     /* s = +||V_g[j,h,:]||_2                                          */
+  QP_SCORE_WINDOW_ATTN = 2     /* "Attention Scores": softmax attention mass that key j of KV
+                                  head h receives from the text-query window, softmax taken over
+                                  the group's own keys, summed over the window's queries and over
+                                  the query heads that map to h                                  */
+} qp_score_rule;
+
+/* Which attention kernel qp_group_attend uses. AUTO picks the MFMA kernel when the
+ * layout allows it (bf16, head_dim 128), else the scalar one. */
+typedef enum { QP_ATTEND_AUTO = 0, QP_ATTEND_SCALAR = 1, QP_ATTEND_MFMA = 2 } qp_attend_kernel;
+
+typedef struct {
+  int32_t n_q_heads;   /* H_q                                                   */
+  int32_t n_kv_heads;  /* H_kv, divides H_q                                     */
+  int32_t head_dim;    /* d                                                     */
+  int32_t dtype;       /* qp_dtype of q/k/v/out and of the cache                */
+  float softmax_scale; /* logit scale; 0 means 1/sqrt(head_dim)                 */
+} qp_layout;
+
+/* The pruned KV cache of one layer (Sec. 3.2, "store the corresponding KV cache"):
+ * the same number of entries `len` for every KV head, in ascending token order. */
+typedef struct {
+  void* k;          /* device, [n_kv_heads][capacity][head_dim], layout dtype            */
+  void* v;          /* device, [n_kv_heads][capacity][head_dim]                          */
+  int32_t* pos;     /* device, [n_kv_heads][capacity]: video-token index of each entry   */
+  int32_t capacity; /* entries per head the buffers can hold                             */
+  int32_t len;      /* host: entries per head currently valid; updated by qp_topk_compact */
+} qp_cache;
+
+/* ---- host arithmetic (no device work) ------------------------------------------------ */
+
+/* k of Eq. 2 for a group of n tokens: ceil(retention * n - 1e-9) clamped to [1, n]; 0 if n <= 0.
+ * retention outside (0, 1] returns -1. */
+int64_t qp_keep_count(int64_t n_group_tokens, double retention);
+
+/* Entries per head the cache must hold after all frame-aligned groups of a video
+ * (groups of group_frames frames, the last one possibly shorter). -1 on bad arguments. */
+int64_t qp_cache_capacity(int32_t n_frames, int32_t tokens_per_frame, int32_t group_frames, double retention);
+
+/* Bytes of workspace that every entry point accepts for groups of at most max_group_tokens
+ * tokens and a query window of n_window rows. 0 on bad arguments. */
+size_t qp_workspace_bytes(const qp_layout* layout, int32_t max_group_tokens, int32_t n_window);
+
+/* ---- the hot path ----------------------------------------------------------------------- */
+
+/* Group attention (Sec. 2.1 softmax self-attention, applied per group as in Sec. 3.2).
+ *   q_g [n_group_tokens][H_q][d], k_g, v_g [n_group_tokens][H_kv][d]  (read)
+ *   cache: entries [0, cache->len) of every head are read; may be NULL or len 0 (first group)
+ *   out_g [n_group_tokens][H_q][d], layout dtype (written)
+ *   lse_or_null [H_q][n_group_tokens] f32: natural-log sum of exp(scale*q.k) over the visible
+ *     keys of each row (written if not NULL)
+ * Row i of query head qh sees all cache entries of KV head qh/R and group tokens j <= i.
+ * Arithmetic: products and sums in f32 (bf16 inputs are widened exactly; the MFMA kernel
+ * rounds the softmax numerators to bf16 before the P.V product); output rounded to nearest even.
+ * Errors: INVALID_ARG (NULL/misaligned pointers, n_group_tokens <= 0, bad layout),
+ * UNSUPPORTED (dtype/head_dim/group size). The cache is not modified. */
+qp_status qp_group_attend(const qp_layout* layout, const void* q_g, const void* k_g, const void* v_g,
+                          int32_t n_group_tokens, const qp_cache* cache, void* out_g, float* lse_or_null,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Importance scores of a group's new KV entries (the functions listed under Eq. 2).
+ *   k_g, v_g as above (the norm rules read only the tensor they name; the other may be NULL)
+ *   q_win [n_window][H_q][d]: the text-query window (QP_SCORE_WINDOW_ATTN only, else ignored)
+ *   scores [H_kv][n_group_tokens] f32 (written)
+ * f32 arithmetic. Errors as above; WINDOW_ATTN with q_win NULL or n_window <= 0 is INVALID_ARG;
+ * CAPACITY if the workspace is too small. */
+qp_status qp_score_kv(const qp_layout* layout, qp_score_rule rule, const void* k_g, const void* v_g,
+                      int32_t n_group_tokens, const void* q_win, int32_t n_window, float* scores,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* TopK of Eq. 2 per KV head and compaction of the survivors into the cache.
+ *   scores [H_kv][n_group_tokens] f32 (read). Ordering: larger first, equal scores (and
+ *     -0.0 == +0.0) by lower token index; scores must not be NaN.
+ *   keep: k, 1 <= keep <= n_group_tokens
+ *   group_token_base: video-token index of the group's first token (recorded in cache->pos)
+ *   cache: rows K_g[I], V_g[I] are appended at [len, len+keep) of every head in ascending
+ *     token order, pos gets group_token_base + I, then cache->len += keep (host side)
+ *   kept_idx_or_null [H_kv][keep] int32: group-local kept indices, ascending (written if not NULL)
+ * Errors: INVALID_ARG, UNSUPPORTED, CAPACITY (len + keep > capacity, or workspace too small);
+ * on any error the cache is untouched. */
+qp_status qp_topk_compact(const qp_layout* layout, const float* scores, const void* k_g, const void* v_g,
+                          int32_t n_group_tokens, int32_t keep, int32_t group_token_base, qp_cache* cache,
+                          int32_t* kept_idx_or_null, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* One layer of QuickPrefill over a whole video (Sec. 3.2): frame-aligned groups of
+ * group_frames frames in order, each attended, scored, pruned and compacted.
+ *   q [N][H_q][d], k, v [N][H_kv][d] with N = n_frames * tokens_per_frame
+ *   q_win [n_window][H_q][d] or NULL (needed by QP_SCORE_WINDOW_ATTN)
+ *   cache: appended starting at cache->len (normally 0); entries already in it are visible
+ *     to every group. Needs capacity >= len + qp_cache_capacity(...).
+ *   out [N][H_q][d]
+ * All arguments are validated before the first launch. */
+qp_status qp_prefill_video(const qp_layout* layout, int32_t n_frames, int32_t tokens_per_frame,
+                           int32_t group_frames, double retention, qp_score_rule rule, const void* q,
+                           const void* k, const void* v, const void* q_win, int32_t n_window, qp_cache* cache,
+                           void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ---- control / diagnostics ------------------------------------------------------------------ */
+
+/* Choose the attention kernel for later qp_group_attend / qp_prefill_video calls of this
+ * process (tests use it to cover both). Returns INVALID_ARG for an unknown value. */
+qp_status qp_select_attend_kernel(int32_t which);
+
+const char* qp_status_string(qp_status s); /* static string, never NULL */
+int qp_last_hip_error(void);               /* hipError_t of the last failed launch on this thread, 0 if none */
+const char* qp_version(void);              /* static string */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QP_H_ */

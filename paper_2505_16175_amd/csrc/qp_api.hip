@@ -1,0 +1,291 @@
+// C-ABI entry points of libqp_hip.so: argument validation, workspace carving, launches,
+// and the per-layer group loop of QuickPrefill (Sec. 3.2). Host code only; kernels live in
+// the other translation units.
+#include <math.h>
+#include <string.h>
+
+#include "qp_internal.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+int g_attend_kernel = QP_ATTEND_AUTO;
+
+inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+inline size_t round256(size_t x) { return (x + 255) / 256 * 256; }
+
+qp_status check_layout(const qp_layout* L) {
+  if (L == nullptr) return QP_ERR_INVALID_ARG;
+  if (L->n_q_heads <= 0 || L->n_kv_heads <= 0 || L->head_dim <= 0) return QP_ERR_INVALID_ARG;
+  if (L->n_q_heads % L->n_kv_heads != 0) return QP_ERR_INVALID_ARG;
+  if (L->dtype != QP_F32 && L->dtype != QP_BF16) return QP_ERR_INVALID_ARG;
+  if (!(L->softmax_scale >= 0.f) || isinf(L->softmax_scale)) return QP_ERR_INVALID_ARG;
+  if (L->head_dim != 64 && L->head_dim != 128) return QP_ERR_UNSUPPORTED;
+  if (L->n_q_heads > 65535 || L->n_kv_heads > 65535) return QP_ERR_UNSUPPORTED;
+  return QP_OK;
+}
+
+qp_status check_group(int32_t n_g) {
+  if (n_g <= 0) return QP_ERR_INVALID_ARG;
+  if (n_g > QP_MAX_GROUP_TOKENS) return QP_ERR_UNSUPPORTED;
+  return QP_OK;
+}
+
+qp_status check_cache(const qp_cache* c, bool required) {
+  if (c == nullptr) return required ? QP_ERR_INVALID_ARG : QP_OK;
+  if (c->capacity < 0 || c->len < 0 || c->len > c->capacity) return QP_ERR_INVALID_ARG;
+  if (c->len > 0 || required) {
+    if (c->k == nullptr || c->v == nullptr || !aligned16(c->k) || !aligned16(c->v)) return QP_ERR_INVALID_ARG;
+  }
+  if (required && (c->pos == nullptr || (((uintptr_t)c->pos) & 3u))) return QP_ERR_INVALID_ARG;
+  return QP_OK;
+}
+
+float scale_log2_of(const qp_layout* L) {
+  const float scale = L->softmax_scale > 0.f ? L->softmax_scale : 1.0f / sqrtf((float)L->head_dim);
+  return scale * 1.4426950408889634f;
+}
+
+qp_status finish(hipError_t launch_err) {
+  hipError_t e = launch_err != hipSuccess ? launch_err : hipGetLastError();
+  if (e != hipSuccess) {
+    g_last_hip_error = (int)e;
+    return QP_ERR_HIP;
+  }
+  return QP_OK;
+}
+
+// Workspace layout: [scores H_kv*n_g f32][window scratch].
+size_t scores_bytes(const qp_layout* L, int32_t n_g) { return round256((size_t)L->n_kv_heads * n_g * sizeof(float)); }
+
+}  // namespace
+
+extern "C" {
+
+int64_t qp_keep_count(int64_t n, double retention) {
+  if (!(retention > 0.0) || retention > 1.0) return -1;
+  if (n <= 0) return 0;
+  int64_t k = (int64_t)ceil(retention * (double)n - 1e-9);
+  if (k < 1) k = 1;
+  if (k > n) k = n;
+  return k;
+}
+
+int64_t qp_cache_capacity(int32_t n_frames, int32_t tokens_per_frame, int32_t group_frames, double retention) {
+  if (n_frames <= 0 || tokens_per_frame <= 0 || group_frames <= 0) return -1;
+  if (!(retention > 0.0) || retention > 1.0) return -1;
+  int64_t total = 0;
+  for (int64_t f = 0; f < n_frames; f += group_frames) {
+    const int64_t g = (n_frames - f) < group_frames ? (n_frames - f) : group_frames;
+    total += qp_keep_count(g * tokens_per_frame, retention);
+  }
+  return total;
+}
+
+size_t qp_workspace_bytes(const qp_layout* L, int32_t max_group_tokens, int32_t n_window) {
+  if (check_layout(L) != QP_OK || check_group(max_group_tokens) != QP_OK || n_window < 0) return 0;
+  size_t b = scores_bytes(L, max_group_tokens);
+  b += qp::window_workspace_bytes(L->n_q_heads, L->n_kv_heads, max_group_tokens, n_window > 0 ? n_window : 1);
+  return b + 256;
+}
+
+qp_status qp_select_attend_kernel(int32_t which) {
+  if (which != QP_ATTEND_AUTO && which != QP_ATTEND_SCALAR && which != QP_ATTEND_MFMA) return QP_ERR_INVALID_ARG;
+  g_attend_kernel = which;
+  return QP_OK;
+}
+
+qp_status qp_group_attend(const qp_layout* L, const void* q_g, const void* k_g, const void* v_g, int32_t n_g,
+                          const qp_cache* cache, void* out_g, float* lse, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  qp_status st = check_layout(L);
+  if (st != QP_OK) return st;
+  if ((st = check_group(n_g)) != QP_OK) return st;
+  if ((st = check_cache(cache, false)) != QP_OK) return st;
+  if (!q_g || !k_g || !v_g || !out_g) return QP_ERR_INVALID_ARG;
+  if (!aligned16(q_g) || !aligned16(k_g) || !aligned16(v_g) || !aligned16(out_g)) return QP_ERR_INVALID_ARG;
+  if (lse && (((uintptr_t)lse) & 3u)) return QP_ERR_INVALID_ARG;
+
+  qp::AttendArgs a;
+  a.q = q_g;
+  a.k = k_g;
+  a.v = v_g;
+  a.c = cache ? cache->len : 0;
+  a.cap = cache ? cache->capacity : 0;
+  a.ck = a.c > 0 ? cache->k : nullptr;
+  a.cv = a.c > 0 ? cache->v : nullptr;
+  a.out = out_g;
+  a.lse = lse;
+  a.n_g = n_g;
+  a.h_q = L->n_q_heads;
+  a.h_kv = L->n_kv_heads;
+  a.d = L->head_dim;
+  a.scale_log2 = scale_log2_of(L);
+
+  hipStream_t s = (hipStream_t)hip_stream;
+  const bool mfma_ok = qp::attend_mfma_supported(a, L->dtype);
+  if (g_attend_kernel == QP_ATTEND_MFMA && !mfma_ok) return QP_ERR_UNSUPPORTED;
+  if (mfma_ok && g_attend_kernel != QP_ATTEND_SCALAR) qp::launch_attend_mfma(a, s);
+  else qp::launch_attend_scalar(a, L->dtype, s);
+  return finish(hipSuccess);
+}
+
+qp_status qp_score_kv(const qp_layout* L, qp_score_rule rule, const void* k_g, const void* v_g, int32_t n_g,
+                      const void* q_win, int32_t n_window, float* scores, void* workspace, size_t workspace_bytes,
+                      void* hip_stream) {
+  qp_status st = check_layout(L);
+  if (st != QP_OK) return st;
+  if ((st = check_group(n_g)) != QP_OK) return st;
+  if (!scores || (((uintptr_t)scores) & 3u)) return QP_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)hip_stream;
+  switch (rule) {
+    case QP_SCORE_KEY_NORM_SMALL:
+      if (!k_g || !aligned16(k_g)) return QP_ERR_INVALID_ARG;
+      qp::launch_score_norm(k_g, L->dtype, n_g, L->n_kv_heads, L->head_dim, -1.f, scores, s);
+      break;
+    case QP_SCORE_VALUE_NORM:
+      if (!v_g || !aligned16(v_g)) return QP_ERR_INVALID_ARG;
+      qp::launch_score_norm(v_g, L->dtype, n_g, L->n_kv_heads, L->head_dim, +1.f, scores, s);
+      break;
+    case QP_SCORE_WINDOW_ATTN: {
+      if (!k_g || !aligned16(k_g) || !q_win || !aligned16(q_win) || n_window <= 0) return QP_ERR_INVALID_ARG;
+      if (n_window > 65535) return QP_ERR_UNSUPPORTED;
+      const size_t need = qp::window_workspace_bytes(L->n_q_heads, L->n_kv_heads, n_g, n_window);
+      if (!workspace || (((uintptr_t)workspace) & 255u)) return QP_ERR_INVALID_ARG;
+      if (workspace_bytes < need) return QP_ERR_CAPACITY;
+      qp::WindowArgs w;
+      w.k = k_g;
+      w.q_win = q_win;
+      w.scores = scores;
+      w.workspace = workspace;
+      w.n_g = n_g;
+      w.h_q = L->n_q_heads;
+      w.h_kv = L->n_kv_heads;
+      w.d = L->head_dim;
+      w.w = n_window;
+      w.scale_log2 = scale_log2_of(L);
+      qp::launch_score_window(w, L->dtype, s);
+      break;
+    }
+    default:
+      return QP_ERR_INVALID_ARG;
+  }
+  return finish(hipSuccess);
+}
+
+qp_status qp_topk_compact(const qp_layout* L, const float* scores, const void* k_g, const void* v_g, int32_t n_g,
+                          int32_t keep, int32_t group_token_base, qp_cache* cache, int32_t* kept_idx, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  qp_status st = check_layout(L);
+  if (st != QP_OK) return st;
+  if ((st = check_group(n_g)) != QP_OK) return st;
+  if ((st = check_cache(cache, true)) != QP_OK) return st;
+  if (!scores || (((uintptr_t)scores) & 3u) || !k_g || !v_g || !aligned16(k_g) || !aligned16(v_g))
+    return QP_ERR_INVALID_ARG;
+  if (kept_idx && (((uintptr_t)kept_idx) & 3u)) return QP_ERR_INVALID_ARG;
+  if (keep < 1 || keep > n_g || group_token_base < 0) return QP_ERR_INVALID_ARG;
+  if ((int64_t)cache->len + keep > cache->capacity) return QP_ERR_CAPACITY;
+
+  qp::TopkArgs a;
+  a.scores = scores;
+  a.k = k_g;
+  a.v = v_g;
+  a.ck = cache->k;
+  a.cv = cache->v;
+  a.pos = cache->pos;
+  a.kept = kept_idx;
+  a.n_g = n_g;
+  a.h_kv = L->n_kv_heads;
+  a.d = L->head_dim;
+  a.keep = keep;
+  a.base = group_token_base;
+  a.cap = cache->capacity;
+  a.len = cache->len;
+  st = finish(qp::launch_topk_compact(a, L->dtype, (hipStream_t)hip_stream));
+  if (st == QP_OK) cache->len += keep;
+  return st;
+}
+
+qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_per_frame, int32_t group_frames,
+                           double retention, qp_score_rule rule, const void* q, const void* k, const void* v,
+                           const void* q_win, int32_t n_window, qp_cache* cache, void* out, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+  qp_status st = check_layout(L);
+  if (st != QP_OK) return st;
+  if (n_frames <= 0 || tokens_per_frame <= 0 || group_frames <= 0) return QP_ERR_INVALID_ARG;
+  if (!(retention > 0.0) || retention > 1.0) return QP_ERR_INVALID_ARG;
+  if (rule != QP_SCORE_KEY_NORM_SMALL && rule != QP_SCORE_VALUE_NORM && rule != QP_SCORE_WINDOW_ATTN)
+    return QP_ERR_INVALID_ARG;
+  const int64_t n_total = (int64_t)n_frames * tokens_per_frame;
+  if (n_total > INT32_MAX) return QP_ERR_UNSUPPORTED;
+  const int64_t max_group = (int64_t)(group_frames < n_frames ? group_frames : n_frames) * tokens_per_frame;
+  if (max_group > QP_MAX_GROUP_TOKENS) return QP_ERR_UNSUPPORTED;
+  if ((st = check_cache(cache, true)) != QP_OK) return st;
+  if (!q || !k || !v || !out || !aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
+    return QP_ERR_INVALID_ARG;
+  if (rule == QP_SCORE_WINDOW_ATTN && (!q_win || !aligned16(q_win) || n_window <= 0)) return QP_ERR_INVALID_ARG;
+  if (rule == QP_SCORE_WINDOW_ATTN && n_window > 65535) return QP_ERR_UNSUPPORTED;
+  if (!workspace || (((uintptr_t)workspace) & 255u)) return QP_ERR_INVALID_ARG;
+  if (workspace_bytes < qp_workspace_bytes(L, (int32_t)max_group, rule == QP_SCORE_WINDOW_ATTN ? n_window : 0))
+    return QP_ERR_CAPACITY;
+  if ((int64_t)cache->len + qp_cache_capacity(n_frames, tokens_per_frame, group_frames, retention) > cache->capacity)
+    return QP_ERR_CAPACITY;
+  if (g_attend_kernel == QP_ATTEND_MFMA) {
+    qp::AttendArgs probe;
+    memset(&probe, 0, sizeof(probe));
+    probe.h_q = L->n_q_heads;
+    probe.h_kv = L->n_kv_heads;
+    probe.d = L->head_dim;
+    probe.n_g = (int)max_group;
+    if (!qp::attend_mfma_supported(probe, L->dtype)) return QP_ERR_UNSUPPORTED;
+  }
+
+  const size_t esz = L->dtype == QP_F32 ? 4 : 2;
+  const size_t q_tok = (size_t)L->n_q_heads * L->head_dim * esz;
+  const size_t kv_tok = (size_t)L->n_kv_heads * L->head_dim * esz;
+  float* scores = (float*)workspace;
+  const size_t sb = scores_bytes(L, (int32_t)max_group);
+  void* ws2 = (char*)workspace + sb;
+  const size_t ws2_bytes = workspace_bytes - sb;
+
+  for (int32_t f = 0; f < n_frames; f += group_frames) {
+    const int32_t g = (n_frames - f) < group_frames ? (n_frames - f) : group_frames;
+    const int32_t base = f * tokens_per_frame, n_g = g * tokens_per_frame;
+    const char* qg = (const char*)q + (size_t)base * q_tok;
+    const char* kg = (const char*)k + (size_t)base * kv_tok;
+    const char* vg = (const char*)v + (size_t)base * kv_tok;
+    char* og = (char*)out + (size_t)base * q_tok;
+    // 1. attend to the pruned cache so far + the group itself
+    st = qp_group_attend(L, qg, kg, vg, n_g, cache, og, nullptr, ws2, ws2_bytes, hip_stream);
+    if (st != QP_OK) return st;
+    // 2. score the group's new KV entries
+    st = qp_score_kv(L, rule, kg, vg, n_g, q_win, n_window, scores, ws2, ws2_bytes, hip_stream);
+    if (st != QP_OK) return st;
+    // 3. TopK + compaction into the cache (cache->len advances on the host)
+    st = qp_topk_compact(L, scores, kg, vg, n_g, (int32_t)qp_keep_count(n_g, retention), base, cache, nullptr, ws2,
+                         ws2_bytes, hip_stream);
+    if (st != QP_OK) return st;
+  }
+  return QP_OK;
+}
+
+const char* qp_status_string(qp_status s) {
+  switch (s) {
+    case QP_OK: return "ok";
+    case QP_ERR_INVALID_ARG: return "invalid argument";
+    case QP_ERR_UNSUPPORTED: return "unsupported dtype, head_dim or size";
+    case QP_ERR_CAPACITY: return "cache capacity or workspace too small";
+    case QP_ERR_HIP: return "HIP launch failed";
+  }
+  return "unknown status";
+}
+
+int qp_last_hip_error(void) { return g_last_hip_error; }
+
+const char* qp_version(void) { return "quickprefill-gfx950 0.1"; }
+
+}  // extern "C"

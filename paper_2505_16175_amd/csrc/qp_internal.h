@@ -1,0 +1,117 @@
+// Internal declarations shared by the translation units of libqp_hip.so (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qp.h"
+
+namespace qp {
+
+// bf16 is handled as raw 16-bit patterns: widening is a shift, narrowing is round-to-nearest-even.
+typedef uint16_t bf16_t;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
+__device__ __forceinline__ float bf16lo_to_f32(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16hi_to_f32(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
+__device__ __forceinline__ bf16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);  // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T>
+struct Elem;
+template <>
+struct Elem<float> {
+  static constexpr int kPer16B = 4;
+};
+template <>
+struct Elem<bf16_t> {
+  static constexpr int kPer16B = 8;
+};
+
+// Widen one 16-byte chunk (uint4) of T into kPer16B floats.
+template <typename T>
+__device__ __forceinline__ void widen16(const uint4& raw, float* out);
+template <>
+__device__ __forceinline__ void widen16<float>(const uint4& raw, float* out) {
+  out[0] = __uint_as_float(raw.x);
+  out[1] = __uint_as_float(raw.y);
+  out[2] = __uint_as_float(raw.z);
+  out[3] = __uint_as_float(raw.w);
+}
+template <>
+__device__ __forceinline__ void widen16<bf16_t>(const uint4& raw, float* out) {
+  out[0] = bf16lo_to_f32(raw.x);
+  out[1] = bf16hi_to_f32(raw.x);
+  out[2] = bf16lo_to_f32(raw.y);
+  out[3] = bf16hi_to_f32(raw.y);
+  out[4] = bf16lo_to_f32(raw.z);
+  out[5] = bf16hi_to_f32(raw.z);
+  out[6] = bf16lo_to_f32(raw.w);
+  out[7] = bf16hi_to_f32(raw.w);
+}
+
+template <typename T>
+__device__ __forceinline__ void store_elem(T* p, float v);
+template <>
+__device__ __forceinline__ void store_elem<float>(float* p, float v) { *p = v; }
+template <>
+__device__ __forceinline__ void store_elem<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16_rne(v); }
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Arguments common to the attention kernels. All pointers are device pointers.
+struct AttendArgs {
+  const void* q;      // [n_g][h_q][d]
+  const void* k;      // [n_g][h_kv][d]
+  const void* v;      // [n_g][h_kv][d]
+  const void* ck;     // [h_kv][cap][d] or nullptr when c == 0
+  const void* cv;
+  void* out;          // [n_g][h_q][d]
+  float* lse;         // [h_q][n_g] or nullptr
+  int n_g, h_q, h_kv, d, c, cap;
+  float scale_log2;   // softmax scale * log2(e)
+};
+
+// Launchers (defined next to their kernels). They only enqueue; hipGetLastError is checked by the caller.
+void launch_attend_scalar(const AttendArgs& a, int dtype, hipStream_t s);
+bool attend_mfma_supported(const AttendArgs& a, int dtype);
+void launch_attend_mfma(const AttendArgs& a, hipStream_t s);
+
+void launch_score_norm(const void* x, int dtype, int n_g, int h_kv, int d, float sign, float* scores, hipStream_t s);
+
+struct WindowArgs {
+  const void* k;      // [n_g][h_kv][d]
+  const void* q_win;  // [w][h_q][d]
+  float* scores;      // [h_kv][n_g]
+  void* workspace;
+  int n_g, h_q, h_kv, d, w;
+  float scale_log2;
+};
+size_t window_workspace_bytes(int h_q, int h_kv, int n_g, int w);
+void launch_score_window(const WindowArgs& a, int dtype, hipStream_t s);
+
+struct TopkArgs {
+  const float* scores;  // [h_kv][n_g]
+  const void* k;        // [n_g][h_kv][d]
+  const void* v;
+  void* ck;             // [h_kv][cap][d]
+  void* cv;
+  int32_t* pos;         // [h_kv][cap]
+  int32_t* kept;        // [h_kv][keep] or nullptr
+  int n_g, h_kv, d, keep, base, cap, len;
+};
+hipError_t launch_topk_compact(const TopkArgs& a, int dtype, hipStream_t s);
+
+}  // namespace qp

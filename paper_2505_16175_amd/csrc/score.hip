@@ -1,0 +1,169 @@
+// Importance scores of a group's new KV entries (the functions listed under Eq. 2, Sec. 3.2).
+//
+//   Key Norms (small):  s[h][j] = -||K_g[j,h,:]||_2
+//   Value Norms:        s[h][j] = +||V_g[j,h,:]||_2
+//   Attention Scores:   s[h][j] = sum over query heads qh of KV head h and window rows t of
+//                       softmax_j(scale * Q_win[t,qh,:] . K_g[j,h,:])   (softmax over the group's keys)
+//
+// Norms: a row of d elements is 256 bytes (bf16 d=128, f32 d=64) or a multiple of 16 bytes in
+// general; LPR = row bytes / 16 lanes load one 16-byte chunk each, square-accumulate in f32 and
+// finish with an xor-shuffle reduction inside the LPR-lane group. HBM-bound streaming.
+//
+// Window rule, scalar version: pass 1 gives every window row its log-sum-exp over the group's
+// keys (one wavefront per row, lanes over keys); pass 2 gives every key the sum over rows of
+// exp(logit - lse) (one thread per key, rows broadcast). The MFMA version lives in
+// score_window_mfma.hip and is used when the layout allows it.
+#include "qp_internal.h"
+
+namespace qp {
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void score_norm_kernel(const T* __restrict__ x, int n_rows, int n_g, int h_kv,
+                                                         float sign, float* __restrict__ scores) {
+  constexpr int PER = Elem<T>::kPer16B;
+  constexpr int LPR = D / PER;  // lanes per row, power of two <= 64
+  const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+  const int row = gid / LPR, sub = gid % LPR;
+  float ss = 0.f;
+  if (row < n_rows) {
+    uint4 raw = *(const uint4*)(x + (size_t)row * D + sub * PER);
+    float v[PER];
+    widen16<T>(raw, v);
+#pragma unroll
+    for (int e = 0; e < PER; ++e) ss = fmaf(v[e], v[e], ss);
+  }
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+  if (row < n_rows && sub == 0) {
+    const int n = row / h_kv, h = row % h_kv;  // rows are (token, kv head)
+    scores[(size_t)h * n_g + n] = sign * sqrtf(ss) + 0.f;
+  }
+}
+
+void launch_score_norm(const void* x, int dtype, int n_g, int h_kv, int d, float sign, float* scores,
+                       hipStream_t s) {
+  const int n_rows = n_g * h_kv;
+  const int lpr = d / (dtype == QP_F32 ? 4 : 8);
+  const long threads = (long)n_rows * lpr;
+  dim3 grid((unsigned)((threads + 255) / 256)), block(256);
+  if (dtype == QP_F32) {
+    if (d == 64) hipLaunchKernelGGL((score_norm_kernel<float, 64>), grid, block, 0, s, (const float*)x, n_rows, n_g, h_kv, sign, scores);
+    else hipLaunchKernelGGL((score_norm_kernel<float, 128>), grid, block, 0, s, (const float*)x, n_rows, n_g, h_kv, sign, scores);
+  } else {
+    if (d == 64) hipLaunchKernelGGL((score_norm_kernel<bf16_t, 64>), grid, block, 0, s, (const bf16_t*)x, n_rows, n_g, h_kv, sign, scores);
+    else hipLaunchKernelGGL((score_norm_kernel<bf16_t, 128>), grid, block, 0, s, (const bf16_t*)x, n_rows, n_g, h_kv, sign, scores);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Window rule, scalar version.
+
+// lse2[qh][t] = log2( sum_j exp2(scale_log2 * q.k_j) ) over the group's n_g keys.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void window_rowstats_kernel(WindowArgs a, float* __restrict__ lse2) {
+  constexpr int WAVES = 4;
+  constexpr int PER = Elem<T>::kPer16B;
+  constexpr int CHUNKS = D / PER;
+  __shared__ float q_lds[WAVES][D];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int t = blockIdx.x * WAVES + wave;
+  const int qh = blockIdx.y;
+  const int h = qh / (a.h_q / a.h_kv);
+  const bool active = t < a.w;
+  if (active) {
+    const T* qrow = (const T*)a.q_win + ((size_t)t * a.h_q + qh) * D;
+    for (int c = lane; c < CHUNKS; c += 64) {
+      uint4 raw = *(const uint4*)(qrow + c * PER);
+      float tmp[PER];
+      widen16<T>(raw, tmp);
+#pragma unroll
+      for (int e = 0; e < PER; ++e) q_lds[wave][c * PER + e] = tmp[e];
+    }
+  }
+  __syncthreads();
+  if (!active) return;
+  float m = -INFINITY, l = 0.f;
+  const T* gk = (const T*)a.k + (size_t)h * D;
+  const size_t gstride = (size_t)a.h_kv * D;
+  for (int j = lane; j < a.n_g; j += 64) {
+    const T* krow = gk + (size_t)j * gstride;
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+      uint4 raw = *(const uint4*)(krow + c * PER);
+      float kv[PER];
+      widen16<T>(raw, kv);
+#pragma unroll
+      for (int e = 0; e < PER; ++e) s = fmaf(q_lds[wave][c * PER + e], kv[e], s);
+    }
+    s *= a.scale_log2;
+    if (s > m) {
+      l *= exp2f(m - s);
+      m = s;
+    }
+    l += exp2f(s - m);
+  }
+  const float mw = wave_max(m);
+  const float lw = wave_sum(l * exp2f(m - mw));
+  if (lane == 0) lse2[(size_t)qh * a.w + t] = mw + log2f(lw);
+}
+
+// scores[h][j] = sum_{qh in head group h} sum_t exp2(scale_log2 * q.k_j - lse2[qh][t]).
+template <typename T, int D>
+__global__ __launch_bounds__(64) void window_colsum_kernel(WindowArgs a, const float* __restrict__ lse2) {
+  constexpr int PER = Elem<T>::kPer16B;
+  constexpr int CHUNKS = D / PER;
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  const int h = blockIdx.y;
+  if (j >= a.n_g) return;
+  const int r = a.h_q / a.h_kv;
+  float kv[D];
+  const T* krow = (const T*)a.k + ((size_t)j * a.h_kv + h) * D;
+#pragma unroll
+  for (int c = 0; c < CHUNKS; ++c) {
+    uint4 raw = *(const uint4*)(krow + c * PER);
+    widen16<T>(raw, kv + c * PER);
+  }
+  float total = 0.f;
+  for (int qh = h * r; qh < (h + 1) * r; ++qh) {
+    for (int t = 0; t < a.w; ++t) {
+      const T* qrow = (const T*)a.q_win + ((size_t)t * a.h_q + qh) * D;  // uniform address: broadcast
+      float s = 0.f;
+#pragma unroll
+      for (int c = 0; c < CHUNKS; ++c) {
+        uint4 raw = *(const uint4*)(qrow + c * PER);
+        float qv[PER];
+        widen16<T>(raw, qv);
+#pragma unroll
+        for (int e = 0; e < PER; ++e) s = fmaf(qv[e], kv[c * PER + e], s);
+      }
+      total += exp2f(s * a.scale_log2 - lse2[(size_t)qh * a.w + t]);
+    }
+  }
+  a.scores[(size_t)h * a.n_g + j] = total;
+}
+
+size_t window_workspace_bytes(int h_q, int h_kv, int n_g, int w) {
+  (void)h_kv;
+  (void)n_g;
+  return ((size_t)h_q * w * sizeof(float) + 255) / 256 * 256;
+}
+
+template <typename T, int D>
+static void launch_window_t(const WindowArgs& a, hipStream_t s) {
+  float* lse2 = (float*)a.workspace;
+  hipLaunchKernelGGL((window_rowstats_kernel<T, D>), dim3((a.w + 3) / 4, a.h_q), dim3(256), 0, s, a, lse2);
+  hipLaunchKernelGGL((window_colsum_kernel<T, D>), dim3((a.n_g + 63) / 64, a.h_kv), dim3(64), 0, s, a, lse2);
+}
+
+void launch_score_window(const WindowArgs& a, int dtype, hipStream_t s) {
+  if (dtype == QP_F32) {
+    if (a.d == 64) launch_window_t<float, 64>(a, s);
+    else launch_window_t<float, 128>(a, s);
+  } else {
+    if (a.d == 64) launch_window_t<bf16_t, 64>(a, s);
+    else launch_window_t<bf16_t, 128>(a, s);
+  }
+}
+
+}  // namespace qp

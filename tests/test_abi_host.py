@@ -1,0 +1,84 @@
+"""Host-side checks of the C-ABI library that need no GPU: exports, host arithmetic, argument errors."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from conftest import ROOT, read_golden
+from oracle import qp_oracle as O
+from paper_2505_16175_amd import binding as B
+from paper_2505_16175_amd.workload import CONFIGS
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "qp.h")).read()
+    body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(qp_[a-z_0-9]+)\s*\(", body))
+    assert {"qp_group_attend", "qp_score_kv", "qp_topk_compact", "qp_prefill_video"} <= declared
+    handle = ctypes.CDLL(B.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(handle, name), f"{name} declared in qp.h but not exported"
+    assert declared == set(B.SIGNATURES), "binding and header disagree on the entry points"
+    assert B.version().startswith("quickprefill")
+
+
+def test_host_arithmetic_matches_oracle_and_golden():
+    for n in (1, 2, 31, 100, 2048, 4096, 8192):
+        for rho in (0.07, 0.1, 0.2, 0.25, 0.3, 0.5, 0.9, 1.0):
+            assert B.keep_count(n, rho) == O.keep_count(n, rho)
+    assert B.keep_count(0, 0.5) == 0 and B.keep_count(10, 0.0) == -1 and B.keep_count(10, 1.5) == -1
+    for name, _, _, _, total in read_golden("cache_lengths.txt"):
+        w = CONFIGS[name]
+        assert B.cache_capacity(w.n_frames, w.tokens_per_frame, w.group_frames, w.retention) == int(total)
+    assert B.cache_capacity(0, 1, 1, 0.5) == -1
+
+
+def test_argument_errors_are_caught_on_the_host():
+    lib = B.lib()
+    L = B.make_layout(28, 4, 128, "bf16")
+    fake = ctypes.c_void_p(4096)            # aligned, never dereferenced: every case fails validation first
+    cache = B.qp_cache(4096, 8192, 12288, 100, 0)
+    ref, refc = ctypes.byref(L), ctypes.byref(cache)
+    ws = ctypes.c_void_p(1 << 20)
+    # NULL / misaligned / bad sizes
+    assert lib.qp_group_attend(ref, None, fake, fake, 16, None, fake, None, None, 0, None) == B.QP_ERR_INVALID_ARG
+    assert lib.qp_group_attend(ref, ctypes.c_void_p(4098), fake, fake, 16, None, fake, None, None, 0, None) == B.QP_ERR_INVALID_ARG
+    assert lib.qp_group_attend(ref, fake, fake, fake, 0, None, fake, None, None, 0, None) == B.QP_ERR_INVALID_ARG
+    assert lib.qp_group_attend(ref, fake, fake, fake, B.QP_MAX_GROUP_TOKENS + 1, None, fake, None, None, 0, None) == B.QP_ERR_UNSUPPORTED
+    bad = B.make_layout(28, 5, 128, "bf16")
+    assert lib.qp_group_attend(ctypes.byref(bad), fake, fake, fake, 16, None, fake, None, None, 0, None) == B.QP_ERR_INVALID_ARG
+    odd = B.make_layout(28, 4, 96, "bf16")
+    assert lib.qp_group_attend(ctypes.byref(odd), fake, fake, fake, 16, None, fake, None, None, 0, None) == B.QP_ERR_UNSUPPORTED
+    # scoring: window rule without a window, unknown rule, small workspace
+    assert lib.qp_score_kv(ref, B.QP_SCORE_WINDOW_ATTN, fake, fake, 16, None, 0, fake, ws, 1 << 20, None) == B.QP_ERR_INVALID_ARG
+    assert lib.qp_score_kv(ref, 7, fake, fake, 16, None, 0, fake, ws, 1 << 20, None) == B.QP_ERR_INVALID_ARG
+    assert lib.qp_score_kv(ref, B.QP_SCORE_WINDOW_ATTN, fake, fake, 16, fake, 64, fake, ws, 16, None) == B.QP_ERR_CAPACITY
+    assert lib.qp_score_kv(ref, B.QP_SCORE_KEY_NORM_SMALL, None, fake, 16, None, 0, fake, None, 0, None) == B.QP_ERR_INVALID_ARG
+    # top-k: keep out of range, capacity overflow; the cache length must not move
+    assert lib.qp_topk_compact(ref, fake, fake, fake, 16, 0, 0, refc, None, None, 0, None) == B.QP_ERR_INVALID_ARG
+    assert lib.qp_topk_compact(ref, fake, fake, fake, 16, 17, 0, refc, None, None, 0, None) == B.QP_ERR_INVALID_ARG
+    cache.len = 95
+    assert lib.qp_topk_compact(ref, fake, fake, fake, 16, 6, 0, refc, None, None, 0, None) == B.QP_ERR_CAPACITY
+    assert cache.len == 95
+    cache.len = 0
+    # whole-video call: bad retention, cache too small, workspace too small
+    args = (fake, fake, fake, fake, 64, refc, fake)
+    assert lib.qp_prefill_video(ref, 8, 16, 2, 0.0, 0, *args, ws, 1 << 20, None) == B.QP_ERR_INVALID_ARG
+    assert lib.qp_prefill_video(ref, 8, 16, 2, 1.0, 0, *args, ws, 1 << 20, None) == B.QP_ERR_CAPACITY   # needs 128 > 100
+    assert lib.qp_prefill_video(ref, 8, 16, 2, 0.5, 2, *args, ws, 64, None) == B.QP_ERR_CAPACITY
+    assert lib.qp_prefill_video(ref, 8, 16, 2, 0.5, 2, fake, fake, fake, None, 0, refc, fake, ws, 1 << 20, None) == B.QP_ERR_INVALID_ARG
+    assert cache.len == 0
+    assert lib.qp_select_attend_kernel(9) == B.QP_ERR_INVALID_ARG
+    assert B.workspace_bytes(L, 0, 0) == 0 and B.workspace_bytes(L, 8192, 64) > 4 * 8192 * 4
+    for s in range(5):
+        assert B.status_string(s)
+
+
+def test_product_path_does_not_touch_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2505_16175_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.replace("the CPU oracle's tests", ""), f

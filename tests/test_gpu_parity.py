@@ -1,0 +1,249 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on the same seeded inputs."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from helpers import assert_attn_close, compare_kept, sample_rows
+from oracle import qp_oracle as O
+from paper_2505_16175_amd import binding as B
+from paper_2505_16175_amd.workload import CONFIGS, make_layer, scaled, to_f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _f64(t):
+    return to_f64(t)
+
+
+def _kernels_for(layout):
+    """Attention kernels to cover for a layout: the scalar one always, the MFMA one when it applies."""
+    ks = [B.QP_ATTEND_SCALAR]
+    if layout.dtype == B.QP_BF16 and layout.head_dim == 128:
+        ks.append(B.QP_ATTEND_MFMA)
+    return ks
+
+
+@pytest.fixture(autouse=True)
+def _reset_kernel_choice():
+    yield
+    B.select_attend_kernel(B.QP_ATTEND_AUTO)
+
+
+# --------------------------------------------------------------------------------------------- S1
+@pytest.mark.parametrize("dtype,h_q,h_kv,d", [("f32", 4, 2, 64), ("bf16", 28, 4, 128), ("bf16", 16, 2, 128),
+                                              ("bf16", 8, 8, 64), ("f32", 6, 2, 128)])
+@pytest.mark.parametrize("n_g,c", [(1, 0), (37, 5), (130, 0), (300, 200), (257, 1031)])
+def test_group_attend_matches_oracle(dtype, h_q, h_kv, d, n_g, c):
+    """Several tiles and ragged tails in both the group and the cache; sharp logits."""
+    print(f"case dtype={dtype} heads={h_q}/{h_kv} d={d} n_g={n_g} c={c}", flush=True)
+    g = torch.Generator().manual_seed(1000 * n_g + c + h_q)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    mk = lambda *s: (torch.randn(*s, generator=g) * 1.0).to(tdt)
+    q, k, v = mk(n_g, h_q, d), mk(n_g, h_kv, d), mk(n_g, h_kv, d)
+    ck, cv = mk(h_kv, c + 7, d), mk(h_kv, c + 7, d)          # capacity > len: stride is the capacity
+    want, want_lse = O.attend_group(_f64(q), _f64(k), _f64(v), _f64(ck)[:, :c], _f64(cv)[:, :c], return_lse=True)
+    layout = B.make_layout(h_q, h_kv, d, dtype)
+    cache = B.Cache(layout, c + 7)
+    cache.k.copy_(ck)
+    cache.v.copy_(cv)
+    cache.c.len = c
+    for kern in _kernels_for(layout):
+        B.select_attend_kernel(kern)
+        out = torch.full((n_g, h_q, d), float("nan"), dtype=tdt, device=DEV)
+        lse = torch.full((h_q, n_g), float("nan"), dtype=torch.float32, device=DEV)
+        B.group_attend(layout, q.to(DEV), k.to(DEV), v.to(DEV), cache if c > 0 else None, out, lse)
+        torch.cuda.synchronize()
+        assert_attn_close(_f64(out), want, dtype, f"kernel {kern}")
+        np.testing.assert_allclose(_f64(lse), want_lse, rtol=2e-5, atol=2e-5 if dtype == "f32" else 2e-4)
+        assert cache.len == c
+
+
+# --------------------------------------------------------------------------------------------- S2
+@pytest.mark.parametrize("dtype,h_kv,d", [("f32", 2, 64), ("bf16", 4, 128), ("bf16", 8, 64), ("f32", 3, 128)])
+@pytest.mark.parametrize("n_g", [1, 33, 2048, 5000])
+def test_norm_scores_match_oracle(dtype, h_kv, d, n_g):
+    print(f"case dtype={dtype} h_kv={h_kv} d={d} n_g={n_g}", flush=True)
+    g = torch.Generator().manual_seed(n_g + d)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    k = (torch.randn(n_g, h_kv, d, generator=g) * torch.exp(0.5 * torch.randn(n_g, 1, 1, generator=g))).to(tdt)
+    v = torch.randn(n_g, h_kv, d, generator=g).to(tdt)
+    k[0] = 0                                                   # a zero row: score +0.0 under both rules
+    layout = B.make_layout(h_kv * 2, h_kv, d, dtype)
+    for rule in ("key_norm_small", "value_norm"):
+        s = torch.full((h_kv, n_g), float("nan"), dtype=torch.float32, device=DEV)
+        B.score_kv(layout, rule, k.to(DEV), v.to(DEV), None, s)
+        torch.cuda.synchronize()
+        want = O.score_kv(rule, _f64(k), _f64(v))
+        np.testing.assert_allclose(_f64(s), want, rtol=1e-6, atol=0)
+    assert not np.signbit(_f64(s)[0, 0])
+
+
+@pytest.mark.parametrize("dtype,h_q,h_kv,d,w", [("f32", 4, 2, 64, 16), ("bf16", 28, 4, 128, 64), ("bf16", 16, 2, 128, 128),
+                                                ("bf16", 8, 8, 64, 5)])
+@pytest.mark.parametrize("n_g,sharp", [(32, True), (300, True), (2048, False), (1000, True)])
+def test_window_scores_match_oracle(dtype, h_q, h_kv, d, w, n_g, sharp):
+    print(f"case dtype={dtype} heads={h_q}/{h_kv} d={d} w={w} n_g={n_g} sharp={sharp}", flush=True)
+    g = torch.Generator().manual_seed(n_g + w)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    sc = 1.0 if sharp else 1.0 / math.sqrt(d)
+    k = (torch.randn(n_g, h_kv, d, generator=g) * sc).to(tdt)
+    qw = (torch.randn(w, h_q, d, generator=g) * sc).to(tdt)
+    layout = B.make_layout(h_q, h_kv, d, dtype)
+    ws = B.make_workspace(layout, n_g, w)
+    s = torch.full((h_kv, n_g), float("nan"), dtype=torch.float32, device=DEV)
+    B.score_kv(layout, "window_attn", k.to(DEV), None, qw.to(DEV), s, ws)
+    torch.cuda.synchronize()
+    want = O.score_kv("window_attn", _f64(k), None, _f64(qw))
+    got = _f64(s)
+    np.testing.assert_allclose(got, want, rtol=2e-5, atol=1e-7)
+    np.testing.assert_allclose(got.sum(axis=1), (h_q // h_kv) * w, rtol=1e-5)   # total attention mass
+
+
+# --------------------------------------------------------------------------------------------- S3 + S4
+@pytest.mark.parametrize("dtype,h_kv,d", [("bf16", 4, 128), ("f32", 2, 64)])
+@pytest.mark.parametrize("n_g,keep,ties", [(4, 2, True), (1, 1, False), (100, 100, True), (1000, 1, True),
+                                           (2048, 615, False), (8192, 820, True), (5000, 4999, False),
+                                           (32768, 20000, True), (32768, 3277, False)])
+def test_topk_compact_exact(dtype, h_kv, d, n_g, keep, ties):
+    """Same f32 scores on both sides: kept sets, positions and copied rows must be bit-exact."""
+    print(f"case dtype={dtype} h_kv={h_kv} d={d} n_g={n_g} keep={keep} ties={ties}", flush=True)
+    g = torch.Generator().manual_seed(n_g * 7 + keep)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    s = torch.randn(h_kv, n_g, generator=g)
+    if ties:
+        s = torch.round(s * 4) / 4                              # heavy ties, includes -0.0 and +0.0
+        s[0, : n_g // 2] = 0.5                                  # a long run of equal scores
+        if n_g >= 4:
+            s[-1, :] = -1.25                                    # all equal: the first `keep` tokens survive
+    k = torch.randn(n_g, h_kv, d, generator=g).to(tdt)
+    v = torch.randn(n_g, h_kv, d, generator=g).to(tdt)
+    layout = B.make_layout(h_kv, h_kv, d, dtype)
+    pre, base = 3, 77000
+    cache = B.Cache(layout, pre + keep + 5)
+    cache.c.len = pre
+    kept = torch.full((h_kv, keep), -1, dtype=torch.int32, device=DEV)
+    B.topk_compact(layout, s.to(DEV), k.to(DEV), v.to(DEV), keep, base, cache, kept)
+    torch.cuda.synchronize()
+    assert cache.len == pre + keep
+    want = O.topk_select(s.double().numpy(), keep)
+    got = kept.cpu().numpy()
+    np.testing.assert_array_equal(got, want)
+    if ties and n_g >= 4:
+        assert got[-1].tolist() == list(range(keep))
+    pos = cache.pos.cpu().numpy()
+    np.testing.assert_array_equal(pos[:, pre:pre + keep], base + want)
+    assert (pos[:, :pre] == -1).all() and (pos[:, pre + keep:] == -1).all()       # nothing else written
+    ck, cv = cache.k.cpu(), cache.v.cpu()
+    for h in range(h_kv):
+        idx = torch.from_numpy(want[h])
+        assert torch.equal(ck[h, pre:pre + keep], k[idx, h]) and torch.equal(cv[h, pre:pre + keep], v[idx, h])
+        assert (ck[h, :pre] == 0).all() and (ck[h, pre + keep:] == 0).all()
+
+
+# --------------------------------------------------------------------------------------------- whole path
+def _run_prefill(w, q, k, v, qw, rule, kernel=B.QP_ATTEND_AUTO):
+    layout = B.make_layout(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
+    cap = B.cache_capacity(w.n_frames, w.tokens_per_frame, w.group_frames, w.retention)
+    cache = B.Cache(layout, cap)
+    ws = B.make_workspace(layout, min(w.group_tokens, w.n_tokens), w.n_window if rule == "window_attn" else 0)
+    out = torch.full_like(q, float("nan"))
+    B.select_attend_kernel(kernel)
+    B.prefill_video(layout, w.n_frames, w.tokens_per_frame, w.group_frames, w.retention, rule, q, k, v,
+                    qw if rule == "window_attn" else None, cache, out, ws)
+    torch.cuda.synchronize()
+    return out, cache
+
+
+def _check_cache_against_oracle(w, k, v, qw, rule, cache):
+    """Kept sets of every group vs the oracle (near-ties counted), and the compaction as a bit-exact copy."""
+    k64, v64 = _f64(k), _f64(v)
+    sel = O.select_all_groups(k64, v64, None if qw is None else _f64(qw), w.n_frames, w.tokens_per_frame,
+                              w.group_frames, w.retention, rule)
+    assert cache.len == sum(i.shape[1] for _, _, i, _ in sel) == O.final_cache_len(
+        w.n_frames, w.tokens_per_frame, w.group_frames, w.retention)
+    pos = cache.pos.cpu().numpy()[:, :cache.len]
+    lo, near = 0, 0
+    for base, n_g, idx, s in sel:
+        kk = idx.shape[1]
+        near += compare_kept(pos[:, lo:lo + kk] - base, idx, s)
+        lo += kk
+    ck, cv = cache.k.cpu(), cache.v.cpu()
+    kc, vc = k.cpu(), v.cpu()
+    for h in range(w.n_kv_heads):
+        p = torch.from_numpy(pos[h].astype(np.int64))
+        assert torch.equal(ck[h, :cache.len], kc[p, h]) and torch.equal(cv[h, :cache.len], vc[p, h])
+    return sel, pos, near
+
+
+@pytest.mark.parametrize("sharp", [False, True])
+@pytest.mark.parametrize("rule", ["key_norm_small", "window_attn", "value_norm"])
+def test_cfg1_tiny_whole_path(rule, sharp):
+    w = CONFIGS["cfg1_tiny_f32"]
+    print(f"case cfg1 rule={rule} sharp={sharp}", flush=True)
+    q, k, v, qw = make_layer(w, sharp=sharp)
+    want, wck, wcv, wpos, _ = O.prefill_video(_f64(q), _f64(k), _f64(v), _f64(qw), w.n_frames, w.tokens_per_frame,
+                                              w.group_frames, w.retention, rule)
+    out, cache = _run_prefill(w, q.to(DEV), k.to(DEV), v.to(DEV), qw.to(DEV), rule)
+    _, pos, near = _check_cache_against_oracle(w, k, v, qw, rule, cache)
+    assert cache.len == 64
+    if near == 0:
+        np.testing.assert_array_equal(pos, wpos)
+        assert_attn_close(_f64(out), want, "f32", "cfg1")
+
+
+@pytest.mark.parametrize("name,frames,tokens_per_frame,group_frames", [
+    ("cfg2_7b_32k", 12, 40, 5),          # ragged: last group 2 frames, group tokens 200 (not a tile multiple)
+    ("cfg4_72b_128k", 6, 96, 2),
+    ("cfg3_7b_128k_norm", 9, 64, 4),
+])
+@pytest.mark.parametrize("sharp", [False, True])
+def test_reduced_configs_whole_path_full_oracle(name, frames, tokens_per_frame, group_frames, sharp):
+    """The benchmark layer shapes at reduced length: every output element against the full oracle."""
+    w = scaled(CONFIGS[name], n_frames=frames, tokens_per_frame=tokens_per_frame, group_frames=group_frames)
+    for rule in w.rules:
+        q, k, v, qw = make_layer(w, sharp=sharp)
+        want, *_ = O.prefill_video(_f64(q), _f64(k), _f64(v), None if qw is None else _f64(qw), w.n_frames,
+                                   w.tokens_per_frame, w.group_frames, w.retention, rule)
+        dq, dk, dv = q.to(DEV), k.to(DEV), v.to(DEV)
+        dqw = None if qw is None else qw.to(DEV)
+        layout = B.make_layout(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
+        for kern in _kernels_for(layout):
+            print(f"case {name} reduced rule={rule} sharp={sharp} kernel={kern}", flush=True)
+            out, cache = _run_prefill(w, dq, dk, dv, dqw, rule, kern)
+            _, _, near = _check_cache_against_oracle(w, k, v, qw, rule, cache)
+            if near == 0:                 # a near-tie changes the cache, hence later outputs
+                assert_attn_close(_f64(out), want, w.dtype, f"{name} kernel {kern}")
+
+
+def _full_size_check(w, rule, sharp, n_rows, layer=0):
+    """Full-size run; kept sets of all groups and sampled attention rows against the oracle."""
+    q, k, v, qw = make_layer(w, layer=layer, device=DEV, sharp=sharp)
+    out, cache = _run_prefill(w, q, k, v, qw, rule)
+    sel, pos, near = _check_cache_against_oracle(w, k, v, qw, rule, cache)
+    rng = np.random.default_rng(5)
+    bounds = w.group_bounds()
+    groups = sorted({0, 1, len(bounds) // 2, len(bounds) - 1})
+    k64, v64 = _f64(k), _f64(v)
+    stats = []
+    for gi in groups:
+        base, n_g = bounds[gi]
+        rows = sample_rows(n_g, n_rows, rng)
+        sl = slice(base, base + n_g)
+        ck, cv, _ = O.gather_cache(k64, v64, sel, gi)          # the oracle's own cache before group gi
+        want = O.attend_group(_f64(q[sl]), k64[sl], v64[sl], ck, cv, rows=rows)
+        got = _f64(out[sl][rows])
+        stats.append(assert_attn_close(got, want, w.dtype, f"{w.name} group {gi}"))
+    return near, stats, cache
+
+
+def test_cfg2_full_size():
+    w = CONFIGS["cfg2_7b_32k"]
+    for sharp in (False, True):
+        print(f"case cfg2 full size sharp={sharp}", flush=True)
+        near, stats, cache = _full_size_check(w, "window_attn", sharp, 24)
+        print(f"  near-tie heads excused: {near}; max abs err {max(s['max_abs'] for s in stats):.3e}; "
+              f"max normalised err {max(s['nrm'] for s in stats):.3e}", flush=True)
+        assert cache.len == 9840
