@@ -101,6 +101,9 @@ struct WindowArgs {
 };
 size_t window_workspace_bytes(int h_q, int h_kv, int n_g, int w);
 void launch_score_window(const WindowArgs& a, int dtype, hipStream_t s);
+bool window_mfma_supported(int dtype, int h_q, int h_kv, int d, int w);
+size_t window_mfma_workspace_bytes(int h_q, int h_kv, int n_g, int w);
+void launch_score_window_mfma(const WindowArgs& a, hipStream_t s);
 
 struct TopkArgs {
   const float* scores;  // [h_kv][n_g]

@@ -12,7 +12,7 @@
 // Window rule, scalar version: pass 1 gives every window row its log-sum-exp over the group's
 // keys (one wavefront per row, lanes over keys); pass 2 gives every key the sum over rows of
 // exp(logit - lse) (one thread per key, rows broadcast). The MFMA version lives in
-// score_window_mfma.hip and is used when the layout allows it.
+// score_window_mfma.hip and is used when the layout allows it (bf16, head_dim 128).
 #include "qp_internal.h"
 
 namespace qp {
@@ -144,9 +144,9 @@ __global__ __launch_bounds__(64) void window_colsum_kernel(WindowArgs a, const f
 }
 
 size_t window_workspace_bytes(int h_q, int h_kv, int n_g, int w) {
-  (void)h_kv;
-  (void)n_g;
-  return ((size_t)h_q * w * sizeof(float) + 255) / 256 * 256;
+  const size_t scalar = (size_t)h_q * w * sizeof(float);
+  const size_t mfma = window_mfma_workspace_bytes(h_q, h_kv, n_g, w);
+  return ((scalar > mfma ? scalar : mfma) + 255) / 256 * 256;
 }
 
 template <typename T, int D>
@@ -157,6 +157,10 @@ static void launch_window_t(const WindowArgs& a, hipStream_t s) {
 }
 
 void launch_score_window(const WindowArgs& a, int dtype, hipStream_t s) {
+  if (window_mfma_supported(dtype, a.h_q, a.h_kv, a.d, a.w)) {
+    launch_score_window_mfma(a, s);
+    return;
+  }
   if (dtype == QP_F32) {
     if (a.d == 64) launch_window_t<float, 64>(a, s);
     else launch_window_t<float, 128>(a, s);
