@@ -57,7 +57,8 @@ def test_group_attend_matches_oracle(dtype, h_q, h_kv, d, n_g, c):
         B.group_attend(layout, q.to(DEV), k.to(DEV), v.to(DEV), cache if c > 0 else None, out, lse)
         torch.cuda.synchronize()
         assert_attn_close(_f64(out), want, dtype, f"kernel {kern}")
-        np.testing.assert_allclose(_f64(lse), want_lse, rtol=2e-5, atol=2e-5 if dtype == "f32" else 2e-4)
+        # bf16 MFMA kernel: the denominator is summed over bf16-rounded numerators (relative 2^-9 each)
+        np.testing.assert_allclose(_f64(lse), want_lse, rtol=2e-5, atol=2e-5 if dtype == "f32" else 2e-3)
         assert cache.len == c
 
 
