@@ -419,7 +419,9 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_v3_kernel(AttendArgs a) 
 
   for (int tile = 0; tile < n_tiles; ++tile) {
     const int buf = tile & 1;
+#if !(defined(QP_ABLATE) && (QP_ABLATE & 8))
     if (tile + 1 < n_tiles) QP_V3_ISSUE(tile + 1, buf ^ 1)
+#endif
     // visibility inside this tile: key_local <= lim_local
     const bool in_cache = tile < n_ct;
     const int gt0 = (tile - n_ct) * MF_BN;  // first group token of a group tile
@@ -436,7 +438,13 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_v3_kernel(AttendArgs a) 
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int s = 0; s < 8; ++s) kf[kb][s] = *(const u32x4*)(kt + kb * 32 * 256 + k_addr[s]);
+          for (int s = 0; s < 8; ++s) {
+#if defined(QP_ABLATE) && (QP_ABLATE & 2)
+            kf[kb][s] = __builtin_bit_cast(u32x4, qf[(s + kb) & 7]);
+#else
+            kf[kb][s] = *(const u32x4*)(kt + kb * 32 * 256 + k_addr[s]);
+#endif
+          }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -445,11 +453,21 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_v3_kernel(AttendArgs a) 
 #pragma unroll
         for (int s = 0; s < 8; ++s)
 #pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
+          for (int kb = 0; kb < 2; ++kb) {
+#if defined(QP_ABLATE) && (QP_ABLATE & 64)
+            st[kb][s] += __builtin_bit_cast(float, kf[kb][s][0]);
+#else
             st[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[kb][s]), qf[s], st[kb], 0, 0, 0);
+#endif
+          }
         __builtin_amdgcn_sched_barrier(0);
       }
       // ---- softmax
+#if defined(QP_ABLATE) && (QP_ABLATE & 32)
+      bf16x8 pf[4];
+      for (int i = 0; i < 4; ++i) { u32x4 t_ = __builtin_bit_cast(u32x4, qf[i]); t_[0] ^= __builtin_bit_cast(unsigned, st[i & 1][i]); t_[1] ^= __builtin_bit_cast(unsigned, st[i & 1][i + 4]); t_[2] ^= __builtin_bit_cast(unsigned, st[i & 1][i + 8]); t_[3] ^= __builtin_bit_cast(unsigned, st[i & 1][i + 12]); pf[i] = __builtin_bit_cast(bf16x8, t_); }
+      (void)lim_local; (void)need_mask; (void)lazy; (void)ones;
+#else
       if (need_mask) {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -473,8 +491,13 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_v3_kernel(AttendArgs a) 
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
           bf16x2 pr;
+#if defined(QP_ABLATE) && (QP_ABLATE & 1)
+          pr[0] = (__bf16)(fmaf(st[kb][r], c2, -mc));
+          pr[1] = (__bf16)(fmaf(st[kb][r + 1], c2, -mc));
+#else
           pr[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(st[kb][r], c2, -mc));
           pr[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(st[kb][r + 1], c2, -mc));
+#endif
           psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
           pf[kb * 2 + (r >> 3)][r & 7] = pr[0];
           pf[kb * 2 + (r >> 3)][(r & 7) + 1] = pr[1];
@@ -489,21 +512,30 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_v3_kernel(AttendArgs a) 
         m_run = m_new;
       }
       l_run += psum;
+#endif
       // ---- O^T += V^T . P^T
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
 #pragma unroll
         for (int n = 0; n < 4; ++n) {
+#if defined(QP_ABLATE) && (QP_ABLATE & 128)
+          o[n][ks] += (float)pf[ks][n];
+#elif defined(QP_ABLATE) && (QP_ABLATE & 4)
+          o[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[(ks + n) & 3], pf[ks], o[n], 0, 0, 0);
+#else
           const unsigned char* p0 = vt + ks * 16 * 256 + v_addr[n];
           s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p0));
           s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p0 + 8 * 256));
           const s16x8 cat = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           o[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, cat), pf[ks], o[n], 0, 0, 0);
+#endif
         }
       }
     }
+#if !(defined(QP_ABLATE) && (QP_ABLATE & 16))
     __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's part of the next tile has landed in LDS
     __syncthreads();
+#endif
   }
 #undef QP_V3_ISSUE
 
@@ -523,13 +555,17 @@ void launch_attend_mfma(const AttendArgs& a, hipStream_t s) {
   static int variant = -1;
   if (variant < 0) {
     const char* e = getenv("QP_MFMA_VARIANT");
-    variant = e ? atoi(e) : 0;
+    variant = e ? atoi(e) : 3;
     (void)hipFuncSetAttribute((const void*)attend_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                               2 * (MF_KBYTES + MF_VBYTES));
     (void)hipFuncSetAttribute((const void*)attend_mfma_v3_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, V3_LDS);
   }
   const int n_rows = a.n_g * (a.h_q / a.h_kv);
   const int n_rb = (n_rows + MF_BM - 1) / MF_BM;
+  if (variant == 4) {
+    launch_attend_mfma64(a, s);
+    return;
+  }
   if (variant == 3)
     hipLaunchKernelGGL(attend_mfma_v3_kernel, dim3(n_rb, a.h_kv), dim3(MF_NT), V3_LDS, s, a);
   else
