@@ -20,8 +20,8 @@
  *   - The library allocates nothing and keeps no pointer after a call returns; scratch
  *     memory is the caller's `workspace` (size from qp_workspace_bytes, 256-byte aligned).
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the
- *     default stream). No call synchronises with the host or reads anything back:
- *     `cache->len` is host arithmetic and is already updated when a call returns, while
+ *     default stream), or ordered with respect to it (see qp_prefill_video). No call
+ *     synchronises with the host or reads anything back: `cache->len` is host arithmetic and is already updated when a call returns, while
  *     the copies it describes may still be in flight on the stream.
  *   - Errors are returned as qp_status; nothing throws or aborts. Argument errors are
  *     detected on the host before anything is launched and leave `cache` untouched.
@@ -145,7 +145,11 @@ qp_status qp_topk_compact(const qp_layout* layout, const float* scores, const vo
  *   cache: appended starting at cache->len (normally 0); entries already in it are visible
  *     to every group. Needs capacity >= len + qp_cache_capacity(...).
  *   out [N][H_q][d]
- * All arguments are validated before the first launch. */
+ * All arguments are validated before the first launch. Scoring and compaction of a group do not
+ * depend on its attention, so they are enqueued on a second, library-owned stream (created on
+ * first use, default priority) that is forked from hip_stream at entry and joined back into it
+ * before the call returns: work the caller enqueues on hip_stream afterwards is ordered after
+ * all of this call's work. */
 qp_status qp_prefill_video(const qp_layout* layout, int32_t n_frames, int32_t tokens_per_frame,
                            int32_t group_frames, double retention, qp_score_rule rule, const void* q,
                            const void* k, const void* v, const void* q_win, int32_t n_window, qp_cache* cache,

@@ -55,6 +55,28 @@ qp_status finish(hipError_t launch_err) {
   return QP_OK;
 }
 
+// Second stream of qp_prefill_video: scoring and top-k/compaction of a group depend only on the
+// group's K/V (and the query window), never on its attention, so they run beside the group's
+// attention kernel. Created once per process, default priority, joined back before the call returns
+// control of the ordering to the caller's stream.
+struct SideStream {
+  hipStream_t stream = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+  bool tried = false, ok = false;
+};
+SideStream g_side;
+
+bool side_stream_ready() {
+  if (!g_side.tried) {
+    g_side.tried = true;
+    g_side.ok = hipStreamCreateWithFlags(&g_side.stream, hipStreamNonBlocking) == hipSuccess &&
+                hipEventCreateWithFlags(&g_side.fork, hipEventDisableTiming) == hipSuccess &&
+                hipEventCreateWithFlags(&g_side.join, hipEventDisableTiming) == hipSuccess;
+    if (!g_side.ok) (void)hipGetLastError();
+  }
+  return g_side.ok;
+}
+
 // Workspace layout: [scores H_kv*n_g f32][window scratch].
 size_t scores_bytes(const qp_layout* L, int32_t n_g) { return round256((size_t)L->n_kv_heads * n_g * sizeof(float)); }
 
@@ -252,6 +274,14 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
   void* ws2 = (char*)workspace + sb;
   const size_t ws2_bytes = workspace_bytes - sb;
 
+  hipStream_t main_stream = (hipStream_t)hip_stream;
+  const bool overlap = side_stream_ready();
+  void* score_stream = overlap ? (void*)g_side.stream : hip_stream;
+  if (overlap) {
+    if (hipEventRecord(g_side.fork, main_stream) != hipSuccess || hipStreamWaitEvent(g_side.stream, g_side.fork, 0) != hipSuccess)
+      return finish(hipGetLastError());
+  }
+  bool pending_join = false;
   for (int32_t f = 0; f < n_frames; f += group_frames) {
     const int32_t g = (n_frames - f) < group_frames ? (n_frames - f) : group_frames;
     const int32_t base = f * tokens_per_frame, n_g = g * tokens_per_frame;
@@ -259,18 +289,28 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
     const char* kg = (const char*)k + (size_t)base * kv_tok;
     const char* vg = (const char*)v + (size_t)base * kv_tok;
     char* og = (char*)out + (size_t)base * q_tok;
-    // 1. attend to the pruned cache so far + the group itself
+    // 1. attend to the pruned cache so far (complete once the previous group's compaction is) + the group itself
+    if (pending_join && hipStreamWaitEvent(main_stream, g_side.join, 0) != hipSuccess) return finish(hipGetLastError());
     st = qp_group_attend(L, qg, kg, vg, n_g, cache, og, nullptr, ws2, ws2_bytes, hip_stream);
-    if (st != QP_OK) return st;
-    // 2. score the group's new KV entries
-    st = qp_score_kv(L, rule, kg, vg, n_g, q_win, n_window, scores, ws2, ws2_bytes, hip_stream);
-    if (st != QP_OK) return st;
-    // 3. TopK + compaction into the cache (cache->len advances on the host)
+    if (st != QP_OK) break;
+    // 2. score the group's new KV entries; 3. TopK + compaction into the cache (cache->len advances on the host).
+    //    The appended rows [len, len+k) are disjoint from the rows [0, len) the attention kernel is reading.
+    st = qp_score_kv(L, rule, kg, vg, n_g, q_win, n_window, scores, ws2, ws2_bytes, score_stream);
+    if (st != QP_OK) break;
     st = qp_topk_compact(L, scores, kg, vg, n_g, (int32_t)qp_keep_count(n_g, retention), base, cache, nullptr, ws2,
-                         ws2_bytes, hip_stream);
-    if (st != QP_OK) return st;
+                         ws2_bytes, score_stream);
+    if (st != QP_OK) break;
+    if (overlap) {
+      if (hipEventRecord(g_side.join, g_side.stream) != hipSuccess) return finish(hipGetLastError());
+      pending_join = true;
+    }
   }
-  return QP_OK;
+  // everything enqueued on the second stream is ordered before whatever the caller enqueues next
+  if (overlap) {
+    if (!pending_join) (void)hipEventRecord(g_side.join, g_side.stream);
+    if (hipStreamWaitEvent(main_stream, g_side.join, 0) != hipSuccess) return finish(hipGetLastError());
+  }
+  return st;
 }
 
 const char* qp_status_string(qp_status s) {
