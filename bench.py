@@ -28,6 +28,12 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
+# HBM bytes per launch of the attention kernel (FETCH_SIZE + WRITE_SIZE of rocprofv3 --pmc, averaged over
+# the launches of this benchmark and scaled by the same counters' reading on the calibration copy below);
+# figures and commands are in profiles/.
+MEASURED_TRAFFIC = {"cfg2_7b_32k": 136.9e6}
+CAL_COPY_BYTES = 256 << 20
+
 
 def attend_flops(w, c, n_g):
     """Useful flops of one group-attention launch: QK^T and PV over visible (row, key) pairs only."""
@@ -167,8 +173,9 @@ def main():
         tb += topk_bytes(w, n_g, keep)
     n_launch = len(ev)
     achieved = fl / t_att / 1e12
-    roofline = {"kernel": "attend_mfma_kernel (qp_group_attend)", "bound": "mfma", "achieved": achieved,
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+    roofline = {"kernel": "attend_mfma_v3_kernel (qp_group_attend)", "bound": "mfma", "achieved": achieved,
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                "traffic": MEASURED_TRAFFIC.get(w.name),
                 "launches": n_launch, "avg_launch_us": t_att / n_launch * 1e6,
                 "flops_per_launch_avg": fl / n_launch}
     if w.dtype == "f32":
@@ -197,6 +204,11 @@ def main():
                    "cache_bytes": cache.nbytes()},
         "roofline": roofline, "stages": stages,
     }
+    # calibration copy for the HBM counters: a plain device-to-device copy of known size (outside all timing)
+    cal_src = torch.empty(CAL_COPY_BYTES // 4, dtype=torch.float32, device="cuda").normal_()
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, q, k, v, qwin, rule)
     print(json.dumps(result))
