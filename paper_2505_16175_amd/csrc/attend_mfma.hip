@@ -316,28 +316,67 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
 //   * The keys are walked as two segments, cache tiles first and then group tiles starting at group
 //     token 0, so a tile never straddles the two sources and a tile's row addresses are
 //     base + lane-constant (the cache's last tile and the group's diagonal tiles are masked).
+//   * Tiles sit in a ring of three LDS buffers and are requested two tiles ahead, so a tile has two
+//     tile-times to arrive from L2 / HBM before a wavefront waits for it.
+//   * Workgroup ids are mapped so that the workgroups of one KV head run on the same XCDs (ids are
+//     dealt round-robin over the 8 XCDs, each with its own L2): with 4 KV heads, XCDs 2h and 2h+1
+//     serve head h, so every L2 streams one head's K/V instead of all of them.
 //   * The running max is only moved when some row's max grew by more than 2^8 (the softmax
 //     numerators stay below 2^8, harmless in f32/bf16), so O^T is rescaled a few times per row
 //     instead of once per tile on slowly growing maxima.
 //   * The row sum is taken over the bf16-rounded numerators with v_dot2c_f32_bf16 (two per
 //     instruction).
 constexpr int V3_TILE_BYTES = MF_BN * 256;          // one K or V tile, unpadded
-constexpr int V3_LDS = 2 * 2 * V3_TILE_BYTES;        // double-buffered K and V
+constexpr int V3_STAGES = 3;                         // ring of K+V tile buffers, fetched two tiles ahead
+constexpr int V3_LDS = V3_STAGES * 2 * V3_TILE_BYTES;
 constexpr float V3_RESCALE_LOG2 = 8.f;
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void glb_void;
 
+// 64 lanes x 16 bytes global -> LDS without passing through registers: lane L's chunk lands at
+// lds_dst + 16 L (lds_dst must be wave-uniform). Written as inline assembly so that the compiler does not
+// treat it as an LDS store it must wait for (vmcnt(0)) before every later LDS read; the kernel waits for
+// these loads itself (s_waitcnt vmcnt) before the barrier that publishes a tile.
+__device__ __forceinline__ void lds_dma16(const unsigned char* base, unsigned byte_off, unsigned char* lds_dst) {
+  const unsigned lds_addr =
+      __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds_dst);
+  asm volatile(
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, %1"
+      :
+      : "v"(byte_off), "s"(base), "s"(lds_addr)
+      : "memory");
+}
+
 __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_v3_kernel(AttendArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, g = lane >> 5;
   const int r_heads = a.h_q / a.h_kv;
-  const int h = blockIdx.y;
   const int n_rows = a.n_g * r_heads;
   const int n_rb = (n_rows + MF_BM - 1) / MF_BM;
-  const int rb = n_rb - 1 - (int)blockIdx.x;  // heaviest (latest tokens) first
+  // workgroup id -> (KV head, row block): ids go round-robin over the 8 XCDs
+  int h, rbi;
+  {
+    const int wg = blockIdx.x, xcd = wg & 7, idx = wg >> 3;
+    if (8 % a.h_kv == 0) {
+      const int per = 8 / a.h_kv;  // XCDs per KV head
+      h = xcd / per;
+      rbi = idx * per + (xcd % per);
+    } else if (a.h_kv % 8 == 0) {
+      const int hp = a.h_kv / 8;  // KV heads per XCD
+      h = (idx % hp) * 8 + xcd;
+      rbi = idx / hp;
+    } else {
+      h = wg % a.h_kv;
+      rbi = wg / a.h_kv;
+    }
+  }
+  if (rbi >= n_rb) return;  // padding workgroups of the XCD mapping (whole workgroup, before any barrier)
+  const int rb = n_rb - 1 - rbi;  // heaviest (latest tokens) first
   const int row0_wg = rb * MF_BM;
   const int row0 = row0_wg + wave * 32;
   const int row = row0 + l32;
@@ -383,10 +422,10 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_v3_kernel(AttendArgs a) 
     const unsigned r1_ = __umul24((unsigned)min(base_ + st_key1, last_), stride_);                            \
     unsigned char* kdst_ = smem + (buf_) * (2 * V3_TILE_BYTES) + st_lds;                                      \
     unsigned char* vdst_ = kdst_ + V3_TILE_BYTES;                                                             \
-    __builtin_amdgcn_global_load_lds((glb_void*)(ksrc_ + (r0_ + st_kc0)), (lds_void*)kdst_, 16, 0, 0);        \
-    __builtin_amdgcn_global_load_lds((glb_void*)(ksrc_ + (r1_ + st_kc1)), (lds_void*)(kdst_ + 1024), 16, 0, 0); \
-    __builtin_amdgcn_global_load_lds((glb_void*)(vsrc_ + (r0_ + st_vc0)), (lds_void*)vdst_, 16, 0, 0);        \
-    __builtin_amdgcn_global_load_lds((glb_void*)(vsrc_ + (r1_ + st_vc1)), (lds_void*)(vdst_ + 1024), 16, 0, 0); \
+    lds_dma16(ksrc_, r0_ + st_kc0, kdst_);                                                                    \
+    lds_dma16(ksrc_, r1_ + st_kc1, kdst_ + 1024);                                                             \
+    lds_dma16(vsrc_, r0_ + st_vc0, vdst_);                                                                    \
+    lds_dma16(vsrc_, r1_ + st_vc1, vdst_ + 1024);                                                             \
   }
 
   // fragment read addresses (bytes inside a tile)
@@ -413,14 +452,25 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_v3_kernel(AttendArgs a) 
   ones[0] = (__bf16)1.0f;
   ones[1] = (__bf16)1.0f;
 
-  QP_V3_ISSUE(0, 0)
+  // The Q fragments must have arrived before the first tile request: from here on the only vector-memory
+  // operations in flight are the tile requests, which the compiler does not see (it would otherwise
+  // re-wait for "pending" Q loads inside the loop and drain the tile requests with them).
   __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+  // each wavefront has 4 loads in flight per requested tile; vmcnt(4) = everything but the newest tile has landed
+  QP_V3_ISSUE(0, 0)
+  if (n_tiles > 1) {
+    QP_V3_ISSUE(1, 1)
+    __builtin_amdgcn_s_waitcnt(0x0f74);  // vmcnt(4)
+  } else {
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+  }
   __syncthreads();
 
+  int buf = 0, buf_next2 = 2;  // ring positions of tile and tile + 2
   for (int tile = 0; tile < n_tiles; ++tile) {
-    const int buf = tile & 1;
 #if !(defined(QP_ABLATE) && (QP_ABLATE & 8))
-    if (tile + 1 < n_tiles) QP_V3_ISSUE(tile + 1, buf ^ 1)
+    // buffer of tile+2 = buffer of tile-1: every wavefront finished reading it before the last barrier
+    if (tile + 2 < n_tiles) QP_V3_ISSUE(tile + 2, buf_next2)
 #endif
     // visibility inside this tile: key_local <= lim_local
     const bool in_cache = tile < n_ct;
@@ -533,9 +583,13 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_v3_kernel(AttendArgs a) 
       }
     }
 #if !(defined(QP_ABLATE) && (QP_ABLATE & 16))
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's part of the next tile has landed in LDS
+    // this wavefront's part of the next tile has landed in LDS (the tile after it may still be in flight)
+    if (tile + 2 < n_tiles) __builtin_amdgcn_s_waitcnt(0x0f74);  // vmcnt(4)
+    else __builtin_amdgcn_s_waitcnt(0x0f70);                     // vmcnt(0)
     __syncthreads();
 #endif
+    buf = buf == V3_STAGES - 1 ? 0 : buf + 1;
+    buf_next2 = buf_next2 == V3_STAGES - 1 ? 0 : buf_next2 + 1;
   }
 #undef QP_V3_ISSUE
 
@@ -566,8 +620,14 @@ void launch_attend_mfma(const AttendArgs& a, hipStream_t s) {
     launch_attend_mfma64(a, s);
     return;
   }
-  if (variant == 3)
-    hipLaunchKernelGGL(attend_mfma_v3_kernel, dim3(n_rb, a.h_kv), dim3(MF_NT), V3_LDS, s, a);
+  if (variant == 3) {
+    int n_wg = n_rb * a.h_kv;
+    if (8 % a.h_kv == 0) {
+      const int per = 8 / a.h_kv;
+      n_wg = (n_rb + per - 1) / per * 8;
+    }
+    hipLaunchKernelGGL(attend_mfma_v3_kernel, dim3(n_wg), dim3(MF_NT), V3_LDS, s, a);
+  }
   else
     hipLaunchKernelGGL(attend_mfma_kernel, dim3(n_rb, a.h_kv), dim3(MF_NT), 2 * (MF_KBYTES + MF_VBYTES), s, a);
 }
