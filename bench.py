@@ -53,6 +53,51 @@ def topk_bytes(w, n_g, keep):
     return w.n_kv_heads * (n_g * 4 + keep * 4 + 2 * 2 * keep * w.head_dim * esz)
 
 
+def characterise_hbm(torch, B, reps=6):
+    """HBM-bound steps at a bandwidth-characterisation shape: the layers of the hour-long stack folded into
+    the head axis (28 x 4 = 112 KV heads x 8192 tokens x 128, bf16), inputs rotated over three buffers
+    (3 x 235 MB > the 256 MB Infinity Cache) so that the bytes come from HBM."""
+    h, n_g, d, keep = 112, 8192, 128, 820
+    layout = B.make_layout(h, h, d, "bf16")
+    ks = [torch.randn(n_g, h, d, device="cuda", dtype=torch.bfloat16) for _ in range(3)]
+    vs = [torch.randn(n_g, h, d, device="cuda", dtype=torch.bfloat16) for _ in range(3)]
+    scores = torch.empty(h, n_g, dtype=torch.float32, device="cuda")
+    cache = B.Cache(layout, keep)
+    out = {}
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    # key-norm scores: read K once, write H*N_g floats
+    for i in range(3):
+        B.score_kv(layout, "key_norm_small", ks[i], None, None, scores)
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    e0.record()
+    for i in range(reps):
+        B.score_kv(layout, "key_norm_small", ks[i % 3], None, None, scores)
+    e1.record()
+    torch.cuda.synchronize()
+    t = e0.elapsed_time(e1) * 1e-3 / reps
+    nbytes = h * n_g * d * 2 + h * n_g * 4
+    out["score_norm"] = {"shape": f"{h} heads x {n_g} tokens x {d} bf16", "bytes": nbytes, "us": t * 1e6,
+                         "GBps": nbytes / t / 1e9, "frac_of_hbm_peak": nbytes / t / 1e9 / PEAK_HBM_GBS}
+    # top-k + compaction: read the scores, gather keep rows of K and V, write them + pos
+    for i in range(3):
+        cache.reset()
+        B.topk_compact(layout, scores, ks[i], vs[i], keep, 0, cache)
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    e0.record()
+    for i in range(reps):
+        cache.reset()
+        B.topk_compact(layout, scores, ks[i % 3], vs[i % 3], keep, 0, cache)
+    e1.record()
+    torch.cuda.synchronize()
+    t = e0.elapsed_time(e1) * 1e-3 / reps
+    nbytes = h * (n_g * 4 + keep * 4 + 2 * 2 * keep * d * 2)
+    out["topk_compact"] = {"shape": f"{h} heads x {n_g} tokens, keep {keep}", "bytes": nbytes, "us": t * 1e6,
+                           "GBps": nbytes / t / 1e9, "frac_of_hbm_peak": nbytes / t / 1e9 / PEAK_HBM_GBS}
+    return out
+
+
 def cpu_baseline(w, q, k, v, qw, rule):
     """The oracle on the host: all groups scored and selected, a sample of groups attended in full."""
     import numpy as np  # noqa: F401
@@ -173,7 +218,7 @@ def main():
         tb += topk_bytes(w, n_g, keep)
     n_launch = len(ev)
     achieved = fl / t_att / 1e12
-    roofline = {"kernel": "attend_mfma_v3_kernel (qp_group_attend)", "bound": "mfma", "achieved": achieved,
+    roofline = {"kernel": "attend_mfma_kernel (qp_group_attend)", "bound": "mfma", "achieved": achieved,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                 "traffic": MEASURED_TRAFFIC.get(w.name),
                 "launches": n_launch, "avg_launch_us": t_att / n_launch * 1e6,
@@ -209,6 +254,7 @@ def main():
     cal_dst = torch.empty_like(cal_src)
     cal_dst.copy_(cal_src)
     torch.cuda.synchronize()
+    result["stages"]["hbm_characterisation"] = characterise_hbm(torch, B)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, q, k, v, qwin, rule)
     print(json.dumps(result))

@@ -88,7 +88,6 @@ struct AttendArgs {
 void launch_attend_scalar(const AttendArgs& a, int dtype, hipStream_t s);
 bool attend_mfma_supported(const AttendArgs& a, int dtype);
 void launch_attend_mfma(const AttendArgs& a, hipStream_t s);
-void launch_attend_mfma64(const AttendArgs& a, hipStream_t s);
 
 void launch_score_norm(const void* x, int dtype, int n_g, int h_kv, int d, float sign, float* scores, hipStream_t s);
 

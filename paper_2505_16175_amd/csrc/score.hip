@@ -7,7 +7,8 @@
 //
 // Norms: a row of d elements is 256 bytes (bf16 d=128, f32 d=64) or a multiple of 16 bytes in
 // general; LPR = row bytes / 16 lanes load one 16-byte chunk each, square-accumulate in f32 and
-// finish with an xor-shuffle reduction inside the LPR-lane group. HBM-bound streaming.
+// finish with an xor-shuffle reduction inside the LPR-lane group; every lane keeps four rows' loads in
+// flight. HBM-bound streaming.
 //
 // Window rule, scalar version: pass 1 gives every window row its log-sum-exp over the group's
 // keys (one wavefront per row, lanes over keys); pass 2 gives every key the sum over rows of
@@ -17,26 +18,38 @@
 
 namespace qp {
 
+constexpr int NORM_UNROLL = 4;  // rows in flight per lane group: four independent 16-byte loads per lane
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void score_norm_kernel(const T* __restrict__ x, int n_rows, int n_g, int h_kv,
                                                          float sign, float* __restrict__ scores) {
   constexpr int PER = Elem<T>::kPer16B;
   constexpr int LPR = D / PER;  // lanes per row, power of two <= 64
   const int gid = blockIdx.x * blockDim.x + threadIdx.x;
-  const int row = gid / LPR, sub = gid % LPR;
-  float ss = 0.f;
-  if (row < n_rows) {
-    uint4 raw = *(const uint4*)(x + (size_t)row * D + sub * PER);
-    float v[PER];
-    widen16<T>(raw, v);
+  const int sub = gid % LPR;
+  const int groups = (gridDim.x * blockDim.x) / LPR;  // lane groups in the grid
+  for (int row0 = gid / LPR; row0 < n_rows; row0 += groups * NORM_UNROLL) {
+    uint4 raw[NORM_UNROLL];
 #pragma unroll
-    for (int e = 0; e < PER; ++e) ss = fmaf(v[e], v[e], ss);
-  }
+    for (int u = 0; u < NORM_UNROLL; ++u) {
+      const int row = row0 + u * groups;
+      raw[u] = row < n_rows ? *(const uint4*)(x + (size_t)row * D + sub * PER) : make_uint4(0, 0, 0, 0);
+    }
 #pragma unroll
-  for (int o = LPR / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
-  if (row < n_rows && sub == 0) {
-    const int n = row / h_kv, h = row % h_kv;  // rows are (token, kv head)
-    scores[(size_t)h * n_g + n] = sign * sqrtf(ss) + 0.f;
+    for (int u = 0; u < NORM_UNROLL; ++u) {
+      const int row = row0 + u * groups;
+      float v[PER];
+      widen16<T>(raw[u], v);
+      float ss = 0.f;
+#pragma unroll
+      for (int e = 0; e < PER; ++e) ss = fmaf(v[e], v[e], ss);
+#pragma unroll
+      for (int o = LPR / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+      if (row < n_rows && sub == 0) {
+        const int n = row / h_kv, h = row - n * h_kv;  // rows are (token, kv head)
+        scores[(size_t)h * n_g + n] = sign * sqrtf(ss) + 0.f;
+      }
+    }
   }
 }
 
@@ -44,8 +57,10 @@ void launch_score_norm(const void* x, int dtype, int n_g, int h_kv, int d, float
                        hipStream_t s) {
   const int n_rows = n_g * h_kv;
   const int lpr = d / (dtype == QP_F32 ? 4 : 8);
-  const long threads = (long)n_rows * lpr;
-  dim3 grid((unsigned)((threads + 255) / 256)), block(256);
+  const long threads = ((long)n_rows * lpr + NORM_UNROLL - 1) / NORM_UNROLL;
+  long wgs = (threads + 255) / 256;
+  if (wgs > 8192) wgs = 8192;  // grid-stride beyond 32 workgroups per CU
+  dim3 grid((unsigned)wgs), block(256);
   if (dtype == QP_F32) {
     if (d == 64) hipLaunchKernelGGL((score_norm_kernel<float, 64>), grid, block, 0, s, (const float*)x, n_rows, n_g, h_kv, sign, scores);
     else hipLaunchKernelGGL((score_norm_kernel<float, 128>), grid, block, 0, s, (const float*)x, n_rows, n_g, h_kv, sign, scores);

@@ -6,8 +6,8 @@
 //
 // Selection = exact radix select on order-preserving 32-bit keys held in LDS:
 //   4 passes of 8 bits from the top: histogram (LDS atomics) of the digit among the keys that
-//   match the prefix found so far, suffix-sum over the 256 bins, pick the bin in which the
-//   k-th largest key falls. After 4 passes the prefix is the exact k-th largest key T and
+//   match the prefix found so far, suffix-sum over the 256 bins (one wavefront, shuffles), pick
+//   the bin in which the k-th largest key falls. After 4 passes the prefix is the exact k-th largest key T and
 //   `need` is how many keys equal to T survive. Ties go to the lower token index because
 //   the compaction below walks tokens in index order: a token survives iff key > T, or
 //   key == T and fewer than `need` equal keys precede it. A block-wide exclusive scan of the
@@ -31,8 +31,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_compact_kernel(TopkArgs a) 
   extern __shared__ uint32_t lds[];
   uint32_t* keys = lds;                 // [n_g]
   uint32_t* kept = lds + a.n_g;         // [rows_per]: this workgroup's slice of the kept list
-  __shared__ uint32_t hist[256];
-  __shared__ uint32_t suffix[257];
+  __shared__ __attribute__((aligned(16))) uint32_t hist[256];
   __shared__ uint32_t wave_gt[TOPK_THREADS / 64], wave_eq[TOPK_THREADS / 64];
   __shared__ uint32_t sel_prefix, sel_need;
 
@@ -57,22 +56,26 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_compact_kernel(TopkArgs a) 
       if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
     }
     __syncthreads();
-    // suffix[b] = number of matching keys with digit >= b (Hillis-Steele over 256 bins)
-    if (tid < 256) suffix[tid] = hist[tid];
-    if (tid == 256) suffix[256] = 0;
-    __syncthreads();
-    for (int off = 1; off < 256; off <<= 1) {
-      uint32_t add = 0;
-      if (tid < 256 && tid + off < 256) add = suffix[tid + off];
-      __syncthreads();
-      if (tid < 256) suffix[tid] += add;
-      __syncthreads();
-    }
-    const uint32_t need = sel_need;
-    __syncthreads();
-    if (tid < 256 && suffix[tid] >= need && suffix[tid + 1] < need) {
-      sel_prefix = prefix | ((uint32_t)tid << shift);
-      sel_need = need - suffix[tid + 1];
+    // Wavefront 0 finds the bin of the k-th largest key: lane l owns bins 4l..4l+3; suffix sums (number of
+    // matching keys with digit >= b) come from an in-lane sum plus a suffix scan over the lanes.
+    if (tid < 64) {
+      const uint32_t need = sel_need;
+      const uint4 hb = *(const uint4*)&hist[4 * tid];
+      const uint32_t s3 = hb.w, s2 = s3 + hb.z, s1 = s2 + hb.y, s0 = s1 + hb.x;
+      uint32_t above = s0;  // inclusive suffix over lanes
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t t = __shfl_down(above, o, 64);
+        if (tid + o < 64) above += t;
+      }
+      above -= s0;  // keys in bins owned by higher lanes
+      const uint32_t suf[5] = {above + s0, above + s1, above + s2, above + s3, above};
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (suf[j] >= need && suf[j + 1] < need) {  // true for exactly one (lane, j)
+          sel_prefix = prefix | ((uint32_t)(4 * tid + j) << shift);
+          sel_need = need - suf[j + 1];
+        }
     }
     mask |= 255u << shift;
     __syncthreads();
@@ -151,7 +154,10 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_compact_kernel(TopkArgs a) 
 
 template <typename T, int D>
 static hipError_t launch_t(const TopkArgs& a, hipStream_t s) {
-  int n_split = (a.keep + 63) / 64;  // >= 64 rows (32 KB of K+V at d=128 bf16) per workgroup
+  // >= 64 rows (32 KB of K+V at d=128 bf16) per workgroup, and about two workgroups per CU over all heads
+  int n_split = (a.keep + 63) / 64;
+  const int cap = 512 / a.h_kv > 1 ? 512 / a.h_kv : 1;
+  if (n_split > cap) n_split = cap;
   if (n_split > 32) n_split = 32;
   if (n_split < 1) n_split = 1;
   const int rows_per = (a.keep + n_split - 1) / n_split;
