@@ -63,6 +63,7 @@ def characterise_hbm(torch, B, reps=6):
     vs = [torch.randn(n_g, h, d, device="cuda", dtype=torch.bfloat16) for _ in range(3)]
     scores = torch.empty(h, n_g, dtype=torch.float32, device="cuda")
     cache = B.Cache(layout, keep)
+    kept = torch.empty(h, keep, dtype=torch.int32, device="cuda")
     out = {}
     ev = lambda: torch.cuda.Event(enable_timing=True)
     # key-norm scores: read K once, write H*N_g floats
@@ -82,13 +83,13 @@ def characterise_hbm(torch, B, reps=6):
     # top-k + compaction: read the scores, gather keep rows of K and V, write them + pos
     for i in range(3):
         cache.reset()
-        B.topk_compact(layout, scores, ks[i], vs[i], keep, 0, cache)
+        B.topk_compact(layout, scores, ks[i], vs[i], keep, 0, cache, kept)
     torch.cuda.synchronize()
     e0, e1 = ev(), ev()
     e0.record()
     for i in range(reps):
         cache.reset()
-        B.topk_compact(layout, scores, ks[i % 3], vs[i % 3], keep, 0, cache)
+        B.topk_compact(layout, scores, ks[i % 3], vs[i % 3], keep, 0, cache, kept)
     e1.record()
     torch.cuda.synchronize()
     t = e0.elapsed_time(e1) * 1e-3 / reps

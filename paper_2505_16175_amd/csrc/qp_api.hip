@@ -77,7 +77,7 @@ bool side_stream_ready() {
   return g_side.ok;
 }
 
-// Workspace layout: [scores H_kv*n_g f32][window scratch].
+// Workspace layout of qp_prefill_video: [scores H_kv*n_g f32][kept indices H_kv*n_g i32][window scratch].
 size_t scores_bytes(const qp_layout* L, int32_t n_g) { return round256((size_t)L->n_kv_heads * n_g * sizeof(float)); }
 
 }  // namespace
@@ -107,6 +107,7 @@ int64_t qp_cache_capacity(int32_t n_frames, int32_t tokens_per_frame, int32_t gr
 size_t qp_workspace_bytes(const qp_layout* L, int32_t max_group_tokens, int32_t n_window) {
   if (check_layout(L) != QP_OK || check_group(max_group_tokens) != QP_OK || n_window < 0) return 0;
   size_t b = scores_bytes(L, max_group_tokens);
+  b += qp::topk_workspace_bytes(L->n_kv_heads, max_group_tokens);
   b += qp::window_workspace_bytes(L->n_q_heads, L->n_kv_heads, max_group_tokens, n_window > 0 ? n_window : 1);
   return b + 256;
 }
@@ -200,8 +201,6 @@ qp_status qp_score_kv(const qp_layout* L, qp_score_rule rule, const void* k_g, c
 qp_status qp_topk_compact(const qp_layout* L, const float* scores, const void* k_g, const void* v_g, int32_t n_g,
                           int32_t keep, int32_t group_token_base, qp_cache* cache, int32_t* kept_idx, void* workspace,
                           size_t workspace_bytes, void* hip_stream) {
-  (void)workspace;
-  (void)workspace_bytes;
   qp_status st = check_layout(L);
   if (st != QP_OK) return st;
   if ((st = check_group(n_g)) != QP_OK) return st;
@@ -211,6 +210,13 @@ qp_status qp_topk_compact(const qp_layout* L, const float* scores, const void* k
   if (kept_idx && (((uintptr_t)kept_idx) & 3u)) return QP_ERR_INVALID_ARG;
   if (keep < 1 || keep > n_g || group_token_base < 0) return QP_ERR_INVALID_ARG;
   if ((int64_t)cache->len + keep > cache->capacity) return QP_ERR_CAPACITY;
+  // the kept indices pass from the selection to the copy through the caller's buffer or the workspace
+  int32_t* kept_ws = kept_idx;
+  if (kept_ws == nullptr) {
+    if (!workspace || (((uintptr_t)workspace) & 255u)) return QP_ERR_INVALID_ARG;
+    if (workspace_bytes < qp::topk_workspace_bytes(L->n_kv_heads, keep)) return QP_ERR_CAPACITY;
+    kept_ws = (int32_t*)workspace;
+  }
 
   qp::TopkArgs a;
   a.scores = scores;
@@ -219,7 +225,6 @@ qp_status qp_topk_compact(const qp_layout* L, const float* scores, const void* k
   a.ck = cache->k;
   a.cv = cache->v;
   a.pos = cache->pos;
-  a.kept = kept_idx;
   a.n_g = n_g;
   a.h_kv = L->n_kv_heads;
   a.d = L->head_dim;
@@ -227,7 +232,7 @@ qp_status qp_topk_compact(const qp_layout* L, const float* scores, const void* k
   a.base = group_token_base;
   a.cap = cache->capacity;
   a.len = cache->len;
-  st = finish(qp::launch_topk_compact(a, L->dtype, (hipStream_t)hip_stream));
+  st = finish(qp::launch_topk_compact(a, L->dtype, kept_ws, (hipStream_t)hip_stream));
   if (st == QP_OK) cache->len += keep;
   return st;
 }
@@ -271,8 +276,10 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
   const size_t kv_tok = (size_t)L->n_kv_heads * L->head_dim * esz;
   float* scores = (float*)workspace;
   const size_t sb = scores_bytes(L, (int32_t)max_group);
-  void* ws2 = (char*)workspace + sb;
-  const size_t ws2_bytes = workspace_bytes - sb;
+  int32_t* kept_ws = (int32_t*)((char*)workspace + sb);
+  const size_t kb = qp::topk_workspace_bytes(L->n_kv_heads, (int32_t)max_group);
+  void* ws2 = (char*)workspace + sb + kb;
+  const size_t ws2_bytes = workspace_bytes - sb - kb;
 
   hipStream_t main_stream = (hipStream_t)hip_stream;
   const bool overlap = side_stream_ready();
@@ -297,7 +304,7 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
     //    The appended rows [len, len+k) are disjoint from the rows [0, len) the attention kernel is reading.
     st = qp_score_kv(L, rule, kg, vg, n_g, q_win, n_window, scores, ws2, ws2_bytes, score_stream);
     if (st != QP_OK) break;
-    st = qp_topk_compact(L, scores, kg, vg, n_g, (int32_t)qp_keep_count(n_g, retention), base, cache, nullptr, ws2,
+    st = qp_topk_compact(L, scores, kg, vg, n_g, (int32_t)qp_keep_count(n_g, retention), base, cache, kept_ws, ws2,
                          ws2_bytes, score_stream);
     if (st != QP_OK) break;
     if (overlap) {

@@ -112,9 +112,9 @@ struct TopkArgs {
   void* ck;             // [h_kv][cap][d]
   void* cv;
   int32_t* pos;         // [h_kv][cap]
-  int32_t* kept;        // [h_kv][keep] or nullptr
   int n_g, h_kv, d, keep, base, cap, len;
 };
-hipError_t launch_topk_compact(const TopkArgs& a, int dtype, hipStream_t s);
+size_t topk_workspace_bytes(int h_kv, int keep);
+hipError_t launch_topk_compact(const TopkArgs& a, int dtype, int32_t* kept_ws, hipStream_t s);
 
 }  // namespace qp
