@@ -147,10 +147,11 @@ qp_status qp_topk_compact(const qp_layout* layout, const float* scores, const vo
  *     to every group. Needs capacity >= len + qp_cache_capacity(...).
  *   out [N][H_q][d]
  * All arguments are validated before the first launch. Scoring and compaction of a group do not
- * depend on its attention, so they are enqueued on a second, library-owned stream (created on
- * first use, default priority) that is forked from hip_stream at entry and joined back into it
- * before the call returns: work the caller enqueues on hip_stream afterwards is ordered after
- * all of this call's work. */
+ * depend on its attention, and the attention of group g+1 depends on the compaction of group g but
+ * not on the attention of group g; the call uses two library-owned streams (created on first use,
+ * default priority) for the scoring/compaction chain and for every other group's attention. They are
+ * forked from hip_stream at entry and joined back into it before the call returns: work the
+ * caller enqueues on hip_stream afterwards is ordered after all of this call's work. */
 qp_status qp_prefill_video(const qp_layout* layout, int32_t n_frames, int32_t tokens_per_frame,
                            int32_t group_frames, double retention, qp_score_rule rule, const void* q,
                            const void* k, const void* v, const void* q_win, int32_t n_window, qp_cache* cache,

@@ -55,23 +55,33 @@ qp_status finish(hipError_t launch_err) {
   return QP_OK;
 }
 
-// Second stream of qp_prefill_video: scoring and top-k/compaction of a group depend only on the
-// group's K/V (and the query window), never on its attention, so they run beside the group's
-// attention kernel. Created once per process, default priority, joined back before the call returns
-// control of the ordering to the caller's stream.
-struct SideStream {
-  hipStream_t stream = nullptr;
-  hipEvent_t fork = nullptr, join = nullptr;
+// Library-owned streams of qp_prefill_video (created once per process, default priority):
+//   score   scoring and top-k/compaction of a group depend only on the group's K/V (and the query window),
+//           never on its attention, so they run beside the group's attention kernel;
+//   attend2 the attention of group g+1 depends on the compaction of group g but not on the attention of
+//           group g, so odd groups' attention kernels go to a second attention stream: the tail of one
+//           group's kernel (a few heavy row blocks, and fewer workgroups than CUs at small groups) is
+//           filled by the next group's workgroups.
+// Both are forked from the caller's stream at entry and joined back into it before the call returns.
+constexpr int MAX_ATT_STREAMS = 2;  // attention streams in rotation, the caller's included (3 measured no better, 4 worse)
+struct SideStreams {
+  hipStream_t score = nullptr, attend[MAX_ATT_STREAMS] = {};  // attend[0] is unused (the caller's stream)
+  hipEvent_t fork = nullptr, compacted[2] = {nullptr, nullptr}, attend_done[MAX_ATT_STREAMS] = {};
+  int n_att = MAX_ATT_STREAMS;
   bool tried = false, ok = false;
 };
-SideStream g_side;
+SideStreams g_side;
 
-bool side_stream_ready() {
+bool side_streams_ready() {
   if (!g_side.tried) {
     g_side.tried = true;
-    g_side.ok = hipStreamCreateWithFlags(&g_side.stream, hipStreamNonBlocking) == hipSuccess &&
+    g_side.ok = hipStreamCreateWithFlags(&g_side.score, hipStreamNonBlocking) == hipSuccess &&
                 hipEventCreateWithFlags(&g_side.fork, hipEventDisableTiming) == hipSuccess &&
-                hipEventCreateWithFlags(&g_side.join, hipEventDisableTiming) == hipSuccess;
+                hipEventCreateWithFlags(&g_side.compacted[0], hipEventDisableTiming) == hipSuccess &&
+                hipEventCreateWithFlags(&g_side.compacted[1], hipEventDisableTiming) == hipSuccess;
+    for (int i = 1; i < MAX_ATT_STREAMS && g_side.ok; ++i)
+      g_side.ok = hipStreamCreateWithFlags(&g_side.attend[i], hipStreamNonBlocking) == hipSuccess &&
+                  hipEventCreateWithFlags(&g_side.attend_done[i], hipEventDisableTiming) == hipSuccess;
     if (!g_side.ok) (void)hipGetLastError();
   }
   return g_side.ok;
@@ -282,14 +292,17 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
   const size_t ws2_bytes = workspace_bytes - sb - kb;
 
   hipStream_t main_stream = (hipStream_t)hip_stream;
-  const bool overlap = side_stream_ready();
-  void* score_stream = overlap ? (void*)g_side.stream : hip_stream;
+  const bool overlap = side_streams_ready();
+  void* score_stream = overlap ? (void*)g_side.score : hip_stream;
+#define QP_HIP_OK(call_) \
+  if ((call_) != hipSuccess) return finish(hipGetLastError())
   if (overlap) {
-    if (hipEventRecord(g_side.fork, main_stream) != hipSuccess || hipStreamWaitEvent(g_side.stream, g_side.fork, 0) != hipSuccess)
-      return finish(hipGetLastError());
+    QP_HIP_OK(hipEventRecord(g_side.fork, main_stream));
+    QP_HIP_OK(hipStreamWaitEvent(g_side.score, g_side.fork, 0));
+    for (int i = 1; i < g_side.n_att; ++i) QP_HIP_OK(hipStreamWaitEvent(g_side.attend[i], g_side.fork, 0));
   }
-  bool pending_join = false;
-  for (int32_t f = 0; f < n_frames; f += group_frames) {
+  int gi = 0;
+  for (int32_t f = 0; f < n_frames; f += group_frames, ++gi) {
     const int32_t g = (n_frames - f) < group_frames ? (n_frames - f) : group_frames;
     const int32_t base = f * tokens_per_frame, n_g = g * tokens_per_frame;
     const char* qg = (const char*)q + (size_t)base * q_tok;
@@ -297,26 +310,30 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
     const char* vg = (const char*)v + (size_t)base * kv_tok;
     char* og = (char*)out + (size_t)base * q_tok;
     // 1. attend to the pruned cache so far (complete once the previous group's compaction is) + the group itself
-    if (pending_join && hipStreamWaitEvent(main_stream, g_side.join, 0) != hipSuccess) return finish(hipGetLastError());
-    st = qp_group_attend(L, qg, kg, vg, n_g, cache, og, nullptr, ws2, ws2_bytes, hip_stream);
+    const int ai = overlap ? gi % g_side.n_att : 0;
+    hipStream_t att_stream = ai ? g_side.attend[ai] : main_stream;
+    if (overlap && gi > 0) QP_HIP_OK(hipStreamWaitEvent(att_stream, g_side.compacted[(gi - 1) & 1], 0));
+    st = qp_group_attend(L, qg, kg, vg, n_g, cache, og, nullptr, ws2, ws2_bytes, (void*)att_stream);
     if (st != QP_OK) break;
     // 2. score the group's new KV entries; 3. TopK + compaction into the cache (cache->len advances on the host).
-    //    The appended rows [len, len+k) are disjoint from the rows [0, len) the attention kernel is reading.
+    //    The appended rows [len, len+k) are disjoint from the rows [0, len) any attention kernel in flight reads.
     st = qp_score_kv(L, rule, kg, vg, n_g, q_win, n_window, scores, ws2, ws2_bytes, score_stream);
     if (st != QP_OK) break;
     st = qp_topk_compact(L, scores, kg, vg, n_g, (int32_t)qp_keep_count(n_g, retention), base, cache, kept_ws, ws2,
                          ws2_bytes, score_stream);
     if (st != QP_OK) break;
-    if (overlap) {
-      if (hipEventRecord(g_side.join, g_side.stream) != hipSuccess) return finish(hipGetLastError());
-      pending_join = true;
+    if (overlap) QP_HIP_OK(hipEventRecord(g_side.compacted[gi & 1], g_side.score));
+  }
+  // everything enqueued on the library's streams is ordered before whatever the caller enqueues next
+  if (overlap) {
+    QP_HIP_OK(hipEventRecord(g_side.compacted[0], g_side.score));
+    QP_HIP_OK(hipStreamWaitEvent(main_stream, g_side.compacted[0], 0));
+    for (int i = 1; i < g_side.n_att; ++i) {
+      QP_HIP_OK(hipEventRecord(g_side.attend_done[i], g_side.attend[i]));
+      QP_HIP_OK(hipStreamWaitEvent(main_stream, g_side.attend_done[i], 0));
     }
   }
-  // everything enqueued on the second stream is ordered before whatever the caller enqueues next
-  if (overlap) {
-    if (!pending_join) (void)hipEventRecord(g_side.join, g_side.stream);
-    if (hipStreamWaitEvent(main_stream, g_side.join, 0) != hipSuccess) return finish(hipGetLastError());
-  }
+#undef QP_HIP_OK
   return st;
 }
 
