@@ -148,7 +148,13 @@ def main():
     ap.add_argument("--config", default="cfg2_7b_32k")
     ap.add_argument("--rule", default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mfma-probe", action="store_true",
+                    help="run the stand-alone matrix-pipe probe (bf16 MFMA rate with constant / random operands) and exit")
     args = ap.parse_args()
+    if args.mfma_probe:
+        import subprocess
+        from paper_2505_16175_amd.build import PROBE_PATH
+        sys.exit(subprocess.run([PROBE_PATH]).returncode)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)

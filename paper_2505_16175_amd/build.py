@@ -21,11 +21,21 @@ def hipcc_command(out=LIB_PATH, extra=()):
             "-I", os.path.join(ROOT, "include"), "-I", CSRC, *extra, *srcs, "-o", out]
 
 
+PROBE_PATH = os.path.join(PKG_DIR, "mfma_peak_probe")
+
+
+def probe_command():
+    """The stand-alone matrix-pipe probe (what bf16 MFMA rate this GPU sustains; see bench.py --mfma-probe)."""
+    return ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+            "-packed-fp32-ops", "-Wno-unused-command-line-argument", os.path.join(CSRC, "mfma_peak_probe.hip"),
+            "-o", PROBE_PATH]
+
+
 def build(verbose=True):
-    cmd = hipcc_command()
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+    for cmd in (hipcc_command(), probe_command()):
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
     return LIB_PATH
 
 
