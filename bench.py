@@ -147,6 +147,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg2_7b_32k")
     ap.add_argument("--rule", default=None)
+    ap.add_argument("--layers", type=int, default=None,
+                    help="layers of a stacked config to run per step (default: all of the config's; inputs and the "
+                         "pruned cache of every layer stay resident in HBM)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mfma-probe", action="store_true",
                     help="run the stand-alone matrix-pipe probe (bf16 MFMA rate with constant / random operands) and exit")
@@ -169,18 +172,22 @@ def main():
     torch.cuda.set_device(0)
     w = CONFIGS[args.config]
     rule = args.rule or w.rules[0]
-    q, k, v, qw = make_layer(w, layer=0, device="cuda")
+    n_layers = args.layers or w.n_layers
+    layers = [make_layer(w, layer=l, device="cuda") for l in range(n_layers)]
+    q, k, v, qw = layers[0]
     layout = B.make_layout(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
     cap = B.cache_capacity(w.n_frames, w.tokens_per_frame, w.group_frames, w.retention)
-    cache = B.Cache(layout, cap)
+    caches = [B.Cache(layout, cap) for _ in range(n_layers)]   # every layer's pruned cache stays resident
+    cache = caches[0]
     ws = B.make_workspace(layout, w.group_tokens, w.n_window)
-    out = torch.empty_like(q)
+    out = torch.empty_like(q)                                  # the layer output is consumed and overwritten
     qwin = qw if rule == "window_attn" else None
 
     def step():
-        cache.reset()
-        B.prefill_video(layout, w.n_frames, w.tokens_per_frame, w.group_frames, w.retention, rule, q, k, v, qwin,
-                        cache, out, ws)
+        for (lq, lk, lv, lqw), c in zip(layers, caches):
+            c.reset()
+            B.prefill_video(layout, w.n_frames, w.tokens_per_frame, w.group_frames, w.retention, rule, lq, lk, lv,
+                            lqw if rule == "window_attn" else None, c, out, ws)
 
     for _ in range(args.warmup):
         step()
@@ -191,7 +198,8 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
-    value = w.n_tokens * args.steps / elapsed
+    value = w.n_tokens * n_layers * args.steps / elapsed      # tokens per second per layer
+    resident_cache_bytes = sum(c.nbytes() for c in caches)
 
     # ---- instrumented replay of the same steps: HIP events around every launch group of the path
     bounds = w.group_bounds()
@@ -252,8 +260,9 @@ def main():
         "config": {"workload": f"{w.name}: {w.n_q_heads}q/{w.n_kv_heads}kv heads x d{w.head_dim}, "
                                f"{w.n_frames} frames x {w.tokens_per_frame} tokens, group {w.group_frames} frames, "
                                f"retention {w.retention}, rule {rule}, window {w.n_window if qwin is not None else 0}",
-                   "n_tokens": w.n_tokens, "groups": len(bounds), "final_cache_len_per_head": cache.len,
-                   "cache_bytes": cache.nbytes()},
+                   "n_tokens": w.n_tokens, "groups": len(bounds), "layers": n_layers,
+                   "final_cache_len_per_head": cache.len, "cache_bytes_per_layer": cache.nbytes(),
+                   "resident_cache_bytes": resident_cache_bytes},
         "roofline": roofline, "stages": stages,
     }
     # calibration copy for the HBM counters: a plain device-to-device copy of known size (outside all timing)
