@@ -307,3 +307,82 @@ def test_cfg5_full_size_layer(layer):
     assert cache.nbytes() == 2 * 4 * 46125 * 128 * 2
     want = O.kv_cache_bytes(1, w.n_tokens, w.n_kv_heads, w.head_dim, 2, retention=cache.len / w.n_tokens)
     assert abs(cache.nbytes() - want) < 1e-6 * want
+
+
+# --------------------------------------------------------------------------------------------- behaviour of the boundary
+def test_runs_are_deterministic_and_stream_ordered():
+    """Same inputs twice -> bit-identical cache, positions and outputs; a non-default caller stream is honoured."""
+    w = scaled(CONFIGS["cfg2_7b_32k"], n_frames=24, tokens_per_frame=96, group_frames=5)
+    q, k, v, qw = make_layer(w, device=DEV, sharp=True)
+    results = []
+    side = torch.cuda.Stream()
+    for use_side in (False, True, False):
+        if use_side:
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                out, cache = _run_prefill(w, q, k, v, qw, "window_attn")
+                # work enqueued on the caller's stream after the call sees all of its results, without a host sync
+                snap = (out.clone(), cache.k.clone(), cache.v.clone(), cache.pos.clone())
+            torch.cuda.current_stream().wait_stream(side)
+        else:
+            out, cache = _run_prefill(w, q, k, v, qw, "window_attn")
+            snap = (out.clone(), cache.k.clone(), cache.v.clone(), cache.pos.clone())
+        torch.cuda.synchronize()
+        results.append(snap)
+    for other in results[1:]:
+        for a, b in zip(results[0], other):
+            assert torch.equal(a, b)
+
+
+def test_capacity_and_unsupported_errors_leave_the_cache_alone():
+    layout = B.make_layout(8, 2, 128, "bf16")
+    n_g, keep = 256, 100
+    k = torch.randn(n_g, 2, 128, device=DEV).bfloat16()
+    v = torch.randn(n_g, 2, 128, device=DEV).bfloat16()
+    s = torch.randn(2, n_g, device=DEV)
+    cache = B.Cache(layout, 150)
+    kept = torch.empty(2, keep, dtype=torch.int32, device=DEV)
+    B.topk_compact(layout, s, k, v, keep, 0, cache, kept)
+    assert cache.len == 100
+    before = (cache.k.clone(), cache.pos.clone())
+    with pytest.raises(B.QPError) as e:
+        B.topk_compact(layout, s, k, v, keep, n_g, cache, kept)          # 100 + 100 > 150
+    assert e.value.status == B.QP_ERR_CAPACITY and cache.len == 100
+    with pytest.raises(B.QPError) as e:
+        B.topk_compact(layout, s, k, v, 20, n_g, cache, None, None)      # fits, but no kept buffer and no workspace
+    assert e.value.status == B.QP_ERR_INVALID_ARG and cache.len == 100
+    torch.cuda.synchronize()
+    assert torch.equal(cache.k, before[0]) and torch.equal(cache.pos, before[1])
+    # forcing the MFMA kernel on a layout it does not take is refused, the scalar kernel takes it
+    l64 = B.make_layout(4, 2, 64, "bf16")
+    q64 = torch.randn(16, 4, 64, device=DEV).bfloat16()
+    k64 = torch.randn(16, 2, 64, device=DEV).bfloat16()
+    o64 = torch.empty_like(q64)
+    B.select_attend_kernel(B.QP_ATTEND_MFMA)
+    with pytest.raises(B.QPError) as e:
+        B.group_attend(l64, q64, k64, k64, None, o64)
+    assert e.value.status == B.QP_ERR_UNSUPPORTED
+    B.select_attend_kernel(B.QP_ATTEND_AUTO)
+    B.group_attend(l64, q64, k64, k64, None, o64)
+    torch.cuda.synchronize()
+    assert torch.isfinite(o64.float()).all()
+
+
+def test_group_attend_largest_group():
+    """The largest group the boundary accepts (32768 tokens), few heads: sampled rows against the oracle."""
+    n_g, h_q, h_kv, d, c = B.QP_MAX_GROUP_TOKENS, 2, 1, 128, 100
+    g = torch.Generator(device=DEV).manual_seed(3)
+    mk = lambda *s: torch.randn(*s, generator=g, device=DEV).bfloat16()
+    q, k, v = mk(n_g, h_q, d), mk(n_g, h_kv, d), mk(n_g, h_kv, d)
+    layout = B.make_layout(h_q, h_kv, d, "bf16")
+    cache = B.Cache(layout, c)
+    cache.k.copy_(mk(h_kv, c, d))
+    cache.v.copy_(mk(h_kv, c, d))
+    cache.c.len = c
+    out = torch.full_like(q, float("nan"))
+    B.group_attend(layout, q, k, v, cache, out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    rows = sample_rows(n_g, 20, np.random.default_rng(1))
+    want = O.attend_group(_f64(q), _f64(k), _f64(v), _f64(cache.k), _f64(cache.v), rows=rows)
+    assert_attn_close(_f64(out[rows]), want, "bf16", "largest group")
