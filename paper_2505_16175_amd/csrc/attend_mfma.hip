@@ -68,22 +68,6 @@ constexpr float MF_RESCALE_LOG2 = 8.f;  // move the reference max only when it g
 constexpr int MF_VMCNT0 = 0x0f70;       // s_waitcnt vmcnt(0), other counters untouched
 constexpr int MF_VMCNT4 = 0x0f74;       // s_waitcnt vmcnt(4)
 
-// 64 lanes x 16 bytes global -> LDS without passing through registers: lane L's chunk lands at
-// lds_dst + 16 L (lds_dst is wave-uniform). Written as inline assembly so that the compiler does not
-// treat it as an LDS store it must drain (vmcnt(0)) before every later LDS read; the kernel waits for
-// these loads itself (s_waitcnt vmcnt) before the barrier that publishes a tile.
-__device__ __forceinline__ void lds_dma16(const unsigned char* base, unsigned byte_off, unsigned char* lds_dst) {
-  const unsigned lds_addr =
-      __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds_dst);
-  asm volatile(
-      "s_mov_b32 m0, %2\n\t"
-      "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %0, %1"
-      :
-      : "v"(byte_off), "s"(base), "s"(lds_addr)
-      : "memory");
-}
-
 // S^T (64 keys x 32 rows, two 32-key blocks) = K tile . Q^T. All 16 K fragments are read before the
 // first MFMA (a scheduling barrier keeps the compiler from sinking each read next to its use,
 // which would serialise on LDS latency).

@@ -71,6 +71,22 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+// 64 lanes x 16 bytes global -> LDS without passing through registers: lane L's chunk lands at
+// lds_dst + 16 L (lds_dst is wave-uniform). Written as inline assembly so that the compiler does not
+// treat it as an LDS store it must drain (vmcnt(0)) before every later LDS read; the kernel waits for
+// these loads itself (s_waitcnt vmcnt) before the barrier that publishes a tile.
+__device__ __forceinline__ void lds_dma16(const unsigned char* base, unsigned byte_off, unsigned char* lds_dst) {
+  const unsigned lds_addr =
+      __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds_dst);
+  asm volatile(
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, %1"
+      :
+      : "v"(byte_off), "s"(base), "s"(lds_addr)
+      : "memory");
+}
+
 // Arguments common to the attention kernels. All pointers are device pointers.
 struct AttendArgs {
   const void* q;      // [n_g][h_q][d]
