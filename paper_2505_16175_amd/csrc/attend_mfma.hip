@@ -6,9 +6,11 @@
 //
 // Mapping. The R query heads that share a KV head are stacked into one row space per KV head:
 // row r = t * R + j (j = query head inside the KV group), which is also the memory order of
-// Q_g[t][h*R + j][:]. A workgroup of 8 wavefronts owns 256 consecutive rows of one KV head;
-// every K/V tile it stages in LDS is therefore shared by all R query heads (GQA) and by 256/R
-// tokens. The keys are walked as two segments, cache tiles first and then group tiles starting
+// Q_g[t][h*R + j][:]. A workgroup of 8 wavefronts owns 256 rows of one KV head, as two half blocks
+// of 128 consecutive rows: one from the early end of the group and its mirror from the late end, so
+// that all workgroups carry the same causal work (a launch of about one workgroup per CU then ends
+// everywhere at the same time instead of waiting for the latest tokens). Every K/V tile staged in
+// LDS is shared by all R query heads (GQA) and by both half blocks. The keys are walked as two segments, cache tiles first and then group tiles starting
 // at group token 0, so a tile never straddles the two sources; only the cache's last tile and the
 // group's diagonal tiles are masked, and a wavefront skips group tiles beyond its causal horizon.
 //
@@ -60,7 +62,7 @@ constexpr int MF_D = 128;               // head_dim
 constexpr int MF_BN = 64;               // keys per tile
 constexpr int MF_NW = 8;                // wavefronts per workgroup
 constexpr int MF_NT = MF_NW * 64;
-constexpr int MF_BM = MF_NW * 32;       // rows per workgroup
+constexpr int MF_HB = MF_NW / 2 * 32;   // rows per half block (4 wavefronts); a workgroup owns two half blocks
 constexpr int MF_TILE = MF_BN * 256;    // bytes of one K or V tile (unpadded, swizzled)
 constexpr int MF_SLOT = 2 * MF_TILE;    // K tile + V tile
 constexpr int MF_STAGES = 3;            // ring of K+V tile slots
@@ -163,7 +165,8 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
   const int l32 = lane & 31, g = lane >> 5;
   const int r_heads = a.h_q / a.h_kv;
   const int n_rows = a.n_g * r_heads;
-  const int n_rb = (n_rows + MF_BM - 1) / MF_BM;
+  const int n_hb = (n_rows + MF_HB - 1) / MF_HB;  // half blocks of 128 rows
+  const int n_rb = (n_hb + 1) / 2;                // workgroups per KV head: one per pair of half blocks
   // workgroup id -> (KV head, row block): ids go round-robin over the 8 XCDs
   int h, rbi;
   {
@@ -182,9 +185,15 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
     }
   }
   if (rbi >= n_rb) return;        // padding workgroups of the XCD mapping (whole workgroup, before any barrier)
-  const int rb = n_rb - 1 - rbi;  // heaviest (latest tokens) first
-  const int row0_wg = rb * MF_BM;
-  const int row0 = row0_wg + wave * 32;
+  // Causal balance: the workgroup owns half block rbi (early tokens, short key range) and its mirror
+  // n_hb-1-rbi (late tokens, long key range), so every workgroup of a launch has the same amount of work.
+  // Wavefronts 0..3 take the early half block and 4..7 the late one: wavefronts w and w+4 share a SIMD,
+  // so each SIMD keeps one wavefront busy after the early rows have reached their causal horizon.
+  const int half = wave >> 2;
+  const int hb_late = n_hb - 1 - rbi;
+  const int hb = half ? hb_late : rbi;
+  const bool unpaired = half == 0 && rbi == hb_late;  // odd count: the middle half block is served as "late" only
+  const int row0 = hb * MF_HB + (wave & 3) * 32;
   const int row = row0 + l32;
   const bool row_ok = row < n_rows;
   const int rowc = row_ok ? row : n_rows - 1;
@@ -194,8 +203,8 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
   // wave-uniform token horizons
   const int t_w_max = min(row0 + 31, n_rows - 1) / r_heads;
   const int t_w_min = min(row0, n_rows - 1) / r_heads;
-  const int t_wg_max = min(row0_wg + MF_BM - 1, n_rows - 1) / r_heads;
-  const bool wave_live = row0 < n_rows;
+  const int t_wg_max = min(hb_late * MF_HB + MF_HB - 1, n_rows - 1) / r_heads;
+  const bool wave_live = row0 < n_rows && !unpaired;
   const int n_ct = (a.c + MF_BN - 1) / MF_BN;       // cache tiles
   const int n_tiles = n_ct + t_wg_max / MF_BN + 1;  // + group tiles
 
@@ -335,7 +344,7 @@ void launch_attend_mfma(const AttendArgs& a, hipStream_t s) {
     attr_set = true;
   }
   const int n_rows = a.n_g * (a.h_q / a.h_kv);
-  const int n_rb = (n_rows + MF_BM - 1) / MF_BM;
+  const int n_rb = ((n_rows + MF_HB - 1) / MF_HB + 1) / 2;
   int n_wg = n_rb * a.h_kv;
   if (8 % a.h_kv == 0) {
     const int per = 8 / a.h_kv;
