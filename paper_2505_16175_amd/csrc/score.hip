@@ -8,7 +8,9 @@
 // Norms: a row of d elements is 256 bytes (bf16 d=128, f32 d=64) or a multiple of 16 bytes in
 // general; LPR = row bytes / 16 lanes load one 16-byte chunk each, square-accumulate in f32 and
 // finish with an xor-shuffle reduction inside the LPR-lane group; every lane keeps four rows' loads in
-// flight. HBM-bound streaming.
+// flight. A wavefront takes consecutive tokens of ONE KV head per step, so that its scores leave as
+// one contiguous store (scores are [h][token] while the rows are [token][h]: writing one float per
+// row in row order cost eight times the score bytes in partial-line writes). HBM-bound streaming.
 //
 // Window rule, scalar version: pass 1 gives every window row its log-sum-exp over the group's
 // keys (one wavefront per row, lanes over keys); pass 2 gives every key the sum over rows of
@@ -21,23 +23,27 @@ namespace qp {
 constexpr int NORM_UNROLL = 4;  // rows in flight per lane group: four independent 16-byte loads per lane
 
 template <typename T, int D>
-__global__ __launch_bounds__(256) void score_norm_kernel(const T* __restrict__ x, int n_rows, int n_g, int h_kv,
-                                                         float sign, float* __restrict__ scores) {
+__global__ __launch_bounds__(256) void score_norm_kernel(const T* __restrict__ x, int n_g, int h_kv, float sign,
+                                                         float* __restrict__ scores) {
   constexpr int PER = Elem<T>::kPer16B;
-  constexpr int LPR = D / PER;  // lanes per row, power of two <= 64
-  const int gid = blockIdx.x * blockDim.x + threadIdx.x;
-  const int sub = gid % LPR;
-  const int groups = (gridDim.x * blockDim.x) / LPR;  // lane groups in the grid
-  for (int row0 = gid / LPR; row0 < n_rows; row0 += groups * NORM_UNROLL) {
+  constexpr int LPR = D / PER;             // lanes per row, power of two in 8..32
+  constexpr int TW = 64 / LPR * NORM_UNROLL;  // tokens per wavefront item
+  static_assert(LPR >= NORM_UNROLL && LPR <= 64, "row layout");
+  const int lane = threadIdx.x & 63, sub = lane % LPR, lg = lane / LPR;
+  const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int n_waves = (gridDim.x * blockDim.x) >> 6;
+  const int n_tb = (n_g + TW - 1) / TW;
+  const long n_items = (long)n_tb * h_kv;  // item = (block of TW consecutive tokens, KV head); head fastest
+  for (long item = wave; item < n_items; item += n_waves) {
+    const int h = (int)(item % h_kv);
+    const int t0 = (int)(item / h_kv) * TW + lg * NORM_UNROLL;  // this lane group's first token
     uint4 raw[NORM_UNROLL];
 #pragma unroll
-    for (int u = 0; u < NORM_UNROLL; ++u) {
-      const int row = row0 + u * groups;
-      raw[u] = row < n_rows ? *(const uint4*)(x + (size_t)row * D + sub * PER) : make_uint4(0, 0, 0, 0);
-    }
+    for (int u = 0; u < NORM_UNROLL; ++u)
+      raw[u] = t0 + u < n_g ? *(const uint4*)(x + ((size_t)(t0 + u) * h_kv + h) * D + sub * PER) : make_uint4(0, 0, 0, 0);
+    float mine = 0.f;  // lane `sub` < NORM_UNROLL of the group ends up with token t0 + sub
 #pragma unroll
     for (int u = 0; u < NORM_UNROLL; ++u) {
-      const int row = row0 + u * groups;
       float v[PER];
       widen16<T>(raw[u], v);
       float ss = 0.f;
@@ -45,28 +51,30 @@ __global__ __launch_bounds__(256) void score_norm_kernel(const T* __restrict__ x
       for (int e = 0; e < PER; ++e) ss = fmaf(v[e], v[e], ss);
 #pragma unroll
       for (int o = LPR / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
-      if (row < n_rows && sub == 0) {
-        const int n = row / h_kv, h = row - n * h_kv;  // rows are (token, kv head)
-        scores[(size_t)h * n_g + n] = sign * sqrtf(ss) + 0.f;
-      }
+      if (sub == u) mine = ss;
     }
+    // one store instruction per wavefront item: TW consecutive floats of scores[h][:]
+    if (sub < NORM_UNROLL && t0 + sub < n_g) scores[(size_t)h * n_g + t0 + sub] = sign * sqrtf(mine) + 0.f;
   }
+}
+
+template <typename T, int D>
+static void launch_norm(const void* x, int n_g, int h_kv, float sign, float* scores, hipStream_t s) {
+  constexpr int TW = 64 / (D / Elem<T>::kPer16B) * NORM_UNROLL;
+  const long items = (long)((n_g + TW - 1) / TW) * h_kv;
+  long wgs = (items + 3) / 4;  // four wavefronts per workgroup, one item each
+  if (wgs > 8192) wgs = 8192;  // wavefronts stride over the items beyond 32 workgroups per CU
+  hipLaunchKernelGGL((score_norm_kernel<T, D>), dim3((unsigned)wgs), dim3(256), 0, s, (const T*)x, n_g, h_kv, sign, scores);
 }
 
 void launch_score_norm(const void* x, int dtype, int n_g, int h_kv, int d, float sign, float* scores,
                        hipStream_t s) {
-  const int n_rows = n_g * h_kv;
-  const int lpr = d / (dtype == QP_F32 ? 4 : 8);
-  const long threads = ((long)n_rows * lpr + NORM_UNROLL - 1) / NORM_UNROLL;
-  long wgs = (threads + 255) / 256;
-  if (wgs > 8192) wgs = 8192;  // grid-stride beyond 32 workgroups per CU
-  dim3 grid((unsigned)wgs), block(256);
   if (dtype == QP_F32) {
-    if (d == 64) hipLaunchKernelGGL((score_norm_kernel<float, 64>), grid, block, 0, s, (const float*)x, n_rows, n_g, h_kv, sign, scores);
-    else hipLaunchKernelGGL((score_norm_kernel<float, 128>), grid, block, 0, s, (const float*)x, n_rows, n_g, h_kv, sign, scores);
+    if (d == 64) launch_norm<float, 64>(x, n_g, h_kv, sign, scores, s);
+    else launch_norm<float, 128>(x, n_g, h_kv, sign, scores, s);
   } else {
-    if (d == 64) hipLaunchKernelGGL((score_norm_kernel<bf16_t, 64>), grid, block, 0, s, (const bf16_t*)x, n_rows, n_g, h_kv, sign, scores);
-    else hipLaunchKernelGGL((score_norm_kernel<bf16_t, 128>), grid, block, 0, s, (const bf16_t*)x, n_rows, n_g, h_kv, sign, scores);
+    if (d == 64) launch_norm<bf16_t, 64>(x, n_g, h_kv, sign, scores, s);
+    else launch_norm<bf16_t, 128>(x, n_g, h_kv, sign, scores, s);
   }
 }
 
