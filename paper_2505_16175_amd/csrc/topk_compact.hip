@@ -1,29 +1,43 @@
 // TopK of Eq. 2 (Sec. 3.2) per KV head, and compaction K~ = K_g[I], V~ = V_g[I] into the cache.
 //
 // Two launches on the same stream:
-//   topk_select_kernel     one workgroup per KV head; exact radix select on order-preserving 32-bit keys
+//   topk_select_kernel     one workgroup per KV head; exact selection on order-preserving 32-bit keys
 //                          held in LDS; writes the kept indices (ascending) and the cache positions.
 //   compact_gather_kernel  pure copy: 16-byte vector loads/stores, one row (d elements) per
 //                          d*sizeof/16 lanes, four rows per lane group in flight, 64 rows per workgroup.
 //
-// Selection: 4 passes of 8 bits from the top. Each pass builds the histogram of the digit among the
-// keys that match the prefix found so far (LDS atomics; the two most common digits of every
-// wavefront-wide batch are first aggregated with ballots, because real scores share sign and
-// exponent, so the first pass would otherwise serialise thousands of atomics on one bin), one
-// wavefront turns it into suffix sums with shuffles and picks the bin in which the k-th largest key
-// falls. After 4 passes the prefix is the exact k-th largest key T and `need` is how many keys equal
-// to T survive. Ties go to the lower token index because the compaction walks tokens in index
-// order: a token survives iff key > T, or key == T and fewer than `need` equal keys precede it. A
-// block-wide exclusive scan of the per-thread (greater, equal) counts over contiguous token
-// chunks gives each survivor its output slot, so the kept list is in ascending token order.
+// Selection = find the k-th largest key T and how many keys equal to T survive (`need`), then emit.
+//   * While loading, the workgroup takes the minimum and maximum key. A round spreads the current key
+//     range [lo, lo+span] over up to 2048 buckets of equal power-of-two width (bucket = (key-lo) >> sh),
+//     counts keys per bucket with LDS atomics, turns the counts into suffix sums (two buckets per
+//     thread, shuffles inside a wavefront, 16 wavefront totals through LDS) and picks the bucket in
+//     which the k-th largest key falls; the range shrinks to that bucket. Because the buckets follow the
+//     data's own range, real scores (which share sign and exponent) spread over them and the atomics
+//     rarely collide; one ballot per batch folds a digit shared by many lanes into a single atomic, so
+//     that a constant score vector does not serialise either.
+//   * As soon as the bucket holds at most 256 keys they are copied to a list and ranked directly
+//     (every candidate counts the candidates above and equal to it). Otherwise another round runs on the
+//     bucket; a bucket of width one is exact. The width shrinks by 2^11 per round: at most 3 rounds.
+//   * Emit: wavefront w owns a contiguous run of tokens and walks it 64 at a time; ballots give every
+//     survivor its rank inside the batch, running counts its slot. A token survives iff key > T, or
+//     key == T and fewer than `need` equal keys precede it: ties go to the lower index and the kept
+//     list comes out in ascending token order. A first sweep counts (greater, equal) per wavefront so
+//     that each one knows where its output starts.
 #include "qp_internal.h"
 
 namespace qp {
 
 constexpr int TOPK_THREADS = 1024;
+constexpr int TOPK_WAVES = TOPK_THREADS / 64;
+constexpr int SEL_BITS = 11;
+constexpr int SEL_NB = 1 << SEL_BITS;  // buckets per round, two per thread
+constexpr int SEL_LIST = 256;          // a bucket of at most this many keys is ranked directly
+constexpr int SEL_UNROLL = 2;          // independent loads per thread and loop trip
+constexpr int SEL_MAX_ROUNDS = 4;      // 3 suffice for 32-bit keys; the bound makes termination explicit
 constexpr int GATHER_THREADS = 256;
 constexpr int GATHER_UNROLL = 4;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+static_assert(SEL_NB == 2 * TOPK_THREADS, "two buckets per thread");
 
 __device__ __forceinline__ uint32_t order_key(float s) {
   s += 0.f;  // -0.0 -> +0.0 so that the two zeros tie
@@ -33,116 +47,192 @@ __device__ __forceinline__ uint32_t order_key(float s) {
 
 __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(TopkArgs a, int32_t* __restrict__ kept_out) {
   extern __shared__ uint32_t keys[];  // [n_g]
-  __shared__ __attribute__((aligned(16))) uint32_t hist[256];
-  __shared__ uint32_t wave_gt[TOPK_THREADS / 64], wave_eq[TOPK_THREADS / 64];
-  __shared__ uint32_t sel_prefix, sel_need;
+  __shared__ __attribute__((aligned(8))) uint32_t hist[SEL_NB];
+  __shared__ uint32_t list[SEL_LIST];
+  __shared__ uint32_t wave_a[TOPK_WAVES], wave_b[TOPK_WAVES], wave_min[TOPK_WAVES], wave_max[TOPK_WAVES];
+  __shared__ uint32_t sel_bucket, sel_need, sel_count, sel_key, list_n;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int h = blockIdx.x;
-  const float* s = a.scores + (size_t)h * a.n_g;
-  for (int j = tid; j < a.n_g; j += TOPK_THREADS) keys[j] = order_key(s[j]);
-  if (tid == 0) {
-    sel_prefix = 0;
-    sel_need = (uint32_t)a.keep;
-  }
-  __syncthreads();
-
-  const int n_round = (a.n_g + TOPK_THREADS - 1) / TOPK_THREADS * TOPK_THREADS;  // whole wavefronts take part
-  uint32_t mask = 0;
-  for (int pass = 0; pass < 4; ++pass) {
-    const int shift = 24 - 8 * pass;
-    if (tid < 256) hist[tid] = 0;
-    __syncthreads();
-    const uint32_t prefix = sel_prefix;
-    for (int j = tid; j < n_round; j += TOPK_THREADS) {
-      const uint32_t key = j < a.n_g ? keys[j] : 0u;
-      bool act = j < a.n_g && (key & mask) == prefix;
-      const uint32_t bin = (key >> shift) & 255u;
-      // aggregate the two most common digits of this wavefront's batch, plain atomics for the rest
+  const int h = blockIdx.x, n = a.n_g;
+  const float* s = a.scores + (size_t)h * n;
+  uint32_t kmin = 0xffffffffu, kmax = 0u;
+  for (int j0 = tid; j0 < n; j0 += SEL_UNROLL * TOPK_THREADS) {
+    float f[SEL_UNROLL];
 #pragma unroll
-      for (int it = 0; it < 2; ++it) {
+    for (int u = 0; u < SEL_UNROLL; ++u) f[u] = j0 + u * TOPK_THREADS < n ? s[j0 + u * TOPK_THREADS] : 0.f;
+#pragma unroll
+    for (int u = 0; u < SEL_UNROLL; ++u)
+      if (j0 + u * TOPK_THREADS < n) {
+        const uint32_t key = order_key(f[u]);
+        keys[j0 + u * TOPK_THREADS] = key;
+        kmin = min(kmin, key);
+        kmax = max(kmax, key);
+      }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, 64));
+    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, 64));
+  }
+  if (lane == 0) {
+    wave_min[wave] = kmin;
+    wave_max[wave] = kmax;
+  }
+  hist[2 * tid] = 0;
+  hist[2 * tid + 1] = 0;
+  if (tid == 0) list_n = 0;
+  __syncthreads();
+  uint32_t lo = 0xffffffffu, hi = 0u;
+#pragma unroll
+  for (int w = 0; w < TOPK_WAVES; ++w) {  // wavefronts without keys hold the identities
+    lo = min(lo, wave_min[w]);
+    hi = max(hi, wave_max[w]);
+  }
+
+  const int n_round = (n + TOPK_THREADS - 1) / TOPK_THREADS * TOPK_THREADS;  // whole wavefronts take part
+  uint32_t span = hi - lo;          // keys still in play: lo <= key <= lo + span
+  uint32_t need = (uint32_t)a.keep; // rank of T among them, counted from the largest
+  uint32_t thr = lo;
+  for (int round = 0; round < SEL_MAX_ROUNDS; ++round) {
+    const int bits = span ? 32 - __builtin_clz(span) : 0;
+    const int sh = bits > SEL_BITS ? bits - SEL_BITS : 0;
+    for (int j0 = tid; j0 < n_round; j0 += SEL_UNROLL * TOPK_THREADS) {
+      uint32_t kk[SEL_UNROLL];
+#pragma unroll
+      for (int u = 0; u < SEL_UNROLL; ++u) kk[u] = j0 + u * TOPK_THREADS < n ? keys[j0 + u * TOPK_THREADS] : 0u;
+#pragma unroll
+      for (int u = 0; u < SEL_UNROLL; ++u) {
+        const int j = j0 + u * TOPK_THREADS;  // j >= n_round only when j >= n: such a batch has no active lane
+        const uint32_t off = kk[u] - lo;
+        bool act = j < n && off <= span;  // a key below lo wraps to a large offset
+        const uint32_t bin = off >> sh;
         const unsigned long long am = __ballot(act);
-        if (am == 0) break;
-        const int leader = __ffsll((long long)am) - 1;
-        const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);
-        const bool mine = act && bin == b0;
-        const unsigned long long same = __ballot(mine);
-        if (lane == leader) atomicAdd(&hist[b0], (uint32_t)__popcll(same));
-        if (mine) act = false;
-      }
-      if (act) atomicAdd(&hist[bin], 1u);
-    }
-    __syncthreads();
-    // Wavefront 0 finds the bin of the k-th largest key: lane l owns bins 4l..4l+3; suffix sums (number of
-    // matching keys with digit >= b) come from an in-lane sum plus a suffix scan over the lanes.
-    if (tid < 64) {
-      const uint32_t need = sel_need;
-      const uint4 hb = *(const uint4*)&hist[4 * tid];
-      const uint32_t s3 = hb.w, s2 = s3 + hb.z, s1 = s2 + hb.y, s0 = s1 + hb.x;
-      uint32_t above = s0;  // inclusive suffix over lanes
-#pragma unroll
-      for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t t = __shfl_down(above, o, 64);
-        if (tid + o < 64) above += t;
-      }
-      above -= s0;  // keys in bins owned by higher lanes
-      const uint32_t suf[5] = {above + s0, above + s1, above + s2, above + s3, above};
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (suf[j] >= need && suf[j + 1] < need) {  // true for exactly one (lane, j)
-          sel_prefix = prefix | ((uint32_t)(4 * tid + j) << shift);
-          sel_need = need - suf[j + 1];
+        if (am != 0) {  // fold the first active lane's bucket when many lanes share it
+          const int leader = __ffsll((long long)am) - 1;
+          const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);
+          const bool mine = act && bin == b0;
+          const unsigned long long same = __ballot(mine);
+          if (__popcll(same) >= 8) {
+            if (lane == leader) atomicAdd(&hist[b0], (uint32_t)__popcll(same));
+            if (mine) act = false;
+          }
         }
+        if (act) atomicAdd(&hist[bin], 1u);
+      }
     }
-    mask |= 255u << shift;
     __syncthreads();
-  }
-  const uint32_t thr = sel_prefix;  // the k-th largest key
-  const uint32_t need = sel_need;   // how many keys equal to it survive (>= 1)
-
-  // ordered compaction over contiguous chunks of tokens
-  const int per = (a.n_g + TOPK_THREADS - 1) / TOPK_THREADS;
-  const int j0 = tid * per, j1 = min(j0 + per, a.n_g);
-  uint32_t gt = 0, eq = 0;
-  for (int j = j0; j < j1; ++j) {
-    const uint32_t key = keys[j];
-    gt += key > thr;
-    eq += key == thr;
-  }
-  uint32_t gt_inc = gt, eq_inc = eq;  // inclusive scan inside the wave
+    // suffix sums over the buckets: this thread owns buckets 2 tid and 2 tid + 1 (and clears them for a next round)
+    const uint2 hb = *(const uint2*)&hist[2 * tid];
+    *(uint2*)&hist[2 * tid] = make_uint2(0u, 0u);
+    const uint32_t own = hb.x + hb.y;
+    uint32_t suf = own;  // inclusive suffix over the wavefront's lanes
 #pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t g2 = __shfl_up(gt_inc, o, 64), e2 = __shfl_up(eq_inc, o, 64);
-    if (lane >= o) {
-      gt_inc += g2;
-      eq_inc += e2;
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t t = __shfl_down(suf, o, 64);
+      if (lane + o < 64) suf += t;
+    }
+    if (lane == 0) wave_a[wave] = suf;
+    __syncthreads();
+    uint32_t above = suf - own;  // keys in buckets above 2 tid + 1
+#pragma unroll
+    for (int w = 1; w < TOPK_WAVES; ++w) above += w > wave ? wave_a[w] : 0u;
+    const uint32_t suf1 = above + hb.y, suf0 = suf1 + hb.x;
+    if (suf1 >= need && above < need) {  // exactly one (thread, bucket) holds the crossing
+      sel_bucket = 2 * tid + 1;
+      sel_need = need - above;
+      sel_count = hb.y;
+    } else if (suf0 >= need && suf1 < need) {
+      sel_bucket = 2 * tid;
+      sel_need = need - suf1;
+      sel_count = hb.x;
+    }
+    __syncthreads();
+    const uint32_t first = sel_bucket << sh;  // offset of the chosen bucket's first key
+    need = sel_need;
+    const uint32_t count = sel_count;
+    lo += first;
+    span = min(span - first, (sh ? (1u << sh) : 1u) - 1u);
+    thr = lo;
+    if (sh == 0) break;  // buckets were single keys: T = lo, `need` of its copies survive
+    if (count <= SEL_LIST) {
+      // rank the bucket's keys directly
+      for (int j = tid; j < n; j += TOPK_THREADS) {
+        const uint32_t key = keys[j];
+        if (key - lo <= span) {
+          const uint32_t p = atomicAdd(&list_n, 1u);
+          if (p < (uint32_t)SEL_LIST) list[p] = key;  // always true: the bucket holds `count` keys
+        }
+      }
+      __syncthreads();
+      if (tid < (int)count) {
+        const uint32_t x = list[tid];
+        uint32_t g = 0, e = 0;
+        for (uint32_t m = 0; m < count; ++m) {
+          const uint32_t y = list[m];
+          g += y > x;
+          e += y == x;
+        }
+        if (g < need && need <= g + e) {  // equal candidates write the same values
+          sel_key = x;
+          sel_need = need - g;
+        }
+      }
+      __syncthreads();
+      thr = sel_key;
+      need = sel_need;
+      break;
     }
   }
-  if (lane == 63) {
-    wave_gt[wave] = gt_inc;
-    wave_eq[wave] = eq_inc;
+  // thr: the k-th largest key; need: how many keys equal to it survive (>= 1)
+
+  // emit, wavefront by wavefront over contiguous runs of tokens
+  const int run = ((n + TOPK_WAVES - 1) / TOPK_WAVES + 63) / 64 * 64;
+  const int j_begin = min(wave * run, n), j_end = min(j_begin + run, n);
+  uint32_t gt_w = 0, eq_w = 0;
+  for (int j0 = j_begin; j0 < j_end; j0 += 64 * SEL_UNROLL) {
+    uint32_t kk[SEL_UNROLL];
+#pragma unroll
+    for (int u = 0; u < SEL_UNROLL; ++u) kk[u] = j0 + 64 * u + lane < j_end ? keys[j0 + 64 * u + lane] : 0u;
+#pragma unroll
+    for (int u = 0; u < SEL_UNROLL; ++u) {
+      const bool in = j0 + 64 * u + lane < j_end;
+      gt_w += (uint32_t)__popcll(__ballot(in && kk[u] > thr));
+      eq_w += (uint32_t)__popcll(__ballot(in && kk[u] == thr));
+    }
+  }
+  if (lane == 0) {
+    wave_a[wave] = gt_w;
+    wave_b[wave] = eq_w;
   }
   __syncthreads();
-  uint32_t gt_before = gt_inc - gt, eq_before = eq_inc - eq;
-  for (int w = 0; w < wave; ++w) {
-    gt_before += wave_gt[w];
-    eq_before += wave_eq[w];
+  uint32_t gt_before = 0, eq_run = 0;
+#pragma unroll
+  for (int w = 0; w < TOPK_WAVES - 1; ++w) {
+    gt_before += w < wave ? wave_a[w] : 0u;
+    eq_run += w < wave ? wave_b[w] : 0u;
   }
+  uint32_t out_run = gt_before + min(eq_run, need);
   int32_t* kept = kept_out + (size_t)h * a.keep;
   int32_t* pos = a.pos + (size_t)h * a.cap + a.len;
-  for (int j = j0; j < j1; ++j) {
-    const uint32_t key = keys[j];
-    int slot = -1;
-    if (key > thr) {
-      slot = (int)(gt_before + min(eq_before, need));
-      ++gt_before;
-    } else if (key == thr) {
-      if (eq_before < need) slot = (int)(gt_before + eq_before);
-      ++eq_before;
-    }
-    if (slot >= 0) {
-      kept[slot] = j;
-      pos[slot] = a.base + j;
+  const unsigned long long below = (1ull << lane) - 1ull;  // lanes before this one
+  for (int j0 = j_begin; j0 < j_end; j0 += 64 * SEL_UNROLL) {
+    uint32_t kk[SEL_UNROLL];
+#pragma unroll
+    for (int u = 0; u < SEL_UNROLL; ++u) kk[u] = j0 + 64 * u + lane < j_end ? keys[j0 + 64 * u + lane] : 0u;
+#pragma unroll
+    for (int u = 0; u < SEL_UNROLL; ++u) {
+      const int j = j0 + 64 * u + lane;
+      const bool is_eq = j < j_end && kk[u] == thr;
+      const unsigned long long be = __ballot(is_eq);
+      const bool keep_it = (j < j_end && kk[u] > thr) || (is_eq && eq_run + (uint32_t)__popcll(be & below) < need);
+      const unsigned long long bs = __ballot(keep_it);
+      const uint32_t slot = out_run + (uint32_t)__popcll(bs & below);
+      if (keep_it && slot < (uint32_t)a.keep) {  // slot < keep always holds; the check keeps the stores in bounds
+        kept[slot] = j;
+        pos[slot] = a.base + j;
+      }
+      out_run += (uint32_t)__popcll(bs);
+      eq_run += (uint32_t)__popcll(be);
     }
   }
 }
