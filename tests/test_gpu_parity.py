@@ -144,6 +144,59 @@ def test_topk_compact_exact(dtype, h_kv, d, n_g, keep, ties):
         assert (ck[h, :pre] == 0).all() and (ck[h, pre + keep:] == 0).all()
 
 
+def _score_families(n_g, g):
+    """Score vectors that drive the selection through each of its routes (one KV head per family)."""
+    base = torch.rand(n_g, generator=g)
+    fams = {}
+    # adjacent floats: the whole key range is narrower than one round of buckets
+    fams["adjacent"] = torch.from_numpy(
+        (np.float32(1.0).view(np.int32) + torch.randint(0, 1500, (n_g,), generator=g).numpy().astype(np.int32))
+        .view(np.float32).copy())
+    # two far outliers stretch the range so that nearly all keys share a bucket: needs further rounds
+    dense = 3.0 + base * 1e-3
+    dense[n_g // 3] = 1e30
+    dense[n_g // 2] = -1e30
+    fams["dense_with_outliers"] = dense
+    # both signs, both zeros, and far more ties at the threshold than the direct-ranking list holds
+    mixed = torch.where(base < 0.2, torch.tensor(-2.5), torch.where(base < 0.7, torch.tensor(0.0), torch.tensor(7.0)))
+    mixed[::5] = -0.0
+    fams["signs_and_zeros"] = mixed
+    # infinities at both ends and a log-uniform body over 60 octaves
+    wide = torch.exp2((base - 0.5) * 60.0) * torch.where(torch.rand(n_g, generator=g) < 0.5, -1.0, 1.0)
+    wide[0], wide[n_g - 1] = float("inf"), float("-inf")
+    fams["wide_with_inf"] = wide
+    return fams
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("n_g", [700, 2048, 8192, 32768])
+@pytest.mark.parametrize("keep_frac", [0.0, 0.1, 0.5, 1.0])
+def test_topk_select_routes(n_g, keep_frac):
+    """Eq. 2's TopK on score distributions chosen for the selection's branches (exact bucket, repeated rounds,
+    direct ranking, ties beyond the list): kept indices are bit-exact against the oracle's stable selection."""
+    keep = min(n_g, max(1, int(round(keep_frac * n_g))))
+    print(f"case n_g={n_g} keep={keep}", flush=True)
+    g = torch.Generator().manual_seed(n_g + keep)
+    fams = _score_families(n_g, g)
+    s = torch.stack(list(fams.values())).float().contiguous()
+    h_kv, d = s.shape[0], 64
+    k = torch.randn(n_g, h_kv, d, generator=g)
+    v = torch.randn(n_g, h_kv, d, generator=g)
+    layout = B.make_layout(h_kv, h_kv, d, "f32")
+    cache = B.Cache(layout, keep)
+    kept = torch.full((h_kv, keep), -1, dtype=torch.int32, device=DEV)
+    B.topk_compact(layout, s.to(DEV), k.to(DEV), v.to(DEV), keep, 0, cache, kept)
+    torch.cuda.synchronize()
+    want = O.topk_select(s.double().numpy(), keep)
+    got = kept.cpu().numpy()
+    for h, name in enumerate(fams):
+        np.testing.assert_array_equal(got[h], want[h], err_msg=name)
+    np.testing.assert_array_equal(cache.pos.cpu().numpy()[:, :keep], want)
+    ck = cache.k.cpu()
+    for h in range(h_kv):
+        assert torch.equal(ck[h, :keep], k[torch.from_numpy(want[h]), h])
+
+
 # --------------------------------------------------------------------------------------------- whole path
 def _run_prefill(w, q, k, v, qw, rule, kernel=B.QP_ATTEND_AUTO):
     layout = B.make_layout(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
