@@ -99,6 +99,40 @@ def characterise_hbm(torch, B, reps=6):
     return out
 
 
+def characterise_after_prefill(torch, B, w, layout, cache, ws, reps=50):
+    """The stages that consume the pruned cache (Sec. 2.1: text-token prefill, then decoding), through the same
+    qp_group_attend: a chunk of W text tokens and a single token against the layer's final cache. Few rows
+    against a long cache: HBM-bound on the cache's K and V; the kernel splits the cache over key chunks."""
+    out = {}
+    d, esz = w.head_dim, 2
+    c = cache.len
+    for name, n_g in (("decode_1_token", 1), ("text_prefill_%d_tokens" % max(w.n_window, 64), max(w.n_window, 64))):
+        q = torch.randn(n_g, w.n_q_heads, d, device="cuda").to(torch.bfloat16) / d ** 0.5
+        k = torch.randn(n_g, w.n_kv_heads, d, device="cuda").to(torch.bfloat16) / d ** 0.5
+        v = torch.randn(n_g, w.n_kv_heads, d, device="cuda").to(torch.bfloat16)
+        o = torch.empty_like(q)
+        res = {}
+        for label, scratch in (("us", ws), ("us_without_key_split", None)):
+            for _ in range(3):
+                B.group_attend(layout, q, k, v, cache, o, None, scratch)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                B.group_attend(layout, q, k, v, cache, o, None, scratch)
+            e1.record()
+            torch.cuda.synchronize()
+            res[label] = e0.elapsed_time(e1) * 1e3 / reps
+        nbytes = 2 * w.n_kv_heads * (c + n_g) * d * esz + 2 * n_g * w.n_q_heads * d * esz
+        flops = 4.0 * d * w.n_q_heads * (n_g * c + n_g * (n_g + 1) / 2)
+        t = res["us"] * 1e-6
+        res.update({"cache_len": c, "bytes": nbytes, "GBps": nbytes / t / 1e9,
+                    "frac_of_hbm_peak": nbytes / t / 1e9 / PEAK_HBM_GBS, "TFLOPs": flops / t / 1e12})
+        out[name] = res
+    out["note"] = "one layer's cache is a few tens of MB and stays in the 256 MB Infinity Cache between repeats"
+    return out
+
+
 def cpu_baseline(w, q, k, v, qw, rule):
     """The oracle on the host: all groups scored and selected, a sample of groups attended in full."""
     import numpy as np  # noqa: F401
@@ -276,6 +310,8 @@ def main():
     cal_dst.copy_(cal_src)
     torch.cuda.synchronize()
     result["stages"]["hbm_characterisation"] = characterise_hbm(torch, B)
+    if w.dtype == "bf16":
+        result["stages"]["after_prefill"] = characterise_after_prefill(torch, B, w, layout, cache, ws)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, q, k, v, qwin, rule)
     print(json.dumps(result))

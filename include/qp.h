@@ -94,7 +94,8 @@ int64_t qp_keep_count(int64_t n_group_tokens, double retention);
 int64_t qp_cache_capacity(int32_t n_frames, int32_t tokens_per_frame, int32_t group_frames, double retention);
 
 /* Bytes of workspace that every entry point accepts for groups of at most max_group_tokens
- * tokens and a query window of n_window rows. 0 on bad arguments. */
+ * tokens and a query window of n_window rows (includes 2 x 32 MiB of key-split scratch for the
+ * attention launches of qp_prefill_video). 0 on bad arguments. */
 size_t qp_workspace_bytes(const qp_layout* layout, int32_t max_group_tokens, int32_t n_window);
 
 /* ---- the hot path ----------------------------------------------------------------------- */
@@ -108,6 +109,14 @@ size_t qp_workspace_bytes(const qp_layout* layout, int32_t max_group_tokens, int
  * Row i of query head qh sees all cache entries of KV head qh/R and group tokens j <= i.
  * Arithmetic: products and sums in f32 (bf16 inputs are widened exactly; the MFMA kernel
  * rounds the softmax numerators to bf16 before the P.V product); output rounded to nearest even.
+ * The same call serves the stages that follow video prefill (Sec. 2.1: text-token prefill, then
+ * decoding): a text chunk or a single new token is a "group" of n_group_tokens >= 1 rows attending
+ * to the whole pruned cache plus itself.
+ *   workspace: optional device scratch (256-byte aligned), may be NULL. When a launch would have too
+ *     few rows to fill the GPU against a long cache, the MFMA kernel splits the cache over key chunks
+ *     and merges their partial results in a second launch; the partials ([chunks][rows][d+1] f32, as
+ *     many chunks as fit, at most 128) live in this scratch. Without scratch it never splits. Calls
+ *     that may overlap on different streams need distinct scratch.
  * Errors: INVALID_ARG (NULL/misaligned pointers, n_group_tokens <= 0, bad layout),
  * UNSUPPORTED (dtype/head_dim/group size). The cache is not modified. */
 qp_status qp_group_attend(const qp_layout* layout, const void* q_g, const void* k_g, const void* v_g,

@@ -47,6 +47,8 @@
 // this load, so overlapping phases lowers the clock instead of the time.)
 #include "qp_internal.h"
 
+#include <algorithm>
+
 namespace qp {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -69,6 +71,8 @@ constexpr int MF_STAGES = 3;            // ring of K+V tile slots
 constexpr float MF_RESCALE_LOG2 = 8.f;  // move the reference max only when it grows by more than 2^8
 constexpr int MF_VMCNT0 = 0x0f70;       // s_waitcnt vmcnt(0), other counters untouched
 constexpr int MF_VMCNT4 = 0x0f74;       // s_waitcnt vmcnt(4)
+constexpr int MF_SPLIT_BELOW = 128;     // launches of fewer workgroups split the cache over chunks
+constexpr int MF_MAX_SPLIT = 128;       // chunks at most
 
 // S^T (64 keys x 32 rows, two 32-key blocks) = K tile . Q^T. All 16 K fragments are read before the
 // first MFMA (a scheduling barrier keeps the compiler from sinking each read next to its use,
@@ -207,11 +211,10 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
   const bool wave_live = row0 < n_rows && !unpaired;
   const int n_ct = (a.c + MF_BN - 1) / MF_BN;       // cache tiles
   const int n_tiles = n_ct + t_wg_max / MF_BN + 1;  // + group tiles
-
-  // Q^T operand: 8 k-steps of 16 d; this lane holds d = 16 s + 8 g .. + 7 of its row
-  bf16x8 qf[8];
-#pragma unroll
-  for (int s = 0; s < 8; ++s) qf[s] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + 16 * s + 8 * g));
+  // key split: chunk blockIdx.y walks cache tiles [t_begin, t_end); the last chunk goes on through the group tiles
+  const int chunk = blockIdx.y;
+  const int t_begin = chunk * a.split_tiles;
+  const int t_end = chunk == a.n_split - 1 ? n_tiles : t_begin + a.split_tiles;
 
   const unsigned char* ck = (const unsigned char*)a.ck + (size_t)h * a.cap * (MF_D * 2);
   const unsigned char* cv = (const unsigned char*)a.cv + (size_t)h * a.cap * (MF_D * 2);
@@ -276,21 +279,25 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
   const int lim_local = in_cache ? a.c - 1 - (tile_)*MF_BN : t_lane - gt0; /* key_local <= lim_local */ \
   const bool need_mask = in_cache ? (a.c - (tile_)*MF_BN < MF_BN) : (gt0 + MF_BN - 1 > t_w_min);
 
-  // The Q fragments must have arrived before the first tile request: from here on the only vector-memory
-  // operations in flight are the tile requests, which the compiler does not see (it would otherwise
-  // re-wait for "pending" Q loads inside the loop and drain the tile requests with them).
-  __builtin_amdgcn_s_waitcnt(MF_VMCNT0);
   // each wavefront has 4 loads in flight per requested tile: vmcnt(4) = all but the newest tile have landed
-  QP_ISSUE(0, 0)
-  if (n_tiles > 1) QP_ISSUE(1, 1)
+  QP_ISSUE(t_begin, 0)
+  if (t_begin + 1 < t_end) QP_ISSUE(t_begin + 1, 1)
+  // Q^T operand: 8 k-steps of 16 d; this lane holds d = 16 s + 8 g .. + 7 of its row. Requested behind the first
+  // tiles so that the two latencies overlap (short key chunks are mostly prologue).
+  bf16x8 qf[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) qf[s] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + 16 * s + 8 * g));
+  // The Q fragments must have arrived before the loop: from there on the only vector-memory operations in flight
+  // are the tile requests, which the compiler does not see (it would otherwise re-wait for "pending" Q loads
+  // inside the loop and drain the tile requests with them).
   __builtin_amdgcn_s_waitcnt(MF_VMCNT0);
   __syncthreads();
 
   {
     int slot = 0, slot2 = 2;  // ring positions of tile and tile + 2
-    for (int tile = 0; tile < n_tiles; ++tile) {
+    for (int tile = t_begin; tile < t_end; ++tile) {
       // slot of tile+2 = slot of tile-1: every wavefront finished reading it before the last barrier
-      if (tile + 2 < n_tiles) QP_ISSUE(tile + 2, slot2)
+      if (tile + 2 < t_end) QP_ISSUE(tile + 2, slot2)
       QP_TILE_VIEW(tile)
       if (live) {
         const unsigned char* kt = smem + slot * MF_SLOT;
@@ -301,7 +308,7 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
         pv_tile(kt + MF_TILE, v_addr, pf, o);
       }
       // this wavefront's part of the next tile has landed in LDS (the tile after it may still be in flight)
-      if (tile + 2 < n_tiles) __builtin_amdgcn_s_waitcnt(MF_VMCNT4);
+      if (tile + 2 < t_end) __builtin_amdgcn_s_waitcnt(MF_VMCNT4);
       else __builtin_amdgcn_s_waitcnt(MF_VMCNT0);
       __syncthreads();
       slot = slot == STAGES - 1 ? 0 : slot + 1;
@@ -315,6 +322,19 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (!row_ok) return;
   const float inv = 1.f / l_tot;
+  if (a.n_split > 1) {
+    // partial result of this chunk: every chunk starts on a cache tile, whose keys all rows see, so l_tot > 0
+    const size_t prow = (size_t)chunk * ((size_t)a.h_kv * n_rows) + (size_t)h * n_rows + row;
+    float* po = a.part_o + prow * MF_D;
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4)
+        *(float4*)(po + 32 * n + 8 * q4 + 4 * g) = make_float4(o[n][4 * q4] * inv, o[n][4 * q4 + 1] * inv,
+                                                               o[n][4 * q4 + 2] * inv, o[n][4 * q4 + 3] * inv);
+    if (g == 0) a.part_lse[prow] = m_run * c2 + log2f(l_tot);
+    return;
+  }
   bf16_t* orow = (bf16_t*)a.out + ((size_t)t_lane * a.h_q + (size_t)h * r_heads + j_lane) * MF_D;
 #pragma unroll
   for (int n = 0; n < 4; ++n)
@@ -330,27 +350,105 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
     a.lse[(size_t)(h * r_heads + j_lane) * a.n_g + t_lane] = (m_run * c2 + log2f(l_tot)) * 0.6931471805599453f;
 }
 
+// Merge of the key split: out[row] = sum_c 2^(lse_c - lse) O_c[row], lse = log2 sum_c 2^lse_c. One workgroup per
+// row: wavefront w takes chunks w, w+4, ... (four loads in flight), lane l owns d = 2l, 2l+1; the four wavefronts'
+// sums meet in LDS.
+__global__ __launch_bounds__(256) void attend_merge_kernel(AttendArgs a) {
+  __shared__ float red[4][64][3];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r_heads = a.h_q / a.h_kv;
+  const int n_rows = a.n_g * r_heads;
+  const long total = (long)a.h_kv * n_rows;
+  const long grow = blockIdx.x;
+  const int h = (int)(grow / n_rows), row = (int)(grow - (long)h * n_rows);
+  const int t = row / r_heads, j = row - t * r_heads;
+  float mx = -INFINITY;  // every wavefront takes the max over all chunks: the same reference everywhere
+  for (int c = lane; c < a.n_split; c += 64) mx = fmaxf(mx, a.part_lse[(size_t)c * total + grow]);
+  mx = wave_max(mx);
+  float den = 0.f, acc0 = 0.f, acc1 = 0.f;
+  for (int c0 = wave; c0 < a.n_split; c0 += 16) {
+    float w[4];
+    float2 po[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int c = min(c0 + 4 * u, a.n_split - 1);
+      w[u] = c0 + 4 * u < a.n_split ? exp2f(a.part_lse[(size_t)c * total + grow] - mx) : 0.f;
+      po[u] = *(const float2*)(a.part_o + ((size_t)c * total + grow) * MF_D + 2 * lane);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      den += w[u];
+      acc0 = fmaf(w[u], po[u].x, acc0);
+      acc1 = fmaf(w[u], po[u].y, acc1);
+    }
+  }
+  red[wave][lane][0] = den;
+  red[wave][lane][1] = acc0;
+  red[wave][lane][2] = acc1;
+  __syncthreads();
+  if (wave != 0) return;
+#pragma unroll
+  for (int w = 1; w < 4; ++w) {
+    den += red[w][lane][0];
+    acc0 += red[w][lane][1];
+    acc1 += red[w][lane][2];
+  }
+  const float inv = 1.f / den;
+  bf16x2 pk;
+  pk[0] = (__bf16)(acc0 * inv);
+  pk[1] = (__bf16)(acc1 * inv);
+  bf16_t* orow = (bf16_t*)a.out + ((size_t)t * a.h_q + (size_t)h * r_heads + j) * MF_D;
+  *(uint32_t*)(orow + 2 * lane) = __builtin_bit_cast(uint32_t, pk);
+  if (a.lse != nullptr && lane == 0)
+    a.lse[(size_t)(h * r_heads + j) * a.n_g + t] = (mx + log2f(den)) * 0.6931471805599453f;
+}
+
 bool attend_mfma_supported(const AttendArgs& a, int dtype) {
   // 24-bit row and 32-bit byte offsets inside one head's cache / the group's K, V
   return dtype == QP_BF16 && a.d == MF_D && a.h_kv <= 65535 && (long long)a.cap * (MF_D * 2) < (1ll << 31) &&
          (long long)a.n_g * a.h_kv * (MF_D * 2) < (1ll << 31) && a.cap < (1 << 24);
 }
 
-void launch_attend_mfma(const AttendArgs& a, hipStream_t s) {
+void launch_attend_mfma(const AttendArgs& a_in, void* split_ws, size_t split_ws_bytes, hipStream_t s) {
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute((const void*)attend_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                               MF_STAGES * MF_SLOT);
     attr_set = true;
   }
+  AttendArgs a = a_in;
   const int n_rows = a.n_g * (a.h_q / a.h_kv);
   const int n_rb = ((n_rows + MF_HB - 1) / MF_HB + 1) / 2;
   int n_wg = n_rb * a.h_kv;
+  // Few rows against a long cache (text prefill, decode, small groups): split the cache over chunks so that the
+  // launch still covers the chip, about one workgroup per CU, at least two tiles per chunk.
+  a.n_split = 1;
+  a.split_tiles = 0;
+  a.part_o = nullptr;
+  a.part_lse = nullptr;
+  const int n_ct = (a.c + MF_BN - 1) / MF_BN;
+  const size_t per_split = (size_t)a.h_kv * n_rows * (MF_D + 1) * sizeof(float);
+  if (split_ws != nullptr && n_wg < MF_SPLIT_BELOW && n_ct >= 4) {
+    long want = (256 + n_wg - 1) / n_wg;
+    want = std::min<long>(want, n_ct / 2);
+    want = std::min<long>(want, MF_MAX_SPLIT);
+    want = std::min<long>(want, (long)(split_ws_bytes / per_split));
+    if (want >= 2) {
+      a.split_tiles = (n_ct + (int)want - 1) / (int)want;
+      a.n_split = (n_ct + a.split_tiles - 1) / a.split_tiles;  // every chunk starts on a cache tile
+      a.part_o = (float*)split_ws;
+      a.part_lse = a.part_o + (size_t)a.n_split * a.h_kv * n_rows * MF_D;
+    }
+  }
   if (8 % a.h_kv == 0) {
     const int per = 8 / a.h_kv;
     n_wg = (n_rb + per - 1) / per * 8;
   }
-  hipLaunchKernelGGL(attend_mfma_kernel, dim3(n_wg), dim3(MF_NT), MF_STAGES * MF_SLOT, s, a);
+  hipLaunchKernelGGL(attend_mfma_kernel, dim3(n_wg, a.n_split), dim3(MF_NT), MF_STAGES * MF_SLOT, s, a);
+  if (a.n_split > 1) {
+    const long total = (long)a.h_kv * n_rows;
+    hipLaunchKernelGGL(attend_merge_kernel, dim3((unsigned)total), dim3(256), 0, s, a);
+  }
 }
 
 }  // namespace qp

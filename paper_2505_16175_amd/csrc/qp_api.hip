@@ -63,6 +63,9 @@ qp_status finish(hipError_t launch_err) {
 //           group's kernel (a few heavy row blocks, and fewer workgroups than CUs at small groups) is
 //           filled by the next group's workgroups.
 // Both are forked from the caller's stream at entry and joined back into it before the call returns.
+// Scratch that qp_group_attend's key split may use (partial outputs of the chunks); qp_prefill_video keeps one
+// area per attention stream, so that two groups' attention launches in flight never share one.
+constexpr size_t kAttendSplitBytes = (size_t)32 << 20;
 constexpr int MAX_ATT_STREAMS = 2;  // attention streams in rotation, the caller's included (3 measured no better, 4 worse)
 struct SideStreams {
   hipStream_t score = nullptr, attend[MAX_ATT_STREAMS] = {};  // attend[0] is unused (the caller's stream)
@@ -119,6 +122,7 @@ size_t qp_workspace_bytes(const qp_layout* L, int32_t max_group_tokens, int32_t 
   size_t b = scores_bytes(L, max_group_tokens);
   b += qp::topk_workspace_bytes(L->n_kv_heads, max_group_tokens);
   b += qp::window_workspace_bytes(L->n_q_heads, L->n_kv_heads, max_group_tokens, n_window > 0 ? n_window : 1);
+  b += MAX_ATT_STREAMS * kAttendSplitBytes;  // key-split scratch of qp_group_attend, one per attention stream of qp_prefill_video
   return b + 256;
 }
 
@@ -131,12 +135,11 @@ qp_status qp_select_attend_kernel(int32_t which) {
 qp_status qp_group_attend(const qp_layout* L, const void* q_g, const void* k_g, const void* v_g, int32_t n_g,
                           const qp_cache* cache, void* out_g, float* lse, void* workspace, size_t workspace_bytes,
                           void* hip_stream) {
-  (void)workspace;
-  (void)workspace_bytes;
   qp_status st = check_layout(L);
   if (st != QP_OK) return st;
   if ((st = check_group(n_g)) != QP_OK) return st;
   if ((st = check_cache(cache, false)) != QP_OK) return st;
+  if (workspace && (((uintptr_t)workspace) & 255u)) return QP_ERR_INVALID_ARG;
   if (!q_g || !k_g || !v_g || !out_g) return QP_ERR_INVALID_ARG;
   if (!aligned16(q_g) || !aligned16(k_g) || !aligned16(v_g) || !aligned16(out_g)) return QP_ERR_INVALID_ARG;
   if (lse && (((uintptr_t)lse) & 3u)) return QP_ERR_INVALID_ARG;
@@ -160,7 +163,7 @@ qp_status qp_group_attend(const qp_layout* L, const void* q_g, const void* k_g, 
   hipStream_t s = (hipStream_t)hip_stream;
   const bool mfma_ok = qp::attend_mfma_supported(a, L->dtype);
   if (g_attend_kernel == QP_ATTEND_MFMA && !mfma_ok) return QP_ERR_UNSUPPORTED;
-  if (mfma_ok && g_attend_kernel != QP_ATTEND_SCALAR) qp::launch_attend_mfma(a, s);
+  if (mfma_ok && g_attend_kernel != QP_ATTEND_SCALAR) qp::launch_attend_mfma(a, workspace, workspace ? workspace_bytes : 0, s);
   else qp::launch_attend_scalar(a, L->dtype, s);
   return finish(hipSuccess);
 }
@@ -288,8 +291,9 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
   const size_t sb = scores_bytes(L, (int32_t)max_group);
   int32_t* kept_ws = (int32_t*)((char*)workspace + sb);
   const size_t kb = qp::topk_workspace_bytes(L->n_kv_heads, (int32_t)max_group);
-  void* ws2 = (char*)workspace + sb + kb;
-  const size_t ws2_bytes = workspace_bytes - sb - kb;
+  void* ws2 = (char*)workspace + sb + kb;  // window scratch, then the two key-split areas of the attention streams
+  const size_t ws2_bytes = workspace_bytes - sb - kb - MAX_ATT_STREAMS * kAttendSplitBytes;
+  char* split_ws = (char*)workspace + (workspace_bytes - MAX_ATT_STREAMS * kAttendSplitBytes) / 256 * 256;
 
   hipStream_t main_stream = (hipStream_t)hip_stream;
   const bool overlap = side_streams_ready();
@@ -313,7 +317,8 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
     const int ai = overlap ? gi % g_side.n_att : 0;
     hipStream_t att_stream = ai ? g_side.attend[ai] : main_stream;
     if (overlap && gi > 0) QP_HIP_OK(hipStreamWaitEvent(att_stream, g_side.compacted[(gi - 1) & 1], 0));
-    st = qp_group_attend(L, qg, kg, vg, n_g, cache, og, nullptr, ws2, ws2_bytes, (void*)att_stream);
+    st = qp_group_attend(L, qg, kg, vg, n_g, cache, og, nullptr, split_ws + ai * kAttendSplitBytes, kAttendSplitBytes,
+                         (void*)att_stream);
     if (st != QP_OK) break;
     // 2. score the group's new KV entries; 3. TopK + compaction into the cache (cache->len advances on the host).
     //    The appended rows [len, len+k) are disjoint from the rows [0, len) any attention kernel in flight reads.

@@ -98,12 +98,19 @@ struct AttendArgs {
   float* lse;         // [h_q][n_g] or nullptr
   int n_g, h_q, h_kv, d, c, cap;
   float scale_log2;   // softmax scale * log2(e)
+  // Key split of the MFMA kernel (few rows against a long cache): the cache tiles are dealt to n_split chunks of
+  // split_tiles tiles, the last chunk also takes the group's own tiles; every chunk leaves a normalised partial
+  // output and its log2-sum-exp, merged by a second launch. n_split == 1: no split, nothing below is used.
+  int n_split, split_tiles;
+  float* part_o;      // [n_split][h_kv * n_g * R][d] f32
+  float* part_lse;    // [n_split][h_kv * n_g * R]    f32, log2 units
 };
 
 // Launchers (defined next to their kernels). They only enqueue; hipGetLastError is checked by the caller.
 void launch_attend_scalar(const AttendArgs& a, int dtype, hipStream_t s);
 bool attend_mfma_supported(const AttendArgs& a, int dtype);
-void launch_attend_mfma(const AttendArgs& a, hipStream_t s);
+// split_ws / split_ws_bytes: optional scratch (256-byte aligned) for the key split; without it the kernel never splits
+void launch_attend_mfma(const AttendArgs& a, void* split_ws, size_t split_ws_bytes, hipStream_t s);
 
 void launch_score_norm(const void* x, int dtype, int n_g, int h_kv, int d, float sign, float* scores, hipStream_t s);
 

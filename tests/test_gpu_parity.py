@@ -62,6 +62,39 @@ def test_group_attend_matches_oracle(dtype, h_q, h_kv, d, n_g, c):
         assert cache.len == c
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("h_q,h_kv", [(28, 4), (64, 8), (6, 3)])
+@pytest.mark.parametrize("n_g,c", [(1, 9840), (1, 257), (64, 9840), (64, 5000), (7, 1031), (200, 3000), (1, 100)])
+def test_group_attend_key_split_matches_oracle(h_q, h_kv, n_g, c):
+    """Text-token prefill and decode over the pruned cache (Sec. 2.1, stages 2 and 3): few rows against a long
+    cache. With scratch the MFMA kernel splits the cache over key chunks and merges; the result must match the
+    oracle and the unsplit launch, output and log-sum-exp alike."""
+    print(f"case heads={h_q}/{h_kv} n_g={n_g} c={c}", flush=True)
+    d = 128
+    g = torch.Generator().manual_seed(31 * n_g + c + h_q)
+    mk = lambda *s: torch.randn(*s, generator=g).to(torch.bfloat16)
+    q, k, v = mk(n_g, h_q, d), mk(n_g, h_kv, d), mk(n_g, h_kv, d)
+    ck, cv = mk(h_kv, c + 3, d), mk(h_kv, c + 3, d)
+    want, want_lse = O.attend_group(_f64(q), _f64(k), _f64(v), _f64(ck)[:, :c], _f64(cv)[:, :c], return_lse=True)
+    layout = B.make_layout(h_q, h_kv, d, "bf16")
+    cache = B.Cache(layout, c + 3)
+    cache.k.copy_(ck)
+    cache.v.copy_(cv)
+    cache.c.len = c
+    ws = B.make_workspace(layout, max(n_g, 32), 0)
+    outs = []
+    for scratch in (ws, None):
+        out = torch.full((n_g, h_q, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+        lse = torch.full((h_q, n_g), float("nan"), dtype=torch.float32, device=DEV)
+        B.group_attend(layout, q.to(DEV), k.to(DEV), v.to(DEV), cache, out, lse, scratch)
+        torch.cuda.synchronize()
+        assert_attn_close(_f64(out), want, "bf16", "split" if scratch is not None else "unsplit")
+        np.testing.assert_allclose(_f64(lse), want_lse, rtol=2e-5, atol=2e-3)
+        outs.append(out.float().cpu())
+    # the two launches round the softmax numerators against different reference maxima: bf16-level agreement
+    assert (outs[0] - outs[1]).abs().max().item() <= 2e-2
+
+
 # --------------------------------------------------------------------------------------------- S2
 @pytest.mark.parametrize("dtype,h_kv,d", [("f32", 2, 64), ("bf16", 4, 128), ("bf16", 8, 64), ("f32", 3, 128)])
 @pytest.mark.parametrize("n_g", [1, 33, 2048, 5000])
@@ -275,6 +308,8 @@ def test_cfg1_tiny_whole_path(rule, sharp):
     ("cfg2_7b_32k", 12, 40, 5),          # ragged: last group 2 frames, group tokens 200 (not a tile multiple)
     ("cfg4_72b_128k", 6, 96, 2),
     ("cfg3_7b_128k_norm", 9, 64, 4),
+    ("cfg2_7b_32k", 40, 32, 1),          # one-frame groups against a growing cache: the attention's key split
+    ("cfg4_72b_128k", 30, 64, 1),        # engages on both attention streams of the call
 ])
 @pytest.mark.parametrize("sharp", [False, True])
 def test_reduced_configs_whole_path_full_oracle(name, frames, tokens_per_frame, group_frames, sharp):
