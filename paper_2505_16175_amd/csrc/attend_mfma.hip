@@ -6,11 +6,14 @@
 //
 // Mapping. The R query heads that share a KV head are stacked into one row space per KV head:
 // row r = t * R + j (j = query head inside the KV group), which is also the memory order of
-// Q_g[t][h*R + j][:]. A workgroup of 8 wavefronts owns 256 rows of one KV head, as two half blocks
-// of 128 consecutive rows: one from the early end of the group and its mirror from the late end, so
-// that all workgroups carry the same causal work (a launch of about one workgroup per CU then ends
-// everywhere at the same time instead of waiting for the latest tokens). Every K/V tile staged in
-// LDS is shared by all R query heads (GQA) and by both half blocks. The keys are walked as two segments, cache tiles first and then group tiles starting
+// Q_g[t][h*R + j][:]. A workgroup of 8 wavefronts owns 256 rows of one KV head; every K/V tile it
+// stages in LDS is shared by all R query heads (GQA). Two row mappings, chosen by the launcher:
+//   * more workgroups than CUs: 256 consecutive rows each, latest tokens (longest key range) first,
+//     so that the short workgroups fill the tail of the launch;
+//   * at most one workgroup per CU (all resident at once, the launch lasts as long as its longest
+//     workgroup): two half blocks of 128 consecutive rows each, one from the early end of the group
+//     and its mirror from the late end, so that all workgroups carry the same causal work.
+// The keys are walked as two segments, cache tiles first and then group tiles starting
 // at group token 0, so a tile never straddles the two sources; only the cache's last tile and the
 // group's diagonal tiles are masked, and a wavefront skips group tiles beyond its causal horizon.
 //
@@ -170,7 +173,7 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
   const int r_heads = a.h_q / a.h_kv;
   const int n_rows = a.n_g * r_heads;
   const int n_hb = (n_rows + MF_HB - 1) / MF_HB;  // half blocks of 128 rows
-  const int n_rb = (n_hb + 1) / 2;                // workgroups per KV head: one per pair of half blocks
+  const int n_rb = (n_hb + 1) / 2;                // workgroups per KV head (256 rows or a pair of half blocks)
   // workgroup id -> (KV head, row block): ids go round-robin over the 8 XCDs
   int h, rbi;
   {
@@ -189,14 +192,15 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
     }
   }
   if (rbi >= n_rb) return;        // padding workgroups of the XCD mapping (whole workgroup, before any barrier)
-  // Causal balance: the workgroup owns half block rbi (early tokens, short key range) and its mirror
-  // n_hb-1-rbi (late tokens, long key range), so every workgroup of a launch has the same amount of work.
-  // Wavefronts 0..3 take the early half block and 4..7 the late one: wavefronts w and w+4 share a SIMD,
-  // so each SIMD keeps one wavefront busy after the early rows have reached their causal horizon.
+  // Mirrored mapping: the workgroup owns half block rbi (early tokens, short key range) and its mirror
+  // n_hb-1-rbi (late tokens, long key range). Wavefronts 0..3 take the early half block and 4..7 the late one:
+  // wavefronts w and w+4 share a SIMD, so each SIMD keeps one wavefront busy after the early rows have reached
+  // their causal horizon. Consecutive mapping: half blocks 2 rb and 2 rb + 1 with rb counted from the late end.
   const int half = wave >> 2;
-  const int hb_late = n_hb - 1 - rbi;
-  const int hb = half ? hb_late : rbi;
-  const bool unpaired = half == 0 && rbi == hb_late;  // odd count: the middle half block is served as "late" only
+  const int hb_late = a.mirrored ? n_hb - 1 - rbi : min(2 * (n_rb - 1 - rbi) + 1, n_hb - 1);
+  const int hb_early = a.mirrored ? rbi : 2 * (n_rb - 1 - rbi);
+  const int hb = half ? hb_late : hb_early;
+  const bool unpaired = half == 0 && hb_early == hb_late;  // odd count: that half block is served as "late" only
   const int row0 = hb * MF_HB + (wave & 3) * 32;
   const int row = row0 + l32;
   const bool row_ok = row < n_rows;
@@ -416,10 +420,20 @@ void launch_attend_mfma(const AttendArgs& a_in, void* split_ws, size_t split_ws_
                               MF_STAGES * MF_SLOT);
     attr_set = true;
   }
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      n_cu = v;
+    else
+      n_cu = 256;
+  }
   AttendArgs a = a_in;
   const int n_rows = a.n_g * (a.h_q / a.h_kv);
   const int n_rb = ((n_rows + MF_HB - 1) / MF_HB + 1) / 2;
   int n_wg = n_rb * a.h_kv;
+  a.mirrored = n_wg <= n_cu;  // all workgroups resident at once: balance them; otherwise longest first
   // Few rows against a long cache (text prefill, decode, small groups): split the cache over chunks so that the
   // launch still covers the chip, about one workgroup per CU, at least two tiles per chunk.
   a.n_split = 1;

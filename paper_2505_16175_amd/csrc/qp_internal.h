@@ -102,6 +102,7 @@ struct AttendArgs {
   // split_tiles tiles, the last chunk also takes the group's own tiles; every chunk leaves a normalised partial
   // output and its log2-sum-exp, merged by a second launch. n_split == 1: no split, nothing below is used.
   int n_split, split_tiles;
+  int mirrored;       // MFMA kernel's row mapping: 1 = mirrored half blocks (balanced), 0 = consecutive, longest first
   float* part_o;      // [n_split][h_kv * n_g * R][d] f32
   float* part_lse;    // [n_split][h_kv * n_g * R]    f32, log2 units
 };
