@@ -157,16 +157,36 @@ qp_status qp_topk_compact(const qp_layout* layout, const float* scores, const vo
  *   out [N][H_q][d]
  * All arguments are validated before the first launch. Scoring and compaction of a group do not
  * depend on its attention, and the attention of group g+1 depends on the compaction of group g but
- * not on the attention of group g; the call uses two library-owned streams (created on first use,
- * default priority) for the scoring/compaction chain and for every other group's attention. They are
- * forked from hip_stream at entry and joined back into it before the call returns: work the
- * caller enqueues on hip_stream afterwards is ordered after all of this call's work. */
+ * not on the attention of group g; the call uses two library-owned streams per device (created on
+ * first use on the current device, default priority) for the scoring/compaction chain and for every
+ * other group's attention. They are forked from hip_stream at entry and joined back into it before
+ * the call returns: work the caller enqueues on hip_stream afterwards is ordered after all of this
+ * call's work. The call only enqueues (it never waits for the GPU); calls from several host threads
+ * are serialised while they enqueue, because they share those streams. */
 qp_status qp_prefill_video(const qp_layout* layout, int32_t n_frames, int32_t tokens_per_frame,
                            int32_t group_frames, double retention, qp_score_rule rule, const void* q,
                            const void* k, const void* v, const void* q_win, int32_t n_window, qp_cache* cache,
                            void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ---- control / diagnostics ------------------------------------------------------------------ */
+
+/* How qp_group_attend would lay out a call (host arithmetic only, nothing is launched): which kernel,
+ * how many workgroups, whether the cache is split over key chunks (key_chunks > 1: two launches, the
+ * second merges the chunks' partial results; tiles_per_chunk counts 64-key cache tiles), whether rows
+ * are dealt to workgroups as mirrored early/late half blocks (launches of at most one workgroup per
+ * compute unit) or consecutively, and how much of the offered workspace the split would use.
+ * For the scalar kernel only `kernel` and key_chunks = 1 are meaningful. */
+typedef struct {
+  int32_t kernel;          /* QP_ATTEND_SCALAR or QP_ATTEND_MFMA */
+  int32_t workgroups;      /* per key chunk, including idle padding workgroups */
+  int32_t key_chunks;
+  int32_t tiles_per_chunk; /* 0 when key_chunks == 1 */
+  int32_t mirrored_rows;
+  size_t scratch_bytes;
+} qp_attend_plan_info;
+qp_status qp_attend_plan(const qp_layout* layout, int32_t n_group_tokens, int32_t cache_len,
+                         size_t workspace_bytes, qp_attend_plan_info* out);
+
 
 /* Choose the attention kernel for later qp_group_attend / qp_prefill_video calls of this
  * process (tests use it to cover both). Returns INVALID_ARG for an unknown value. */

@@ -33,6 +33,12 @@ class qp_cache(ctypes.Structure):
                 ("capacity", ctypes.c_int32), ("len", ctypes.c_int32)]
 
 
+class qp_attend_plan_info(ctypes.Structure):
+    _fields_ = [("kernel", ctypes.c_int32), ("workgroups", ctypes.c_int32), ("key_chunks", ctypes.c_int32),
+                ("tiles_per_chunk", ctypes.c_int32), ("mirrored_rows", ctypes.c_int32),
+                ("scratch_bytes", ctypes.c_size_t)]
+
+
 class QPError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
@@ -51,6 +57,7 @@ SIGNATURES = {
     "qp_score_kv": (_i32, [_LP, _i32, _vp, _vp, _i32, _vp, _i32, _vp, _vp, _sz, _vp]),
     "qp_topk_compact": (_i32, [_LP, _vp, _vp, _vp, _i32, _i32, _i32, _CP, _vp, _vp, _sz, _vp]),
     "qp_prefill_video": (_i32, [_LP, _i32, _i32, _i32, _f64, _i32, _vp, _vp, _vp, _vp, _i32, _CP, _vp, _vp, _sz, _vp]),
+    "qp_attend_plan": (_i32, [_LP, _i32, _i32, _sz, ctypes.POINTER(qp_attend_plan_info)]),
     "qp_select_attend_kernel": (_i32, [_i32]),
     "qp_status_string": (ctypes.c_char_p, [_i32]),
     "qp_last_hip_error": (ctypes.c_int, []),
@@ -146,6 +153,13 @@ def make_workspace(layout, max_group_tokens, n_window, device="cuda") -> torch.T
     if n == 0:
         raise QPError(QP_ERR_INVALID_ARG, "qp_workspace_bytes")
     return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def attend_plan(layout, n_group_tokens, cache_len, workspace_bytes=0) -> dict:
+    info = qp_attend_plan_info()
+    _check(lib().qp_attend_plan(ctypes.byref(layout), n_group_tokens, cache_len, workspace_bytes, ctypes.byref(info)),
+           "qp_attend_plan")
+    return {name: getattr(info, name) for name, _ in qp_attend_plan_info._fields_}
 
 
 def select_attend_kernel(which: int):

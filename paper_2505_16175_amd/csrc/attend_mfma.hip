@@ -413,54 +413,61 @@ bool attend_mfma_supported(const AttendArgs& a, int dtype) {
          (long long)a.n_g * a.h_kv * (MF_D * 2) < (1ll << 31) && a.cap < (1 << 24);
 }
 
-void launch_attend_mfma(const AttendArgs& a_in, void* split_ws, size_t split_ws_bytes, hipStream_t s) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)attend_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              MF_STAGES * MF_SLOT);
-    attr_set = true;
-  }
-  static int n_cu = 0;
-  if (n_cu == 0) {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-      n_cu = v;
-    else
-      n_cu = 256;
-  }
-  AttendArgs a = a_in;
+AttendPlan plan_attend_mfma(const AttendArgs& a, size_t split_ws_bytes) {
+  AttendPlan p;
   const int n_rows = a.n_g * (a.h_q / a.h_kv);
   const int n_rb = ((n_rows + MF_HB - 1) / MF_HB + 1) / 2;
-  int n_wg = n_rb * a.h_kv;
-  a.mirrored = n_wg <= n_cu;  // all workgroups resident at once: balance them; otherwise longest first
+  const int n_wg = n_rb * a.h_kv;
+  p.mirrored = n_wg <= device_cu_count();  // all workgroups resident at once: balance them; otherwise longest first
   // Few rows against a long cache (text prefill, decode, small groups): split the cache over chunks so that the
   // launch still covers the chip, about one workgroup per CU, at least two tiles per chunk.
-  a.n_split = 1;
-  a.split_tiles = 0;
-  a.part_o = nullptr;
-  a.part_lse = nullptr;
+  p.n_split = 1;
+  p.split_tiles = 0;
+  p.scratch_bytes = 0;
   const int n_ct = (a.c + MF_BN - 1) / MF_BN;
   const size_t per_split = (size_t)a.h_kv * n_rows * (MF_D + 1) * sizeof(float);
-  if (split_ws != nullptr && n_wg < MF_SPLIT_BELOW && n_ct >= 4) {
+  if (split_ws_bytes > 0 && n_wg < MF_SPLIT_BELOW && n_ct >= 4) {
     long want = (256 + n_wg - 1) / n_wg;
     want = std::min<long>(want, n_ct / 2);
     want = std::min<long>(want, MF_MAX_SPLIT);
     want = std::min<long>(want, (long)(split_ws_bytes / per_split));
     if (want >= 2) {
-      a.split_tiles = (n_ct + (int)want - 1) / (int)want;
-      a.n_split = (n_ct + a.split_tiles - 1) / a.split_tiles;  // every chunk starts on a cache tile
-      a.part_o = (float*)split_ws;
-      a.part_lse = a.part_o + (size_t)a.n_split * a.h_kv * n_rows * MF_D;
+      p.split_tiles = (n_ct + (int)want - 1) / (int)want;
+      p.n_split = (n_ct + p.split_tiles - 1) / p.split_tiles;  // every chunk starts on a cache tile
+      p.scratch_bytes = (size_t)p.n_split * per_split;
     }
   }
+  p.workgroups = n_wg;
   if (8 % a.h_kv == 0) {
     const int per = 8 / a.h_kv;
-    n_wg = (n_rb + per - 1) / per * 8;
+    p.workgroups = (n_rb + per - 1) / per * 8;
   }
-  hipLaunchKernelGGL(attend_mfma_kernel, dim3(n_wg, a.n_split), dim3(MF_NT), MF_STAGES * MF_SLOT, s, a);
-  if (a.n_split > 1) {
-    const long total = (long)a.h_kv * n_rows;
+  return p;
+}
+
+void launch_attend_mfma(const AttendArgs& a_in, void* split_ws, size_t split_ws_bytes, hipStream_t s) {
+  static bool attr_set[QP_MAX_DEVICES] = {};
+  const int dev = current_device();
+  if (dev < 0 || !attr_set[dev]) {
+    (void)hipFuncSetAttribute((const void*)attend_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              MF_STAGES * MF_SLOT);
+    if (dev >= 0) attr_set[dev] = true;
+  }
+  AttendArgs a = a_in;
+  const AttendPlan p = plan_attend_mfma(a, split_ws != nullptr ? split_ws_bytes : 0);
+  a.mirrored = p.mirrored;
+  a.n_split = p.n_split;
+  a.split_tiles = p.split_tiles;
+  a.part_o = nullptr;
+  a.part_lse = nullptr;
+  if (p.n_split > 1) {
+    const size_t rows_total = (size_t)a.h_kv * a.n_g * (a.h_q / a.h_kv);
+    a.part_o = (float*)split_ws;
+    a.part_lse = a.part_o + (size_t)p.n_split * rows_total * MF_D;
+  }
+  hipLaunchKernelGGL(attend_mfma_kernel, dim3(p.workgroups, p.n_split), dim3(MF_NT), MF_STAGES * MF_SLOT, s, a);
+  if (p.n_split > 1) {
+    const long total = (long)a.h_kv * a.n_g * (a.h_q / a.h_kv);
     hipLaunchKernelGGL(attend_merge_kernel, dim3((unsigned)total), dim3(256), 0, s, a);
   }
 }

@@ -4,6 +4,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "qp_internal.h"
 
 namespace {
@@ -55,17 +57,19 @@ qp_status finish(hipError_t launch_err) {
   return QP_OK;
 }
 
-// Library-owned streams of qp_prefill_video (created once per process, default priority):
-//   score   scoring and top-k/compaction of a group depend only on the group's K/V (and the query window),
-//           never on its attention, so they run beside the group's attention kernel;
-//   attend2 the attention of group g+1 depends on the compaction of group g but not on the attention of
-//           group g, so odd groups' attention kernels go to a second attention stream: the tail of one
-//           group's kernel (a few heavy row blocks, and fewer workgroups than CUs at small groups) is
-//           filled by the next group's workgroups.
-// Both are forked from the caller's stream at entry and joined back into it before the call returns.
 // Scratch that qp_group_attend's key split may use (partial outputs of the chunks); qp_prefill_video keeps one
 // area per attention stream, so that two groups' attention launches in flight never share one.
 constexpr size_t kAttendSplitBytes = (size_t)32 << 20;
+
+// Library-owned streams of qp_prefill_video (created once per device, default priority):
+//   score   scoring and top-k/compaction of a group depend only on the group's K/V (and the query window),
+//           never on its attention, so they run beside the group's attention kernel;
+//   attend  the attention of group g+1 depends on the compaction of group g but not on the attention of
+//           group g, so consecutive groups' attention kernels alternate between the caller's stream and a
+//           second attention stream: launch gaps and the tail of one group's kernel are filled by the next.
+// They are forked from the caller's stream at entry and joined back into it before the call returns. The
+// streams and their events are shared by all calls on a device, so qp_prefill_video holds g_prefill_mutex while
+// it enqueues (it never waits for the GPU inside).
 constexpr int MAX_ATT_STREAMS = 2;  // attention streams in rotation, the caller's included (3 measured no better, 4 worse)
 struct SideStreams {
   hipStream_t score = nullptr, attend[MAX_ATT_STREAMS] = {};  // attend[0] is unused (the caller's stream)
@@ -73,27 +77,61 @@ struct SideStreams {
   int n_att = MAX_ATT_STREAMS;
   bool tried = false, ok = false;
 };
-SideStreams g_side;
+SideStreams g_side_of[qp::QP_MAX_DEVICES];
+std::mutex g_prefill_mutex;
 
-bool side_streams_ready() {
-  if (!g_side.tried) {
-    g_side.tried = true;
-    g_side.ok = hipStreamCreateWithFlags(&g_side.score, hipStreamNonBlocking) == hipSuccess &&
-                hipEventCreateWithFlags(&g_side.fork, hipEventDisableTiming) == hipSuccess &&
-                hipEventCreateWithFlags(&g_side.compacted[0], hipEventDisableTiming) == hipSuccess &&
-                hipEventCreateWithFlags(&g_side.compacted[1], hipEventDisableTiming) == hipSuccess;
-    for (int i = 1; i < MAX_ATT_STREAMS && g_side.ok; ++i)
-      g_side.ok = hipStreamCreateWithFlags(&g_side.attend[i], hipStreamNonBlocking) == hipSuccess &&
-                  hipEventCreateWithFlags(&g_side.attend_done[i], hipEventDisableTiming) == hipSuccess;
-    if (!g_side.ok) (void)hipGetLastError();
+// The current device's side streams, created on first use; nullptr if there is no usable device slot or the
+// creation failed (the call then runs everything on the caller's stream).
+SideStreams* side_streams() {
+  const int dev = qp::current_device();
+  if (dev < 0) return nullptr;
+  SideStreams& g = g_side_of[dev];
+  if (!g.tried) {
+    g.tried = true;
+    g.ok = hipStreamCreateWithFlags(&g.score, hipStreamNonBlocking) == hipSuccess &&
+           hipEventCreateWithFlags(&g.fork, hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&g.compacted[0], hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&g.compacted[1], hipEventDisableTiming) == hipSuccess;
+    for (int i = 1; i < MAX_ATT_STREAMS && g.ok; ++i)
+      g.ok = hipStreamCreateWithFlags(&g.attend[i], hipStreamNonBlocking) == hipSuccess &&
+             hipEventCreateWithFlags(&g.attend_done[i], hipEventDisableTiming) == hipSuccess;
+    if (!g.ok) (void)hipGetLastError();
   }
-  return g_side.ok;
+  return g.ok ? &g : nullptr;
 }
 
 // Workspace layout of qp_prefill_video: [scores H_kv*n_g f32][kept indices H_kv*n_g i32][window scratch].
 size_t scores_bytes(const qp_layout* L, int32_t n_g) { return round256((size_t)L->n_kv_heads * n_g * sizeof(float)); }
 
 }  // namespace
+
+namespace qp {
+
+int current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return -1;
+  }
+  return dev >= 0 && dev < QP_MAX_DEVICES ? dev : -1;
+}
+
+int device_cu_count() {
+  static int cached[QP_MAX_DEVICES] = {};
+  const int dev = current_device();
+  if (dev < 0) return 256;
+  if (cached[dev] == 0) {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) {
+      (void)hipGetLastError();
+      v = 256;
+    }
+    cached[dev] = v;
+  }
+  return cached[dev];
+}
+
+}  // namespace qp
 
 extern "C" {
 
@@ -124,6 +162,37 @@ size_t qp_workspace_bytes(const qp_layout* L, int32_t max_group_tokens, int32_t 
   b += qp::window_workspace_bytes(L->n_q_heads, L->n_kv_heads, max_group_tokens, n_window > 0 ? n_window : 1);
   b += MAX_ATT_STREAMS * kAttendSplitBytes;  // key-split scratch of qp_group_attend, one per attention stream of qp_prefill_video
   return b + 256;
+}
+
+qp_status qp_attend_plan(const qp_layout* L, int32_t n_g, int32_t cache_len, size_t workspace_bytes,
+                         qp_attend_plan_info* out) {
+  qp_status st = check_layout(L);
+  if (st != QP_OK) return st;
+  if ((st = check_group(n_g)) != QP_OK) return st;
+  if (cache_len < 0 || out == nullptr) return QP_ERR_INVALID_ARG;
+  qp::AttendArgs a;
+  memset(&a, 0, sizeof(a));
+  a.n_g = n_g;
+  a.h_q = L->n_q_heads;
+  a.h_kv = L->n_kv_heads;
+  a.d = L->head_dim;
+  a.c = a.cap = cache_len;
+  const bool mfma_ok = qp::attend_mfma_supported(a, L->dtype);
+  if (g_attend_kernel == QP_ATTEND_MFMA && !mfma_ok) return QP_ERR_UNSUPPORTED;
+  memset(out, 0, sizeof(*out));
+  if (mfma_ok && g_attend_kernel != QP_ATTEND_SCALAR) {
+    const qp::AttendPlan p = qp::plan_attend_mfma(a, workspace_bytes);
+    out->kernel = QP_ATTEND_MFMA;
+    out->workgroups = p.workgroups;
+    out->key_chunks = p.n_split;
+    out->tiles_per_chunk = p.split_tiles;
+    out->mirrored_rows = p.mirrored;
+    out->scratch_bytes = p.scratch_bytes;
+  } else {
+    out->kernel = QP_ATTEND_SCALAR;
+    out->key_chunks = 1;
+  }
+  return QP_OK;
 }
 
 qp_status qp_select_attend_kernel(int32_t which) {
@@ -296,7 +365,11 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
   char* split_ws = (char*)workspace + (workspace_bytes - MAX_ATT_STREAMS * kAttendSplitBytes) / 256 * 256;
 
   hipStream_t main_stream = (hipStream_t)hip_stream;
-  const bool overlap = side_streams_ready();
+  std::lock_guard<std::mutex> lock(g_prefill_mutex);
+  SideStreams* side = side_streams();
+  const bool overlap = side != nullptr;
+  SideStreams none;
+  SideStreams& g_side = overlap ? *side : none;
   void* score_stream = overlap ? (void*)g_side.score : hip_stream;
 #define QP_HIP_OK(call_) \
   if ((call_) != hipSuccess) return finish(hipGetLastError())

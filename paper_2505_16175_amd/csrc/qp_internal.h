@@ -110,8 +110,23 @@ struct AttendArgs {
 // Launchers (defined next to their kernels). They only enqueue; hipGetLastError is checked by the caller.
 void launch_attend_scalar(const AttendArgs& a, int dtype, hipStream_t s);
 bool attend_mfma_supported(const AttendArgs& a, int dtype);
+// How launch_attend_mfma lays a call out: grid (workgroups x key_chunks), row mapping, scratch it takes.
+struct AttendPlan {
+  int workgroups;       // grid.x, including the padding workgroups of the XCD mapping
+  int n_split;          // grid.y: key chunks (1 = no split)
+  int split_tiles;      // cache tiles per chunk
+  int mirrored;         // row mapping, see AttendArgs
+  size_t scratch_bytes; // bytes of the split scratch used (0 without split)
+};
+// split_ws_bytes: scratch the caller can offer for the key split (0: never split). Host arithmetic only.
+AttendPlan plan_attend_mfma(const AttendArgs& a, size_t split_ws_bytes);
 // split_ws / split_ws_bytes: optional scratch (256-byte aligned) for the key split; without it the kernel never splits
 void launch_attend_mfma(const AttendArgs& a, void* split_ws, size_t split_ws_bytes, hipStream_t s);
+
+// Per-device host state (kernel attributes, library streams, CU count) is kept in arrays of this many slots.
+constexpr int QP_MAX_DEVICES = 64;
+int current_device();   // index of the current HIP device, -1 if there is none or it does not fit the arrays
+int device_cu_count();  // compute units of the current device; 256 (MI355X) if it cannot be asked
 
 void launch_score_norm(const void* x, int dtype, int n_g, int h_kv, int d, float sign, float* scores, hipStream_t s);
 

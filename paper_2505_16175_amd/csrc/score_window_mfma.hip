@@ -213,11 +213,12 @@ void launch_score_window_mfma(const WindowArgs& a, hipStream_t s) {
   const int n_kc = (a.n_g + WIN_KC - 1) / WIN_KC;
   float2* partial = (float2*)a.workspace;
   const size_t lds2 = (size_t)(rows < WIN_CH ? rows : WIN_CH) * 256 + (size_t)rows * sizeof(float);
-  static bool attr_set = false;
-  if (!attr_set) {
+  static bool attr_set[QP_MAX_DEVICES] = {};
+  const int dev = current_device();
+  if (dev < 0 || !attr_set[dev]) {
     (void)hipFuncSetAttribute((const void*)window_pass2_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                               WIN_CH * 256 + WIN_MAX_ROWS * (int)sizeof(float));
-    attr_set = true;
+    if (dev >= 0) attr_set[dev] = true;
   }
   hipLaunchKernelGGL(window_pass1_kernel, dim3((n_rbk * n_kc + 3) / 4, a.h_kv), dim3(256), 0, s, a, partial);
   hipLaunchKernelGGL(window_pass2_kernel, dim3((a.n_g + WIN_P2_KEYS - 1) / WIN_P2_KEYS, a.h_kv), dim3(256), lds2, s, a,

@@ -284,12 +284,13 @@ static void launch_gather(const TopkArgs& a, const int32_t* kept, hipStream_t s)
 // kept_ws: [h_kv][keep] int32 scratch for the kept indices (the caller's kept buffer or the workspace)
 hipError_t launch_topk_compact(const TopkArgs& a, int dtype, int32_t* kept_ws, hipStream_t s) {
   const size_t lds_bytes = (size_t)a.n_g * sizeof(uint32_t);
-  static bool attr_set = false;
-  if (!attr_set) {
+  static bool attr_set[QP_MAX_DEVICES] = {};
+  const int dev = current_device();
+  if (dev < 0 || !attr_set[dev]) {
     hipError_t e = hipFuncSetAttribute((const void*)topk_select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        QP_MAX_GROUP_TOKENS * (int)sizeof(uint32_t));
     if (e != hipSuccess) return e;
-    attr_set = true;
+    if (dev >= 0) attr_set[dev] = true;
   }
   hipLaunchKernelGGL(topk_select_kernel, dim3(a.h_kv), dim3(TOPK_THREADS), lds_bytes, s, a, kept_ws);
   if (dtype == QP_F32) {

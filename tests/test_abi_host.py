@@ -34,6 +34,40 @@ def test_host_arithmetic_matches_oracle_and_golden():
     assert B.cache_capacity(0, 1, 1, 0.5) == -1
 
 
+def test_attend_plan_chunks_cover_the_cache_exactly():
+    """Host arithmetic of the attention launch: when the cache is split over key chunks, every chunk is non-empty,
+    the chunks tile the cache's 64-key tiles exactly, the scratch fits what was offered, and big launches never split."""
+    L = B.make_layout(28, 4, 128, "bf16")
+    offered = 32 << 20
+    for n_g in (1, 2, 7, 64, 100, 128, 500, 2048, 8192):
+        for c in (0, 1, 63, 64, 200, 256, 257, 1031, 5000, 9840, 46125, 200000):
+            p = B.attend_plan(L, n_g, c, offered)
+            assert p["kernel"] == B.QP_ATTEND_MFMA
+            rows_per_head = n_g * 7
+            real_wgs = ((rows_per_head + 127) // 128 + 1) // 2 * 4
+            assert p["workgroups"] >= real_wgs and p["workgroups"] % 8 == 0
+            n_ct = (c + 63) // 64
+            s, per = p["key_chunks"], p["tiles_per_chunk"]
+            if s == 1:
+                assert per == 0 and p["scratch_bytes"] == 0
+                # a small launch against a long cache must have split (enough scratch was offered for two chunks)
+                if real_wgs < 128 and n_ct >= 4 and 2 * 4 * rows_per_head * 129 * 4 <= offered:
+                    raise AssertionError(f"no split for n_g={n_g} c={c}")
+            else:
+                assert real_wgs < 128 and 2 <= s <= 128 and per >= 2
+                assert (s - 1) * per < n_ct <= s * per          # every chunk starts on an existing cache tile
+                assert p["scratch_bytes"] == s * 4 * rows_per_head * 129 * 4 <= offered
+                assert real_wgs * s <= 2 * 256 + real_wgs       # about one workgroup per compute unit
+            assert B.attend_plan(L, n_g, c, 0)["key_chunks"] == 1   # no scratch, no split
+    assert B.attend_plan(L, 2048, 9840, offered)["mirrored_rows"] == 1      # 224 workgroups: one per CU, balanced
+    assert B.attend_plan(L, 8192, 24000, offered)["mirrored_rows"] == 0     # 896 workgroups: longest first
+    assert B.attend_plan(B.make_layout(4, 2, 64, "f32"), 32, 64, offered)["kernel"] == B.QP_ATTEND_SCALAR
+    with pytest.raises(B.QPError):
+        B.attend_plan(L, 0, 10, 0)
+    with pytest.raises(B.QPError):
+        B.attend_plan(L, 16, -1, 0)
+
+
 def test_argument_errors_are_caught_on_the_host():
     lib = B.lib()
     L = B.make_layout(28, 4, 128, "bf16")

@@ -82,6 +82,7 @@ def test_group_attend_key_split_matches_oracle(h_q, h_kv, n_g, c):
     cache.v.copy_(cv)
     cache.c.len = c
     ws = B.make_workspace(layout, max(n_g, 32), 0)
+    assert (B.attend_plan(layout, n_g, c, ws.numel())["key_chunks"] > 1) == (c >= 4 * 64)   # the split is what runs
     outs = []
     for scratch in (ws, None):
         out = torch.full((n_g, h_q, d), float("nan"), dtype=torch.bfloat16, device=DEV)
