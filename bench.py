@@ -184,6 +184,10 @@ def main():
     ap.add_argument("--layers", type=int, default=None,
                     help="layers of a stacked config to run per step (default: all of the config's; inputs and the "
                          "pruned cache of every layer stay resident in HBM)")
+    ap.add_argument("--group-frames", type=int, default=None,
+                    help="frames per group instead of the config's (the group-size axis of the paper's Table 2 grid)")
+    ap.add_argument("--retention", type=float, default=None,
+                    help="KV retention ratio rho instead of the config's (the other axis of that grid)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mfma-probe", action="store_true",
                     help="run the stand-alone matrix-pipe probe (bf16 MFMA rate with constant / random operands) and exit")
@@ -205,6 +209,10 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     w = CONFIGS[args.config]
+    if args.group_frames is not None or args.retention is not None:
+        import dataclasses
+        w = dataclasses.replace(w, group_frames=args.group_frames or w.group_frames,
+                                retention=args.retention or w.retention)
     rule = args.rule or w.rules[0]
     n_layers = args.layers or w.n_layers
     layers = [make_layer(w, layer=l, device="cuda") for l in range(n_layers)]
@@ -273,7 +281,7 @@ def main():
     achieved = fl / t_att / 1e12
     roofline = {"kernel": "attend_mfma_kernel (qp_group_attend)", "bound": "mfma", "achieved": achieved,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                "traffic": MEASURED_TRAFFIC.get(w.name),
+                "traffic": MEASURED_TRAFFIC.get(w.name) if w == CONFIGS[args.config] else None,
                 "launches": n_launch, "avg_launch_us": t_att / n_launch * 1e6,
                 "flops_per_launch_avg": fl / n_launch}
     if w.dtype == "f32":
