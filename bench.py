@@ -96,6 +96,28 @@ def characterise_hbm(torch, B, reps=6):
     nbytes = h * (n_g * 4 + keep * 4 + 2 * 2 * keep * d * 2)
     out["topk_compact"] = {"shape": f"{h} heads x {n_g} tokens, keep {keep}", "bytes": nbytes, "us": t * 1e6,
                            "GBps": nbytes / t / 1e9, "frac_of_hbm_peak": nbytes / t / 1e9 / PEAK_HBM_GBS}
+    # window-attention scores at the same folded shape: 7 query heads per KV head, 64 window rows; the two-pass
+    # kernel does 2 x (2 H_q W N_g d) flops and reads K twice (the second time mostly from cache)
+    r, win = 7, 64
+    wl = B.make_layout(h * r, h, d, "bf16")
+    qwin = torch.randn(win, h * r, d, device="cuda", dtype=torch.bfloat16) / d ** 0.5
+    wws = B.make_workspace(wl, n_g, win)
+    for i in range(3):
+        B.score_kv(wl, "window_attn", ks[i], None, qwin, scores, wws)
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    e0.record()
+    for i in range(reps):
+        B.score_kv(wl, "window_attn", ks[i % 3], None, qwin, scores, wws)
+    e1.record()
+    torch.cuda.synchronize()
+    t = e0.elapsed_time(e1) * 1e-3 / reps
+    flops = 2 * 2.0 * h * r * win * n_g * d
+    nbytes = h * n_g * d * 2 + h * n_g * 4 + win * h * r * d * 2
+    out["score_window"] = {"shape": f"{h} KV heads x {r} query heads x {win} window rows x {n_g} tokens",
+                           "flops_two_pass": flops, "us": t * 1e6, "TFLOPs": flops / t / 1e12,
+                           "frac_of_mfma_peak": flops / t / 1e12 / PEAK_BF16_TFLOPS, "bytes": nbytes,
+                           "GBps": nbytes / t / 1e9, "frac_of_hbm_peak": nbytes / t / 1e9 / PEAK_HBM_GBS}
     return out
 
 
@@ -297,6 +319,10 @@ def main():
                          "algorithmic_GBps": tb / t_tk / 1e9, "frac_of_hbm_peak": tb / t_tk / 1e9 / PEAK_HBM_GBS},
         "note": "score/top-k figures are at the real per-group shapes (a few MB per launch: latency-bound)",
     }
+
+    if rule == "window_attn":   # two passes of 2 H_q W N_g d flops each
+        wf = sum(2 * 2.0 * w.n_q_heads * w.n_window * n_g * w.head_dim for _, _, n_g, _ in ev)
+        stages["score"].update({"TFLOPs": wf / t_sc / 1e12, "frac_of_mfma_peak": wf / t_sc / 1e12 / PEAK_BF16_TFLOPS})
 
     result = {
         "metric": "video tokens prefilled/sec per layer (attend+score+prune)",

@@ -6,9 +6,9 @@
 // The R*W window rows of a KV head are stacked as row = t*R + j (their memory order in
 // Q_win[t][h*R + j][:]). The work is a (R*W) x N_g x 128 contraction done twice; the whole problem is
 // a few MB and ~1 % of the attention flops, so the kernels are shaped for latency, not for the roof:
-//   pass 1   one wavefront per (32 rows, 64 keys): Q and both K blocks are requested up front (24 loads in
-//            flight), S^T = K . Q^T, a lane holds one row, so the chunk's row max and sum of exponentials
-//            are in-register reductions; one (m, l) partial per (row, chunk).
+//   pass 1   one wavefront per (32 rows, chunk of 64..1024 keys, 64 at a time): Q and both K blocks are requested
+//            up front (24 loads in flight), S^T = K . Q^T, a lane holds one row, so the row max and sum of
+//            exponentials are in-register reductions; one (m, l) partial per (row, chunk).
 //   pass 2   a workgroup first merges the partials into lse[row] in LDS (padded rows get +inf = weight 0);
 //            it owns 128 keys (32 per wavefront, K fragments in registers) and stages the head's
 //            window rows in LDS (direct global -> LDS loads, XOR-swizzled 16-byte chunks, up to 512 rows
@@ -32,8 +32,11 @@ constexpr int WIN_P2_KEYS = 128;    // keys per pass-2 workgroup
 
 __host__ __device__ inline int win_rows_padded(int h_q, int h_kv, int w) { return ((h_q / h_kv) * w + 31) / 32 * 32; }
 
-// partial[h][kc][row] = (m * c2, l): max of the scaled logits over the chunk and sum of exp2 around it.
-__global__ __launch_bounds__(256) void window_pass1_kernel(WindowArgs a, float2* __restrict__ partial) {
+// partial[h][kc][row] = (m * c2, l): max of the scaled logits over chunk kc and sum of exp2 around it. A chunk is
+// kc_sub sub-chunks of 64 keys walked by one wavefront with the Q fragments kept in registers (kc_sub = 1 for
+// small groups: most parallelism, least latency; larger for long groups, so that pass 2 merges at most 32
+// partials per row and Q is fetched once per chunk).
+__global__ __launch_bounds__(256) void window_pass1_kernel(WindowArgs a, float2* __restrict__ partial, int kc_sub) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int l32 = lane & 31, g = lane >> 5;
   const int h = blockIdx.y;
@@ -41,7 +44,8 @@ __global__ __launch_bounds__(256) void window_pass1_kernel(WindowArgs a, float2*
   const int n_rows = r_heads * a.w;
   const int n_rows_pad = win_rows_padded(a.h_q, a.h_kv, a.w);
   const int n_rbk = n_rows_pad / 32;
-  const int n_kc = (a.n_g + WIN_KC - 1) / WIN_KC;
+  const int chunk_keys = WIN_KC * kc_sub;
+  const int n_kc = (a.n_g + chunk_keys - 1) / chunk_keys;
   const int task = blockIdx.x * 4 + wave;
   if (task >= n_rbk * n_kc) return;
   const int kc = task / n_rbk, rbk = task - kc * n_rbk;
@@ -52,52 +56,60 @@ __global__ __launch_bounds__(256) void window_pass1_kernel(WindowArgs a, float2*
   const bf16_t* qrow = (const bf16_t*)a.q_win + ((size_t)t * a.h_q + (size_t)h * r_heads + j) * WIN_D;
   const bf16_t* gk = (const bf16_t*)a.k + (size_t)h * WIN_D;
   const size_t gstride = (size_t)a.h_kv * WIN_D;
-  const int k0 = kc * WIN_KC;
-  // all 24 fragment loads are issued before the first use
-  u32x4 qf[8], kf[2][8];
+  const float c2 = a.scale_log2;
+  // Q and the first sub-chunk's K: all 24 fragment loads are issued before the first use
+  u32x4 qf[8];
 #pragma unroll
   for (int s = 0; s < 8; ++s) qf[s] = *(const u32x4*)(qrow + 16 * s + 8 * g);
+  float m_run = -INFINITY, l_run = 0.f;  // over the sub-chunks so far (m in scaled log2 units)
+  for (int sub = 0; sub < kc_sub; ++sub) {
+    const int k0 = kc * chunk_keys + sub * WIN_KC;
+    if (k0 >= a.n_g) break;  // the chunk's first sub-chunk always exists
+    u32x4 kf[2][8];
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
-    const bf16_t* krow = gk + (size_t)min(k0 + 32 * b + l32, a.n_g - 1) * gstride;
+    for (int b = 0; b < 2; ++b) {
+      const bf16_t* krow = gk + (size_t)min(k0 + 32 * b + l32, a.n_g - 1) * gstride;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) kf[b][s] = *(const u32x4*)(krow + 16 * s + 8 * g);
-  }
-  const float c2 = a.scale_log2;
-  f32x16 st[2];
+      for (int s = 0; s < 8; ++s) kf[b][s] = *(const u32x4*)(krow + 16 * s + 8 * g);
+    }
+    f32x16 st[2];
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < 2; ++b) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) st[b][r] = 0.f;
+      for (int r = 0; r < 16; ++r) st[b][r] = 0.f;
 #pragma unroll
-    for (int s = 0; s < 8; ++s)
-      st[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[b][s]),
-                                                      __builtin_bit_cast(bf16x8, qf[s]), st[b], 0, 0, 0);
-  }
-  if (k0 + WIN_KC > a.n_g) {  // ragged last chunk: its first key exists, the rest may not
+      for (int s = 0; s < 8; ++s)
+        st[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[b][s]),
+                                                        __builtin_bit_cast(bf16x8, qf[s]), st[b], 0, 0, 0);
+    }
+    if (k0 + WIN_KC > a.n_g) {  // ragged last sub-chunk: its first key exists, the rest may not
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (k0 + 32 * b + 8 * (r >> 2) + 4 * g + (r & 3) >= a.n_g) st[b][r] = -INFINITY;
+    }
+    float mx = st[0][0];
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        if (k0 + 32 * b + 8 * (r >> 2) + 4 * g + (r & 3) >= a.n_g) st[b][r] = -INFINITY;
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, st[b][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mc = mx * c2;  // finite: key k0 exists
+    float psum = 0.f;
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) psum += __builtin_amdgcn_exp2f(fmaf(st[b][r], c2, -mc));
+    psum += __shfl_xor(psum, 32, 64);
+    const float m_new = fmaxf(m_run, mc);
+    l_run = l_run * __builtin_amdgcn_exp2f(m_run - m_new) + psum * __builtin_amdgcn_exp2f(mc - m_new);
+    m_run = m_new;
   }
-  float mx = st[0][0];
-#pragma unroll
-  for (int b = 0; b < 2; ++b)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, st[b][r]);
-  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-  const float mc = mx * c2;
-  float psum = 0.f;
-#pragma unroll
-  for (int b = 0; b < 2; ++b)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) psum += __builtin_amdgcn_exp2f(fmaf(st[b][r], c2, -mc));
-  psum += __shfl_xor(psum, 32, 64);
-  if (g == 0) partial[((size_t)h * n_kc + kc) * n_rows_pad + row] = make_float2(mc, psum);
+  if (g == 0) partial[((size_t)h * n_kc + kc) * n_rows_pad + row] = make_float2(m_run, l_run);
 }
 
-__global__ __launch_bounds__(256) void window_pass2_kernel(WindowArgs a, const float2* __restrict__ partial) {
+__global__ __launch_bounds__(256) void window_pass2_kernel(WindowArgs a, const float2* __restrict__ partial, int kc_sub) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [ch_rows x 256 B of Q][n_rows_pad floats of lse]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int l32 = lane & 31, g = lane >> 5;
@@ -107,11 +119,34 @@ __global__ __launch_bounds__(256) void window_pass2_kernel(WindowArgs a, const f
   const int n_rows_pad = win_rows_padded(a.h_q, a.h_kv, a.w);
   const int ch_rows = min(n_rows_pad, WIN_CH);
   float* lse2 = (float*)(smem + (size_t)ch_rows * 256);
+  const unsigned char* qbase = (const unsigned char*)a.q_win + (size_t)h * r_heads * (WIN_D * 2);
+  const unsigned q_tok_stride = (unsigned)a.h_q * (WIN_D * 2);
+  // stage window rows [c0_, c0_ + rows_): one load instruction moves 4 rows; lane -> (row, LDS position)
+#define QP_STAGE_ROWS(c0_, rows_)                                                                          \
+  for (int i = wave; i < (rows_) / 4; i += 4) {                                                            \
+    const int rl = 4 * i + (lane >> 4);           /* row inside the chunk */                               \
+    const int rowc = min((c0_) + rl, n_rows - 1); /* padded rows re-read the last row; their weight is 0 */ \
+    const int t = rowc / r_heads, j = rowc - t * r_heads;                                                  \
+    const unsigned off = (unsigned)t * q_tok_stride + (unsigned)j * (WIN_D * 2) +                          \
+                         (unsigned)((((lane & 15) ^ (rl & 15))) << 4);                                     \
+    lds_dma16(qbase, off, smem + (size_t)i * 1024);                                                        \
+  }
+  // The first chunk of rows is requested before anything else: it lands while the partials are merged.
+  QP_STAGE_ROWS(0, min(ch_rows, n_rows_pad))
+
+  // this wavefront's 32 keys as the B operand (K^T), held in registers for the whole kernel
+  const int k0 = blockIdx.x * WIN_P2_KEYS + wave * 32;
+  const bool wave_live = k0 < a.n_g;
+  const bf16_t* krow = (const bf16_t*)a.k + ((size_t)min(k0 + l32, a.n_g - 1) * a.h_kv + h) * WIN_D;
+  bf16x8 kf[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) kf[s] = __builtin_bit_cast(bf16x8, *(const u32x4*)(krow + 16 * s + 8 * g));
+
   // lse2[row] = log2 sum_j exp2(c2 * s_j), merged from the chunk partials (every workgroup repeats this small
   // reduction: it is cheaper than a launch); padded rows get +inf, i.e. weight 0 below. The partials of a row
   // are read eight at a time so that the loads overlap.
   {
-    const int n_kc = (a.n_g + WIN_KC - 1) / WIN_KC;
+    const int n_kc = (a.n_g + WIN_KC * kc_sub - 1) / (WIN_KC * kc_sub);
     for (int r = tid; r < n_rows_pad; r += 256) {
       float v = INFINITY;
       if (r < n_rows) {
@@ -137,17 +172,6 @@ __global__ __launch_bounds__(256) void window_pass2_kernel(WindowArgs a, const f
     }
   }
 
-  // this wavefront's 32 keys as the B operand (K^T), held in registers for the whole kernel
-  const int k0 = blockIdx.x * WIN_P2_KEYS + wave * 32;
-  const bool wave_live = k0 < a.n_g;
-  const bf16_t* krow = (const bf16_t*)a.k + ((size_t)min(k0 + l32, a.n_g - 1) * a.h_kv + h) * WIN_D;
-  bf16x8 kf[8];
-#pragma unroll
-  for (int s = 0; s < 8; ++s) kf[s] = __builtin_bit_cast(bf16x8, *(const u32x4*)(krow + 16 * s + 8 * g));
-  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): only the staging loads below stay untracked by the compiler
-
-  const unsigned char* qbase = (const unsigned char*)a.q_win + (size_t)h * r_heads * (WIN_D * 2);
-  const unsigned q_tok_stride = (unsigned)a.h_q * (WIN_D * 2);
   const float c2 = a.scale_log2;
   float colsum = 0.f;
   int a_addr[8];  // A fragment (Q rows) of d-step s: row l32 of the block, chunk 2s+g at position (2s+g) ^ (l32 & 15)
@@ -156,16 +180,8 @@ __global__ __launch_bounds__(256) void window_pass2_kernel(WindowArgs a, const f
 
   for (int c0 = 0; c0 < n_rows_pad; c0 += ch_rows) {
     const int rows_here = min(ch_rows, n_rows_pad - c0);
-    // stage rows [c0, c0 + rows_here): one load instruction moves 4 rows; lane -> (row, LDS position)
-    for (int i = wave; i < rows_here / 4; i += 4) {
-      const int rl = 4 * i + (lane >> 4);                 // row inside the chunk
-      const int rowc = min(c0 + rl, n_rows - 1);          // padded rows re-read the last row; their weight is 0
-      const int t = rowc / r_heads, j = rowc - t * r_heads;
-      const unsigned off = (unsigned)t * q_tok_stride + (unsigned)j * (WIN_D * 2) +
-                           (unsigned)((((lane & 15) ^ (rl & 15))) << 4);
-      lds_dma16(qbase, off, smem + (size_t)i * 1024);
-    }
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+    if (c0 > 0) QP_STAGE_ROWS(c0, rows_here)
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): staged rows (and, the first time, K fragments and partials)
     __syncthreads();
     if (wave_live) {
       for (int rbk = 0; rbk < rows_here / 32; ++rbk) {
@@ -192,6 +208,7 @@ __global__ __launch_bounds__(256) void window_pass2_kernel(WindowArgs a, const f
     }
     __syncthreads();  // before the next chunk overwrites the staged rows
   }
+#undef QP_STAGE_ROWS
   colsum += __shfl_xor(colsum, 32, 64);
   if (wave_live && g == 0 && k0 + l32 < a.n_g) a.scores[(size_t)h * a.n_g + k0 + l32] = colsum;
 }
@@ -210,8 +227,10 @@ size_t window_mfma_workspace_bytes(int h_q, int h_kv, int n_g, int w) {
 void launch_score_window_mfma(const WindowArgs& a, hipStream_t s) {
   const int rows = win_rows_padded(a.h_q, a.h_kv, a.w);
   const int n_rbk = rows / 32;
-  const int n_kc = (a.n_g + WIN_KC - 1) / WIN_KC;
-  float2* partial = (float2*)a.workspace;
+  int kc_sub = 1;  // sub-chunks of 64 keys per pass-1 chunk: at most 32 chunks per row for pass 2 to merge
+  while ((a.n_g + WIN_KC * kc_sub - 1) / (WIN_KC * kc_sub) > 32) kc_sub *= 2;
+  const int n_kc = (a.n_g + WIN_KC * kc_sub - 1) / (WIN_KC * kc_sub);
+  float2* partial = (float2*)a.workspace;  // sized for kc_sub = 1
   const size_t lds2 = (size_t)(rows < WIN_CH ? rows : WIN_CH) * 256 + (size_t)rows * sizeof(float);
   static bool attr_set[QP_MAX_DEVICES] = {};
   const int dev = current_device();
@@ -220,9 +239,9 @@ void launch_score_window_mfma(const WindowArgs& a, hipStream_t s) {
                               WIN_CH * 256 + WIN_MAX_ROWS * (int)sizeof(float));
     if (dev >= 0) attr_set[dev] = true;
   }
-  hipLaunchKernelGGL(window_pass1_kernel, dim3((n_rbk * n_kc + 3) / 4, a.h_kv), dim3(256), 0, s, a, partial);
+  hipLaunchKernelGGL(window_pass1_kernel, dim3((n_rbk * n_kc + 3) / 4, a.h_kv), dim3(256), 0, s, a, partial, kc_sub);
   hipLaunchKernelGGL(window_pass2_kernel, dim3((a.n_g + WIN_P2_KEYS - 1) / WIN_P2_KEYS, a.h_kv), dim3(256), lds2, s, a,
-                     partial);
+                     partial, kc_sub);
 }
 
 }  // namespace qp
