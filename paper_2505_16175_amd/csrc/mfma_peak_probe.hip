@@ -6,6 +6,7 @@
 // (2.5 PFLOP/s dense bf16) is reached with constant operands; with random operands the chip lowers
 // its clock (power management), which bounds any real kernel: attention roofline fractions in this
 // repository are quoted against the published peak, and this probe says how much of it is reachable.
+// A second part (overlap_loop below) measures how far vector work hides under another wavefront's MFMAs.
 #include <hip/hip_runtime.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -33,6 +34,51 @@ __global__ __launch_bounds__(512) void mfma_loop(const u32x4* src, float* out, i
   for (int n = 0; n < 4; ++n)
     for (int r = 0; r < 16; ++r) s += acc[n][r];
   out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+// Second question: does the vector work of one wavefront run under the MFMAs of another wavefront of the same
+// SIMD? 16 workgroups of 8 wavefronts (16 CUs, far below any power limit; wavefronts w and w+4 share a SIMD).
+// mode bits: 1 = wavefronts 0..3 run 32 MFMAs per iteration, 4 = wavefronts 4..7 do, 2 = wavefronts 4..7 run a
+// block of ~130 vector operations with 32 exp2 (the size of one tile's softmax), 8 = wavefronts 0..3 do.
+__global__ __launch_bounds__(512) void overlap_loop(float* out, int iters, int mode, float seed) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const bool lo = wave < 4;
+  const bool do_mfma = lo ? (mode & 1) : (mode & 4);
+  const bool do_valu = lo ? (mode & 8) : (mode & 2);
+  bf16x8 a, b;
+  for (int i = 0; i < 8; ++i) {
+    a[i] = (__bf16)(seed * (lane + i));
+    b[i] = (__bf16)(seed * (lane * 3 + i));
+  }
+  f32x16 acc[4];
+  for (int n = 0; n < 4; ++n)
+    for (int r = 0; r < 16; ++r) acc[n][r] = 0.f;
+  float v[16];
+  for (int i = 0; i < 16; ++i) v[i] = seed * (lane + i);
+  for (int it = 0; it < iters; ++it) {
+    if (do_mfma) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+#pragma unroll
+        for (int n = 0; n < 4; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[n], 0, 0, 0);
+    }
+    if (do_valu) {
+#pragma unroll
+      for (int rep = 0; rep < 2; ++rep)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          float x = fmaf(v[i], 0.999f, -0.25f);
+          x = __builtin_amdgcn_exp2f(x);
+          v[i] = fmaxf(x, v[(i + 1) & 15]) * 0.5f + 0.125f;
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  float s = 0.f;
+  for (int n = 0; n < 4; ++n)
+    for (int r = 0; r < 16; ++r) s += acc[n][r];
+  for (int i = 0; i < 16; ++i) s += v[i];
+  out[blockIdx.x * 512 + threadIdx.x] = s;
 }
 
 #define CHECK(x)                                                              \
@@ -79,6 +125,27 @@ int main() {
     const double flops = 512.0 * 8 * iters * 32 * 32768.0;
     printf("operands %s: %.3f ms per launch, %.1f TFLOP/s (%.1f %% of 2500)\n", names[mode], ms, flops / ms / 1e9,
            flops / ms / 1e9 / 25.0);
+  }
+  // co-execution of MFMA and vector work on one SIMD
+  const int modes[] = {1, 2, 3, 5, 10, 9, 15};
+  const char* what[] = {"wavefronts 0-3: MFMAs, 4-7 idle", "wavefronts 4-7: vector block, 0-3 idle",
+                        "wavefronts 0-3: MFMAs, 4-7: vector block", "all 8: MFMAs", "all 8: vector block",
+                        "wavefronts 0-3: MFMAs then vector block, 4-7 idle", "all 8: MFMAs then vector block"};
+  const int it2 = 20000;
+  for (int m = 0; m < 7; ++m) {
+    hipEvent_t e0, e1;
+    CHECK(hipEventCreate(&e0));
+    CHECK(hipEventCreate(&e1));
+    hipLaunchKernelGGL(overlap_loop, dim3(16), dim3(512), 0, 0, out, 100, modes[m], 0.001f);
+    CHECK(hipDeviceSynchronize());
+    CHECK(hipEventRecord(e0));
+    hipLaunchKernelGGL(overlap_loop, dim3(16), dim3(512), 0, 0, out, it2, modes[m], 0.001f);
+    CHECK(hipEventRecord(e1));
+    CHECK(hipEventSynchronize(e1));
+    float ms;
+    CHECK(hipEventElapsedTime(&ms, e0, e1));
+    printf("16 CUs, %-52s: %.1f ns per iteration (32 MFMAs and/or ~130 vector ops per wavefront)\n", what[m],
+           ms * 1e6 / it2);
   }
   return 0;
 }
