@@ -210,6 +210,9 @@ def main():
                     help="frames per group instead of the config's (the group-size axis of the paper's Table 2 grid)")
     ap.add_argument("--retention", type=float, default=None,
                     help="KV retention ratio rho instead of the config's (the other axis of that grid)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step (every layer's qp_prefill_video, library streams included) into a HIP graph "
+                         "and time its replays: removes the host's launch cost, which bounds configs of many small groups")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mfma-probe", action="store_true",
                     help="run the stand-alone matrix-pipe probe (bf16 MFMA rate with constant / random operands) and exit")
@@ -256,6 +259,14 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.graph:
+        eager_step = step
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            eager_step()
+        step = graph.replay
+        step()
+        torch.cuda.synchronize()
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
     marks[0].record()
@@ -329,7 +340,7 @@ def main():
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "ms_per_step_median": per_step[len(per_step) // 2],
         "ms_per_step_min": per_step[0], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype, "data": "synthetic",
+        "dtype": w.dtype, "data": "synthetic", "launch": "hip_graph_replay" if args.graph else "eager",
         "config": {"workload": f"{w.name}: {w.n_q_heads}q/{w.n_kv_heads}kv heads x d{w.head_dim}, "
                                f"{w.n_frames} frames x {w.tokens_per_frame} tokens, group {w.group_frames} frames, "
                                f"retention {w.retention}, rule {rule}, window {w.n_window if qwin is not None else 0}",

@@ -423,6 +423,49 @@ def test_runs_are_deterministic_and_stream_ordered():
             assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("group_frames", [5, 1])
+def test_prefill_video_replays_from_a_hip_graph(group_frames):
+    """A caller may capture qp_prefill_video (its forked library streams included) into a HIP graph: every replay,
+    with eager work and synchronisations in between, reproduces the eager call bit for bit. One-frame groups make
+    the attention launches take the key split (two launches and scratch per group) inside the graph."""
+    w = scaled(CONFIGS["cfg2_7b_32k"], n_frames=24, tokens_per_frame=64, group_frames=group_frames)
+    q, k, v, qw = make_layer(w, device=DEV, sharp=True)
+    layout = B.make_layout(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
+    cap = B.cache_capacity(w.n_frames, w.tokens_per_frame, w.group_frames, w.retention)
+    ws = B.make_workspace(layout, w.group_tokens, w.n_window)
+    cache = B.Cache(layout, cap)
+    out = torch.empty_like(q)
+
+    def run():
+        cache.reset()
+        B.prefill_video(layout, w.n_frames, w.tokens_per_frame, w.group_frames, w.retention, "window_attn", q, k, v,
+                        qw, cache, out, ws)
+
+    run()                                                     # eager: also creates the library's streams
+    torch.cuda.synchronize()
+    want = (out.clone(), cache.k.clone(), cache.v.clone(), cache.pos.clone())
+    final_len = cache.len
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    assert cache.len == final_len                             # the host-side length advanced during capture
+    for replay in range(3):
+        out.fill_(float("nan"))
+        cache.k.zero_()
+        cache.v.zero_()
+        cache.pos.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (out, cache.k, cache.v, cache.pos)
+        for a, b in zip(want, got):
+            assert torch.equal(a, b), f"replay {replay}"
+        run()                                                 # eager work between the replays
+        torch.cuda.synchronize()
+        for a, b in zip(want, got):
+            assert torch.equal(a, b), f"eager after replay {replay}"
+
+
 def test_capacity_and_unsupported_errors_leave_the_cache_alone():
     layout = B.make_layout(8, 2, 128, "bf16")
     n_g, keep = 256, 100
