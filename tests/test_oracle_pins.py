@@ -131,6 +131,42 @@ def test_attend_invariants():
     np.testing.assert_allclose(mha, base, atol=1e-13)
 
 
+def test_attention_over_key_chunks_merges_by_log_sum_exp():
+    """The identity behind a key split: softmax attention over a key set equals the merge of the attentions over a
+    partition of it, weighted by exp(lse_chunk - lse). Pins the oracle's lse output and is what the kernel's
+    split-and-merge path relies on (each chunk starts on cache entries; the last takes the group's own keys)."""
+    n_g, h_q, h_kv, d, c = 5, 6, 2, 8, 23
+    q, k, v = _rand(n_g, h_q, d), _rand(n_g, h_kv, d), _rand(n_g, h_kv, d)
+    ck, cv = _rand(h_kv, c, d), _rand(h_kv, c, d)
+    whole, lse = O.attend_group(q, k, v, ck, cv, return_lse=True)
+    # lse against its definition on one row: head 3 (KV head 1), token 2 sees the cache and group tokens 0..2
+    logits = np.concatenate([ck[1] @ q[2, 3], k[:3, 1] @ q[2, 3]]) / math.sqrt(d)
+    assert abs(lse[3, 2] - math.log(np.exp(logits).sum())) < 1e-12
+    # chunks: cache [0,7), cache [7,16), cache [16,23) + the group itself. A cache-only chunk has no causal part; the
+    # oracle always adds the group's own keys, so each row is run as a one-token group whose own key and value are
+    # zero (logit 0, value 0) and that dummy key's share is then removed exactly
+    cuts = [(0, 7), (7, 16), (16, 23)]
+    parts = []
+    for i, (a, b) in enumerate(cuts):
+        if i < len(cuts) - 1:
+            o = np.zeros((n_g, h_q, d))
+            l = np.zeros((h_q, n_g))
+            zero = np.zeros((1, h_kv, d))
+            for t in range(n_g):
+                oo, ll = O.attend_group(q[t:t + 1], zero, zero, ck[:, a:b], cv[:, a:b], return_lse=True)
+                # remove the dummy key's contribution exactly: its logit is 0, its value 0
+                w_dummy = np.exp(0.0 - ll[:, 0])                       # weight the dummy key received
+                o[t] = oo[0] / (1.0 - w_dummy)[:, None]
+                l[:, t] = ll[:, 0] + np.log1p(-w_dummy)
+            parts.append((o, l))
+        else:
+            parts.append(O.attend_group(q, k, v, ck[:, a:b], cv[:, a:b], return_lse=True))
+    lse_all = np.logaddexp.reduce(np.stack([l for _, l in parts]), axis=0)
+    merged = sum(o * np.exp(l - lse_all).T[:, :, None] for o, l in parts)
+    np.testing.assert_allclose(lse_all, lse, atol=1e-12)
+    np.testing.assert_allclose(merged, whole, atol=1e-12)
+
+
 def test_hand_example_whole_path():
     rows = {r[0]: r[1].split() for r in read_golden("hand_example_path.txt")}
     k = np.log(np.array([float(x) for x in rows["k_exp"]])).reshape(4, 1, 1)
