@@ -31,7 +31,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per launch of the attention kernel (FETCH_SIZE + WRITE_SIZE of rocprofv3 --pmc, averaged over
 # the launches of this benchmark and scaled by the same counters' reading on the calibration copy below);
 # figures and commands are in profiles/.
-MEASURED_TRAFFIC = {"cfg2_7b_32k": 56.8e6}
+MEASURED_TRAFFIC = {"cfg2_7b_32k": 56.8e6, "cfg3_7b_128k_norm": 186.4e6, "cfg4_72b_128k": 435.9e6}
 CAL_COPY_BYTES = 256 << 20
 
 
