@@ -124,7 +124,9 @@ def characterise_hbm(torch, B, reps=6):
 def characterise_after_prefill(torch, B, w, layout, cache, ws, reps=50):
     """The stages that consume the pruned cache (Sec. 2.1: text-token prefill, then decoding), through the same
     qp_group_attend: a chunk of W text tokens and a single token against the layer's final cache. Few rows
-    against a long cache: HBM-bound on the cache's K and V; the kernel splits the cache over key chunks."""
+    against a long cache: HBM-bound on the cache's K and V. With scratch the cache is dealt to about one workgroup
+    per CU (decode: the kernel whose wavefronts stream their own key blocks; text chunk: key split of the large
+    kernel) and a second launch merges; without scratch a single workgroup per row block walks the whole cache."""
     out = {}
     d, esz = w.head_dim, 2
     c = cache.len
@@ -134,7 +136,7 @@ def characterise_after_prefill(torch, B, w, layout, cache, ws, reps=50):
         v = torch.randn(n_g, w.n_kv_heads, d, device="cuda").to(torch.bfloat16)
         o = torch.empty_like(q)
         res = {}
-        for label, scratch in (("us", ws), ("us_without_key_split", None)):
+        for label, scratch in (("us", ws), ("us_without_scratch", None)):
             for _ in range(3):
                 B.group_attend(layout, q, k, v, cache, o, None, scratch)
             torch.cuda.synchronize()

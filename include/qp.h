@@ -63,7 +63,13 @@ typedef enum {
 
 /* Which attention kernel qp_group_attend uses. AUTO picks the MFMA kernel when the
  * layout allows it (bf16, head_dim 128), else the scalar one. */
-typedef enum { QP_ATTEND_AUTO = 0, QP_ATTEND_SCALAR = 1, QP_ATTEND_MFMA = 2 } qp_attend_kernel;
+typedef enum {
+  QP_ATTEND_AUTO = 0,
+  QP_ATTEND_SCALAR = 1,
+  QP_ATTEND_MFMA = 2,
+  QP_ATTEND_MFMA_DECODE = 3 /* reported by qp_attend_plan only: AUTO's kernel for at most 32 stacked rows
+                               per KV head (decode-shaped calls); not selectable */
+} qp_attend_kernel;
 
 typedef struct {
   int32_t n_q_heads;   /* H_q                                                   */
@@ -113,10 +119,13 @@ size_t qp_workspace_bytes(const qp_layout* layout, int32_t max_group_tokens, int
  * decoding): a text chunk or a single new token is a "group" of n_group_tokens >= 1 rows attending
  * to the whole pruned cache plus itself.
  *   workspace: optional device scratch (256-byte aligned), may be NULL. When a launch would have too
- *     few rows to fill the GPU against a long cache, the MFMA kernel splits the cache over key chunks
- *     and merges their partial results in a second launch; the partials ([chunks][rows][d+1] f32, as
- *     many chunks as fit, at most 128) live in this scratch. Without scratch it never splits. Calls
- *     that may overlap on different streams need distinct scratch.
+ *     few rows to fill the GPU against a long cache, the cache is dealt to key chunks whose partial
+ *     results a second launch merges; the partials ([chunks][rows][d+1] f32, as many chunks as fit)
+ *     live in this scratch. Two kernels do this: calls of at most 32 stacked rows per KV head
+ *     (n_group_tokens * H_q/H_kv <= 32: decoding) run a kernel in which every wavefront streams its
+ *     own blocks of keys; larger ones split the tiles of the large kernel (at most 128 chunks).
+ *     Without scratch nothing is split. Calls that may overlap on different streams need distinct
+ *     scratch. qp_attend_plan reports the choice.
  * Errors: INVALID_ARG (NULL/misaligned pointers, n_group_tokens <= 0, bad layout),
  * UNSUPPORTED (dtype/head_dim/group size). The cache is not modified. */
 qp_status qp_group_attend(const qp_layout* layout, const void* q_g, const void* k_g, const void* v_g,
@@ -177,7 +186,7 @@ qp_status qp_prefill_video(const qp_layout* layout, int32_t n_frames, int32_t to
  * compute unit) or consecutively, and how much of the offered workspace the split would use.
  * For the scalar kernel only `kernel` and key_chunks = 1 are meaningful. */
 typedef struct {
-  int32_t kernel;          /* QP_ATTEND_SCALAR or QP_ATTEND_MFMA */
+  int32_t kernel;          /* QP_ATTEND_SCALAR, QP_ATTEND_MFMA or QP_ATTEND_MFMA_DECODE */
   int32_t workgroups;      /* per key chunk, including idle padding workgroups */
   int32_t key_chunks;
   int32_t tiles_per_chunk; /* 0 when key_chunks == 1 */

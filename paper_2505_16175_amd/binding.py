@@ -17,7 +17,7 @@ from .build import LIB_PATH
 QP_OK, QP_ERR_INVALID_ARG, QP_ERR_UNSUPPORTED, QP_ERR_CAPACITY, QP_ERR_HIP = range(5)
 QP_F32, QP_BF16 = 0, 1
 QP_SCORE_KEY_NORM_SMALL, QP_SCORE_VALUE_NORM, QP_SCORE_WINDOW_ATTN = 0, 1, 2
-QP_ATTEND_AUTO, QP_ATTEND_SCALAR, QP_ATTEND_MFMA = 0, 1, 2
+QP_ATTEND_AUTO, QP_ATTEND_SCALAR, QP_ATTEND_MFMA, QP_ATTEND_MFMA_DECODE = 0, 1, 2, 3
 RULES = {"key_norm_small": QP_SCORE_KEY_NORM_SMALL, "value_norm": QP_SCORE_VALUE_NORM,
          "window_attn": QP_SCORE_WINDOW_ATTN}
 QP_MAX_GROUP_TOKENS = 32768

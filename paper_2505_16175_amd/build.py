@@ -9,8 +9,8 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libqp_hip.so")
-SOURCES = ["qp_api.hip", "attend_scalar.hip", "attend_mfma.hip", "score.hip", "score_window_mfma.hip",
-           "topk_compact.hip"]
+SOURCES = ["qp_api.hip", "attend_scalar.hip", "attend_mfma.hip", "attend_decode.hip", "score.hip",
+           "score_window_mfma.hip", "topk_compact.hip"]
 
 
 def hipcc_command(out=LIB_PATH, extra=()):

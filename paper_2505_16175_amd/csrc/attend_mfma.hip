@@ -354,57 +354,75 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
     a.lse[(size_t)(h * r_heads + j_lane) * a.n_g + t_lane] = (m_run * c2 + log2f(l_tot)) * 0.6931471805599453f;
 }
 
-// Merge of the key split: out[row] = sum_c 2^(lse_c - lse) O_c[row], lse = log2 sum_c 2^lse_c. One workgroup per
-// row: wavefront w takes chunks w, w+4, ... (four loads in flight), lane l owns d = 2l, 2l+1; the four wavefronts'
-// sums meet in LDS.
-__global__ __launch_bounds__(256) void attend_merge_kernel(AttendArgs a) {
-  __shared__ float red[4][64][3];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+// Merge of the key split: out[row] = sum_c 2^(lse_c - lse) O_c[row], lse = log2 sum_c 2^lse_c. One workgroup of 8
+// wavefronts per row: wavefront w takes chunks w, w+8, ..., eight at a time with all their loads in flight at once
+// (the log-sum-exps and the partial rows alike, so a wavefront pays one memory round trip per batch), merges them
+// around its own maximum, and the eight results meet in LDS. Lane l owns d = 2l, 2l+1.
+constexpr int MG_WAVES = 8;
+__global__ __launch_bounds__(MG_WAVES * 64) void attend_merge_kernel(AttendArgs a) {
+  __shared__ float red[MG_WAVES][64][2], red_m[MG_WAVES], red_l[MG_WAVES];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int r_heads = a.h_q / a.h_kv;
   const int n_rows = a.n_g * r_heads;
   const long total = (long)a.h_kv * n_rows;
   const long grow = blockIdx.x;
   const int h = (int)(grow / n_rows), row = (int)(grow - (long)h * n_rows);
   const int t = row / r_heads, j = row - t * r_heads;
-  float mx = -INFINITY;  // every wavefront takes the max over all chunks: the same reference everywhere
-  for (int c = lane; c < a.n_split; c += 64) mx = fmaxf(mx, a.part_lse[(size_t)c * total + grow]);
-  mx = wave_max(mx);
-  float den = 0.f, acc0 = 0.f, acc1 = 0.f;
-  for (int c0 = wave; c0 < a.n_split; c0 += 16) {
-    float w[4];
-    float2 po[4];
+  float m = -INFINITY, den = 0.f, acc0 = 0.f, acc1 = 0.f;  // this wavefront's chunks, relative to m
+  for (int c0 = wave; c0 < a.n_split; c0 += 8 * MG_WAVES) {
+    float ls[8];
+    float2 po[8];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int c = min(c0 + 4 * u, a.n_split - 1);
-      w[u] = c0 + 4 * u < a.n_split ? exp2f(a.part_lse[(size_t)c * total + grow] - mx) : 0.f;
+    for (int u = 0; u < 8; ++u) {
+      const int c = min(c0 + MG_WAVES * u, a.n_split - 1);
+      ls[u] = c0 + MG_WAVES * u < a.n_split ? a.part_lse[(size_t)c * total + grow] : -INFINITY;
       po[u] = *(const float2*)(a.part_o + ((size_t)c * total + grow) * MF_D + 2 * lane);
     }
+    float mb = ls[0];  // finite: chunk c0 exists
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      den += w[u];
-      acc0 = fmaf(w[u], po[u].x, acc0);
-      acc1 = fmaf(w[u], po[u].y, acc1);
+    for (int u = 1; u < 8; ++u) mb = fmaxf(mb, ls[u]);
+    const float m_new = fmaxf(m, mb);
+    const float keep = exp2f(m - m_new);  // 0 the first time
+    den *= keep;
+    acc0 *= keep;
+    acc1 *= keep;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const float w = exp2f(ls[u] - m_new);
+      den += w;
+      acc0 = fmaf(w, po[u].x, acc0);
+      acc1 = fmaf(w, po[u].y, acc1);
     }
+    m = m_new;
   }
-  red[wave][lane][0] = den;
-  red[wave][lane][1] = acc0;
-  red[wave][lane][2] = acc1;
+  red[wave][lane][0] = acc0;
+  red[wave][lane][1] = acc1;
+  if (lane == 0) {
+    red_m[wave] = m;  // -inf for a wavefront without chunks: weight 0 below
+    red_l[wave] = den;
+  }
   __syncthreads();
   if (wave != 0) return;
+  float big = red_m[0];
 #pragma unroll
-  for (int w = 1; w < 4; ++w) {
-    den += red[w][lane][0];
-    acc0 += red[w][lane][1];
-    acc1 += red[w][lane][2];
+  for (int w = 1; w < MG_WAVES; ++w) big = fmaxf(big, red_m[w]);
+  float dsum = 0.f, o0 = 0.f, o1 = 0.f;
+#pragma unroll
+  for (int w = 0; w < MG_WAVES; ++w) {
+    const float wgt = exp2f(red_m[w] - big);
+    dsum = fmaf(wgt, red_l[w], dsum);
+    o0 = fmaf(wgt, red[w][lane][0], o0);
+    o1 = fmaf(wgt, red[w][lane][1], o1);
   }
-  const float inv = 1.f / den;
+  const float inv = 1.f / dsum;
   bf16x2 pk;
-  pk[0] = (__bf16)(acc0 * inv);
-  pk[1] = (__bf16)(acc1 * inv);
+  pk[0] = (__bf16)(o0 * inv);
+  pk[1] = (__bf16)(o1 * inv);
   bf16_t* orow = (bf16_t*)a.out + ((size_t)t * a.h_q + (size_t)h * r_heads + j) * MF_D;
   *(uint32_t*)(orow + 2 * lane) = __builtin_bit_cast(uint32_t, pk);
   if (a.lse != nullptr && lane == 0)
-    a.lse[(size_t)(h * r_heads + j) * a.n_g + t] = (mx + log2f(den)) * 0.6931471805599453f;
+    a.lse[(size_t)(h * r_heads + j) * a.n_g + t] = (big + log2f(dsum)) * 0.6931471805599453f;
 }
 
 bool attend_mfma_supported(const AttendArgs& a, int dtype) {
@@ -466,10 +484,12 @@ void launch_attend_mfma(const AttendArgs& a_in, void* split_ws, size_t split_ws_
     a.part_lse = a.part_o + (size_t)p.n_split * rows_total * MF_D;
   }
   hipLaunchKernelGGL(attend_mfma_kernel, dim3(p.workgroups, p.n_split), dim3(MF_NT), MF_STAGES * MF_SLOT, s, a);
-  if (p.n_split > 1) {
-    const long total = (long)a.h_kv * a.n_g * (a.h_q / a.h_kv);
-    hipLaunchKernelGGL(attend_merge_kernel, dim3((unsigned)total), dim3(256), 0, s, a);
-  }
+  if (p.n_split > 1) launch_attend_merge(a, s);
+}
+
+void launch_attend_merge(const AttendArgs& a, hipStream_t s) {
+  const long total = (long)a.h_kv * a.n_g * (a.h_q / a.h_kv);
+  hipLaunchKernelGGL(attend_merge_kernel, dim3((unsigned)total), dim3(MG_WAVES * 64), 0, s, a);
 }
 
 }  // namespace qp

@@ -181,8 +181,9 @@ qp_status qp_attend_plan(const qp_layout* L, int32_t n_g, int32_t cache_len, siz
   if (g_attend_kernel == QP_ATTEND_MFMA && !mfma_ok) return QP_ERR_UNSUPPORTED;
   memset(out, 0, sizeof(*out));
   if (mfma_ok && g_attend_kernel != QP_ATTEND_SCALAR) {
-    const qp::AttendPlan p = qp::plan_attend_mfma(a, workspace_bytes);
-    out->kernel = QP_ATTEND_MFMA;
+    const bool decode = g_attend_kernel == QP_ATTEND_AUTO && qp::attend_decode_applies(a, L->dtype);
+    const qp::AttendPlan p = decode ? qp::plan_attend_decode(a, workspace_bytes) : qp::plan_attend_mfma(a, workspace_bytes);
+    out->kernel = decode ? QP_ATTEND_MFMA_DECODE : QP_ATTEND_MFMA;
     out->workgroups = p.workgroups;
     out->key_chunks = p.n_split;
     out->tiles_per_chunk = p.split_tiles;
@@ -232,7 +233,10 @@ qp_status qp_group_attend(const qp_layout* L, const void* q_g, const void* k_g, 
   hipStream_t s = (hipStream_t)hip_stream;
   const bool mfma_ok = qp::attend_mfma_supported(a, L->dtype);
   if (g_attend_kernel == QP_ATTEND_MFMA && !mfma_ok) return QP_ERR_UNSUPPORTED;
-  if (mfma_ok && g_attend_kernel != QP_ATTEND_SCALAR) qp::launch_attend_mfma(a, workspace, workspace ? workspace_bytes : 0, s);
+  const size_t ws_bytes = workspace ? workspace_bytes : 0;
+  if (mfma_ok && g_attend_kernel == QP_ATTEND_AUTO && qp::attend_decode_applies(a, L->dtype))
+    qp::launch_attend_decode(a, workspace, ws_bytes, s);
+  else if (mfma_ok && g_attend_kernel != QP_ATTEND_SCALAR) qp::launch_attend_mfma(a, workspace, ws_bytes, s);
   else qp::launch_attend_scalar(a, L->dtype, s);
   return finish(hipSuccess);
 }

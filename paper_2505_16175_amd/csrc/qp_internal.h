@@ -123,6 +123,12 @@ AttendPlan plan_attend_mfma(const AttendArgs& a, size_t split_ws_bytes);
 // split_ws / split_ws_bytes: optional scratch (256-byte aligned) for the key split; without it the kernel never splits
 void launch_attend_mfma(const AttendArgs& a, void* split_ws, size_t split_ws_bytes, hipStream_t s);
 
+void launch_attend_merge(const AttendArgs& a, hipStream_t s);  // merges a.n_split partials (a.part_o, a.part_lse)
+// Decode-shaped launches (at most 32 stacked rows per KV head): every wavefront streams its own key blocks.
+bool attend_decode_applies(const AttendArgs& a, int dtype);
+AttendPlan plan_attend_decode(const AttendArgs& a, size_t split_ws_bytes);  // n_split = workgroups per KV head
+void launch_attend_decode(const AttendArgs& a, void* split_ws, size_t split_ws_bytes, hipStream_t s);
+
 // Per-device host state (kernel attributes, library streams, CU count) is kept in arrays of this many slots.
 constexpr int QP_MAX_DEVICES = 64;
 int current_device();   // index of the current HIP device, -1 if there is none or it does not fit the arrays

@@ -42,8 +42,19 @@ def test_attend_plan_chunks_cover_the_cache_exactly():
     for n_g in (1, 2, 7, 64, 100, 128, 500, 2048, 8192):
         for c in (0, 1, 63, 64, 200, 256, 257, 1031, 5000, 9840, 46125, 200000):
             p = B.attend_plan(L, n_g, c, offered)
-            assert p["kernel"] == B.QP_ATTEND_MFMA
             rows_per_head = n_g * 7
+            if rows_per_head <= 32:
+                # decode-shaped: blocks of 32 keys (+ one block for the group's own keys) dealt to workgroups of 4
+                # wavefronts; every workgroup gets at least one block, every wavefront of a full one too
+                assert p["kernel"] == B.QP_ATTEND_MFMA_DECODE
+                nb = (c + 31) // 32 + 1
+                s, per = p["key_chunks"], p["tiles_per_chunk"]
+                assert per >= 4 and (s - 1) * per < nb <= s * per and s == p["workgroups"]
+                assert s * 4 <= 256 + 4                              # about one workgroup per compute unit at most
+                assert p["scratch_bytes"] == (s * 4 * rows_per_head * 129 * 4 if s > 1 else 0) <= offered
+                assert B.attend_plan(L, n_g, c, 0)["key_chunks"] == 1
+                continue
+            assert p["kernel"] == B.QP_ATTEND_MFMA
             real_wgs = ((rows_per_head + 127) // 128 + 1) // 2 * 4
             assert p["workgroups"] >= real_wgs and p["workgroups"] % 8 == 0
             n_ct = (c + 63) // 64

@@ -82,7 +82,9 @@ def test_group_attend_key_split_matches_oracle(h_q, h_kv, n_g, c):
     cache.v.copy_(cv)
     cache.c.len = c
     ws = B.make_workspace(layout, max(n_g, 32), 0)
-    assert (B.attend_plan(layout, n_g, c, ws.numel())["key_chunks"] > 1) == (c >= 4 * 64)   # the split is what runs
+    plan = B.attend_plan(layout, n_g, c, ws.numel())
+    assert plan["kernel"] == (B.QP_ATTEND_MFMA_DECODE if n_g * (h_q // h_kv) <= 32 else B.QP_ATTEND_MFMA)
+    assert plan["key_chunks"] > 1 or c < 4 * 64                     # with scratch, a long cache is split
     outs = []
     for scratch in (ws, None):
         out = torch.full((n_g, h_q, d), float("nan"), dtype=torch.bfloat16, device=DEV)
