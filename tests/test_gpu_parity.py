@@ -98,6 +98,36 @@ def test_group_attend_key_split_matches_oracle(h_q, h_kv, n_g, c):
     assert (outs[0] - outs[1]).abs().max().item() <= 2e-2
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("h_q,h_kv,n_g", [(28, 4, 1), (28, 4, 4), (64, 8, 3), (6, 3, 16), (4, 4, 32), (32, 1, 1)])
+@pytest.mark.parametrize("c", [0, 1, 31, 32, 33, 127, 128, 129, 1000, 4097])
+def test_decode_shaped_attend_matches_oracle(h_q, h_kv, n_g, c):
+    """At most 32 stacked rows per KV head: the kernel whose wavefronts stream their own 32-key blocks. Block
+    boundaries of the cache (31/32/33, 127/128/129), an empty cache, several new tokens (causal among themselves),
+    one workgroup per head (no scratch) and many (scratch + merge)."""
+    print(f"case heads={h_q}/{h_kv} n_g={n_g} c={c}", flush=True)
+    d = 128
+    g = torch.Generator().manual_seed(977 * n_g + c + h_q)
+    mk = lambda *s: torch.randn(*s, generator=g).to(torch.bfloat16)
+    q, k, v = mk(n_g, h_q, d), mk(n_g, h_kv, d), mk(n_g, h_kv, d)
+    ck, cv = mk(h_kv, c + 2, d), mk(h_kv, c + 2, d)
+    want, want_lse = O.attend_group(_f64(q), _f64(k), _f64(v), _f64(ck)[:, :c], _f64(cv)[:, :c], return_lse=True)
+    layout = B.make_layout(h_q, h_kv, d, "bf16")
+    cache = B.Cache(layout, c + 2)
+    cache.k.copy_(ck)
+    cache.v.copy_(cv)
+    cache.c.len = c
+    ws = B.make_workspace(layout, 32, 0)
+    assert B.attend_plan(layout, n_g, c, ws.numel())["kernel"] == B.QP_ATTEND_MFMA_DECODE
+    for scratch in (ws, None):
+        out = torch.full((n_g, h_q, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+        lse = torch.full((h_q, n_g), float("nan"), dtype=torch.float32, device=DEV)
+        B.group_attend(layout, q.to(DEV), k.to(DEV), v.to(DEV), cache if c > 0 else None, out, lse, scratch)
+        torch.cuda.synchronize()
+        assert_attn_close(_f64(out), want, "bf16", "with scratch" if scratch is not None else "one workgroup per head")
+        np.testing.assert_allclose(_f64(lse), want_lse, rtol=2e-5, atol=2e-3)
+
+
 # --------------------------------------------------------------------------------------------- S2
 @pytest.mark.parametrize("dtype,h_kv,d", [("f32", 2, 64), ("bf16", 4, 128), ("bf16", 8, 64), ("f32", 3, 128)])
 @pytest.mark.parametrize("n_g", [1, 33, 2048, 5000])
