@@ -143,7 +143,30 @@ def score_kv(rule, k_g, v_g, q_win=None, scale=None):
             p /= p.sum(axis=1, keepdims=True)
             s[h] += p.sum(axis=0)
         return s
+    if rule == "window_logit":
+        # Variant of the attention-score rule without the softmax: the literal `s = matmul(K_g, Q)` of the list under
+        # Eq. 2, i.e. the scaled logits summed over the window's queries and the query heads of the KV head.
+        q_win = np.asarray(q_win, dtype=np.float64)
+        w, h_q, _ = q_win.shape
+        r = h_q // h_kv
+        if scale is None:
+            scale = 1.0 / math.sqrt(d)
+        s = np.zeros((h_kv, n_g), dtype=np.float64)
+        for qh in range(h_q):
+            logits = scale * (q_win[:, qh, :] @ k_g[:, qh // r, :].T)    # [W, N_g]
+            s[qh // r] += logits.sum(axis=0)
+        return s
     raise ValueError(f"unknown scoring rule {rule!r}")
+
+
+def share_scores_across_heads(scores):
+    """Head-shared selection (Eq. 2 writes one index set I_g without a head index): every KV head scores a token by
+    the sum of all heads' scores, so the per-head TopK returns the same set for every head."""
+    scores = np.asarray(scores, dtype=np.float64)
+    total = np.zeros(scores.shape[1], dtype=np.float64)
+    for h in range(scores.shape[0]):       # in head order
+        total = total + scores[h]
+    return np.broadcast_to(total, scores.shape).copy()
 
 
 # --------------------------------------------------------------------------- #

@@ -241,6 +241,52 @@ def test_window_score_brute_force_and_mass():
 
 
 # ----------------------------------------------------------------------------- top-k
+def test_window_logit_rule_brute_force_and_properties():
+    """The softmax-free variant of the attention-score rule: element-wise brute force, linearity in the window
+    queries, and agreement of its ranking with the softmax rule's when there is one query row and one query head per
+    KV head (softmax is monotone in the logit)."""
+    n_g, h_q, h_kv, d, w = 9, 4, 2, 5, 3
+    k, qw = _rand(n_g, h_kv, d), _rand(w, h_q, d)
+    got = O.score_kv("window_logit", k, None, qw)
+    r = h_q // h_kv
+    for h in range(h_kv):
+        for j in range(n_g):
+            acc = 0.0
+            for t in range(w):
+                for qh in range(h * r, (h + 1) * r):
+                    acc += sum(qw[t, qh, e] * k[j, h, e] for e in range(d)) / math.sqrt(d)
+            assert abs(got[h, j] - acc) < 1e-12
+    qw2 = _rand(w, h_q, d)
+    np.testing.assert_allclose(O.score_kv("window_logit", k, None, qw + qw2),
+                               got + O.score_kv("window_logit", k, None, qw2), atol=1e-12)
+    np.testing.assert_allclose(O.score_kv("window_logit", k, None, qw, scale=0.5),
+                               0.5 * math.sqrt(d) * got, atol=1e-12)
+    one = _rand(1, h_kv, d)                                    # W = 1, R = 1
+    a = O.score_kv("window_logit", k, None, one)
+    b = O.score_kv("window_attn", k, None, one)
+    for h in range(h_kv):
+        assert (np.argsort(-a[h], kind="stable") == np.argsort(-b[h], kind="stable")).all()
+    for keep in (1, 4, n_g):
+        np.testing.assert_array_equal(O.topk_select(a, keep), O.topk_select(b, keep))
+
+
+def test_head_shared_selection():
+    """One index set per group: every head's scores are replaced by the sum over heads, so the per-head TopK agrees
+    across heads and equals the TopK of the summed scores; with one head nothing changes."""
+    s = _rand(3, 11)
+    shared = O.share_scores_across_heads(s)
+    np.testing.assert_allclose(shared[0], s[0] + s[1] + s[2], atol=1e-15)
+    assert (shared == shared[0]).all()
+    sel = O.topk_select(shared, 4)
+    assert (sel == sel[0]).all()
+    np.testing.assert_array_equal(sel[0], O.topk_select((s[0] + s[1] + s[2])[None], 4)[0])
+    np.testing.assert_array_equal(O.share_scores_across_heads(s[:1]), s[:1])
+    # a token that one head loves and the others ignore is kept for all of them
+    s2 = np.zeros((3, 6))
+    s2[1, 4] = 10.0
+    assert 4 in O.topk_select(O.share_scores_across_heads(s2), 1)[2]
+
+
 def test_topk_hand_cases():
     for rule, vals, k, want in read_golden("topk_hand_cases.txt"):
         x = np.array([float(t) for t in vals.split()])
