@@ -43,7 +43,7 @@ def attend_flops(w, c, n_g):
 def score_bytes(w, rule, n_g):
     esz = 4 if w.dtype == "f32" else 2
     b = w.n_kv_heads * n_g * w.head_dim * esz + w.n_kv_heads * n_g * 4
-    if rule == "window_attn":
+    if rule.startswith("window"):
         b += w.n_window * w.n_q_heads * w.head_dim * esz
     return b
 
@@ -112,8 +112,22 @@ def characterise_hbm(torch, B, reps=6):
     e1.record()
     torch.cuda.synchronize()
     t = e0.elapsed_time(e1) * 1e-3 / reps
-    flops = 2 * 2.0 * h * r * win * n_g * d
+    # the softmax-free variant of that rule: one dot product per key, HBM-bound like the norms
+    for i in range(3):
+        B.score_kv(wl, "window_logit", ks[i], None, qwin, scores, wws)
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    e0.record()
+    for i in range(reps):
+        B.score_kv(wl, "window_logit", ks[i % 3], None, qwin, scores, wws)
+    e1.record()
+    torch.cuda.synchronize()
+    tl = e0.elapsed_time(e1) * 1e-3 / reps
     nbytes = h * n_g * d * 2 + h * n_g * 4 + win * h * r * d * 2
+    out["score_window_logit"] = {"shape": f"{h} KV heads x {r} query heads x {win} window rows x {n_g} tokens",
+                                 "bytes": nbytes, "us": tl * 1e6, "GBps": nbytes / tl / 1e9,
+                                 "frac_of_hbm_peak": nbytes / tl / 1e9 / PEAK_HBM_GBS}
+    flops = 2 * 2.0 * h * r * win * n_g * d
     out["score_window"] = {"shape": f"{h} KV heads x {r} query heads x {win} window rows x {n_g} tokens",
                            "flops_two_pass": flops, "us": t * 1e6, "TFLOPs": flops / t / 1e12,
                            "frac_of_mfma_peak": flops / t / 1e12 / PEAK_BF16_TFLOPS, "bytes": nbytes,
@@ -250,13 +264,13 @@ def main():
     cache = caches[0]
     ws = B.make_workspace(layout, w.group_tokens, w.n_window)
     out = torch.empty_like(q)                                  # the layer output is consumed and overwritten
-    qwin = qw if rule == "window_attn" else None
+    qwin = qw if rule.startswith("window") else None
 
     def step():
         for (lq, lk, lv, lqw), c in zip(layers, caches):
             c.reset()
             B.prefill_video(layout, w.n_frames, w.tokens_per_frame, w.group_frames, w.retention, rule, lq, lk, lv,
-                            lqw if rule == "window_attn" else None, c, out, ws)
+                            lqw if rule.startswith("window") else None, c, out, ws)
 
     for _ in range(args.warmup):
         step()
@@ -326,14 +340,14 @@ def main():
         "attend_ms_per_step": t_att / args.steps * 1e3,
         "score_ms_per_step": t_sc / args.steps * 1e3,
         "topk_compact_ms_per_step": t_tk / args.steps * 1e3,
-        "score": {"bound": "hbm" if rule != "window_attn" else "mfma", "avg_launch_us": t_sc / n_launch * 1e6,
+        "score": {"bound": "mfma" if rule.startswith("window_attn") else "hbm", "avg_launch_us": t_sc / n_launch * 1e6,
                   "algorithmic_GBps": sb / t_sc / 1e9, "frac_of_hbm_peak": sb / t_sc / 1e9 / PEAK_HBM_GBS},
         "topk_compact": {"bound": "hbm", "avg_launch_us": t_tk / n_launch * 1e6,
                          "algorithmic_GBps": tb / t_tk / 1e9, "frac_of_hbm_peak": tb / t_tk / 1e9 / PEAK_HBM_GBS},
         "note": "score/top-k figures are at the real per-group shapes (a few MB per launch: latency-bound)",
     }
 
-    if rule == "window_attn":   # two passes of 2 H_q W N_g d flops each
+    if rule.startswith("window_attn"):   # two passes of 2 H_q W N_g d flops each
         wf = sum(2 * 2.0 * w.n_q_heads * w.n_window * n_g * w.head_dim for _, _, n_g, _ in ev)
         stages["score"].update({"TFLOPs": wf / t_sc / 1e12, "frac_of_mfma_peak": wf / t_sc / 1e12 / PEAK_BF16_TFLOPS})
 

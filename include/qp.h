@@ -55,10 +55,17 @@ typedef enum { QP_F32 = 0, QP_BF16 = 1 } qp_dtype;
 typedef enum {
   QP_SCORE_KEY_NORM_SMALL = 0, /* s = -||K_g[j,h,:]||_2  (the paper's default)                  */
   QP_SCORE_VALUE_NORM = 1,     /* s = +||V_g[j,h,:]||_2                                          */
-  QP_SCORE_WINDOW_ATTN = 2     /* "Attention Scores": softmax attention mass that key j of KV
+  QP_SCORE_WINDOW_ATTN = 2,    /* "Attention Scores": softmax attention mass that key j of KV
                                   head h receives from the text-query window, softmax taken over
                                   the group's own keys, summed over the window's queries and over
                                   the query heads that map to h                                  */
+  QP_SCORE_WINDOW_LOGIT = 3,   /* variant of the above without the softmax (the literal
+                                  s = matmul(K_g, Q) of the list): scale * sum of the logits
+                                  q.k over the same queries and heads = one dot product per key  */
+  QP_SCORE_SHARED_HEADS = 0x100 /* flag, OR-ed into a rule above: head-shared selection. Every KV
+                                  head's score of a token becomes the sum of all heads' scores
+                                  (f32, in head order), so the per-head TopK of Eq. 2 -- which
+                                  writes one index set I_g -- keeps the same tokens for all heads */
 } qp_score_rule;
 
 /* Which attention kernel qp_group_attend uses. AUTO picks the MFMA kernel when the
@@ -134,10 +141,11 @@ qp_status qp_group_attend(const qp_layout* layout, const void* q_g, const void* 
 
 /* Importance scores of a group's new KV entries (the functions listed under Eq. 2).
  *   k_g, v_g as above (the norm rules read only the tensor they name; the other may be NULL)
- *   q_win [n_window][H_q][d]: the text-query window (QP_SCORE_WINDOW_ATTN only, else ignored)
+ *   q_win [n_window][H_q][d]: the text-query window (the two WINDOW rules only, else ignored)
  *   scores [H_kv][n_group_tokens] f32 (written)
- * f32 arithmetic. Errors as above; WINDOW_ATTN with q_win NULL or n_window <= 0 is INVALID_ARG;
- * CAPACITY if the workspace is too small. */
+ * f32 arithmetic. Errors as above; a WINDOW rule with q_win NULL or n_window <= 0 is INVALID_ARG;
+ * CAPACITY if the workspace is too small (the WINDOW rules need qp_workspace_bytes(layout,
+ * n_group_tokens, n_window)). */
 qp_status qp_score_kv(const qp_layout* layout, qp_score_rule rule, const void* k_g, const void* v_g,
                       int32_t n_group_tokens, const void* q_win, int32_t n_window, float* scores,
                       void* workspace, size_t workspace_bytes, void* hip_stream);

@@ -121,7 +121,10 @@ def attend_group(q_g, k_g, v_g, cache_k, cache_v, scale=None, rows=None, return_
 # Importance scores (the three functions listed under Eq. 2)
 # --------------------------------------------------------------------------- #
 def score_kv(rule, k_g, v_g, q_win=None, scale=None):
-    """s [H_kv, N_g] for one group; larger = more important."""
+    """s [H_kv, N_g] for one group; larger = more important. A rule name ending in "+shared" is that rule followed by
+    share_scores_across_heads (head-shared selection)."""
+    if rule.endswith("+shared"):
+        return share_scores_across_heads(score_kv(rule[:-len("+shared")], k_g, v_g, q_win, scale))
     k_g = np.asarray(k_g, dtype=np.float64)
     n_g, h_kv, d = k_g.shape
     if rule == "key_norm_small":

@@ -18,8 +18,10 @@ QP_OK, QP_ERR_INVALID_ARG, QP_ERR_UNSUPPORTED, QP_ERR_CAPACITY, QP_ERR_HIP = ran
 QP_F32, QP_BF16 = 0, 1
 QP_SCORE_KEY_NORM_SMALL, QP_SCORE_VALUE_NORM, QP_SCORE_WINDOW_ATTN = 0, 1, 2
 QP_ATTEND_AUTO, QP_ATTEND_SCALAR, QP_ATTEND_MFMA, QP_ATTEND_MFMA_DECODE = 0, 1, 2, 3
+QP_SCORE_WINDOW_LOGIT, QP_SCORE_SHARED_HEADS = 3, 0x100
 RULES = {"key_norm_small": QP_SCORE_KEY_NORM_SMALL, "value_norm": QP_SCORE_VALUE_NORM,
-         "window_attn": QP_SCORE_WINDOW_ATTN}
+         "window_attn": QP_SCORE_WINDOW_ATTN, "window_logit": QP_SCORE_WINDOW_LOGIT}
+RULES.update({name + "+shared": code | QP_SCORE_SHARED_HEADS for name, code in list(RULES.items())})
 QP_MAX_GROUP_TOKENS = 32768
 
 

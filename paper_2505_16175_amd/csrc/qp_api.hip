@@ -159,7 +159,9 @@ size_t qp_workspace_bytes(const qp_layout* L, int32_t max_group_tokens, int32_t 
   if (check_layout(L) != QP_OK || check_group(max_group_tokens) != QP_OK || n_window < 0) return 0;
   size_t b = scores_bytes(L, max_group_tokens);
   b += qp::topk_workspace_bytes(L->n_kv_heads, max_group_tokens);
-  b += qp::window_workspace_bytes(L->n_q_heads, L->n_kv_heads, max_group_tokens, n_window > 0 ? n_window : 1);
+  const size_t win = qp::window_workspace_bytes(L->n_q_heads, L->n_kv_heads, max_group_tokens, n_window > 0 ? n_window : 1);
+  const size_t logit = qp::window_logit_workspace_bytes(L->n_kv_heads, L->head_dim);
+  b += win > logit ? win : logit;
   b += MAX_ATT_STREAMS * kAttendSplitBytes;  // key-split scratch of qp_group_attend, one per attention stream of qp_prefill_video
   return b + 256;
 }
@@ -249,7 +251,9 @@ qp_status qp_score_kv(const qp_layout* L, qp_score_rule rule, const void* k_g, c
   if ((st = check_group(n_g)) != QP_OK) return st;
   if (!scores || (((uintptr_t)scores) & 3u)) return QP_ERR_INVALID_ARG;
   hipStream_t s = (hipStream_t)hip_stream;
-  switch (rule) {
+  const bool shared = ((int)rule & QP_SCORE_SHARED_HEADS) != 0;
+  const int base_rule = (int)rule & ~QP_SCORE_SHARED_HEADS;
+  switch (base_rule) {
     case QP_SCORE_KEY_NORM_SMALL:
       if (!k_g || !aligned16(k_g)) return QP_ERR_INVALID_ARG;
       qp::launch_score_norm(k_g, L->dtype, n_g, L->n_kv_heads, L->head_dim, -1.f, scores, s);
@@ -278,9 +282,29 @@ qp_status qp_score_kv(const qp_layout* L, qp_score_rule rule, const void* k_g, c
       qp::launch_score_window(w, L->dtype, s);
       break;
     }
+    case QP_SCORE_WINDOW_LOGIT: {
+      if (!k_g || !aligned16(k_g) || !q_win || !aligned16(q_win) || n_window <= 0) return QP_ERR_INVALID_ARG;
+      if (n_window > 65535) return QP_ERR_UNSUPPORTED;
+      if (!workspace || (((uintptr_t)workspace) & 255u)) return QP_ERR_INVALID_ARG;
+      if (workspace_bytes < qp::window_logit_workspace_bytes(L->n_kv_heads, L->head_dim)) return QP_ERR_CAPACITY;
+      qp::WindowArgs w;
+      w.k = k_g;
+      w.q_win = q_win;
+      w.scores = scores;
+      w.workspace = workspace;
+      w.n_g = n_g;
+      w.h_q = L->n_q_heads;
+      w.h_kv = L->n_kv_heads;
+      w.d = L->head_dim;
+      w.w = n_window;
+      w.scale_log2 = scale_log2_of(L);
+      qp::launch_score_window_logit(w, L->dtype, scale_log2_of(L) * 0.6931471805599453f, s);
+      break;
+    }
     default:
       return QP_ERR_INVALID_ARG;
   }
+  if (shared) qp::launch_share_heads(scores, L->n_kv_heads, n_g, s);
   return finish(hipSuccess);
 }
 
@@ -331,8 +355,9 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
   if (st != QP_OK) return st;
   if (n_frames <= 0 || tokens_per_frame <= 0 || group_frames <= 0) return QP_ERR_INVALID_ARG;
   if (!(retention > 0.0) || retention > 1.0) return QP_ERR_INVALID_ARG;
-  if (rule != QP_SCORE_KEY_NORM_SMALL && rule != QP_SCORE_VALUE_NORM && rule != QP_SCORE_WINDOW_ATTN)
-    return QP_ERR_INVALID_ARG;
+  const int base_rule = (int)rule & ~QP_SCORE_SHARED_HEADS;
+  const bool window_rule = base_rule == QP_SCORE_WINDOW_ATTN || base_rule == QP_SCORE_WINDOW_LOGIT;
+  if (base_rule != QP_SCORE_KEY_NORM_SMALL && base_rule != QP_SCORE_VALUE_NORM && !window_rule) return QP_ERR_INVALID_ARG;
   const int64_t n_total = (int64_t)n_frames * tokens_per_frame;
   if (n_total > INT32_MAX) return QP_ERR_UNSUPPORTED;
   const int64_t max_group = (int64_t)(group_frames < n_frames ? group_frames : n_frames) * tokens_per_frame;
@@ -340,10 +365,10 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
   if ((st = check_cache(cache, true)) != QP_OK) return st;
   if (!q || !k || !v || !out || !aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
     return QP_ERR_INVALID_ARG;
-  if (rule == QP_SCORE_WINDOW_ATTN && (!q_win || !aligned16(q_win) || n_window <= 0)) return QP_ERR_INVALID_ARG;
-  if (rule == QP_SCORE_WINDOW_ATTN && n_window > 65535) return QP_ERR_UNSUPPORTED;
+  if (window_rule && (!q_win || !aligned16(q_win) || n_window <= 0)) return QP_ERR_INVALID_ARG;
+  if (window_rule && n_window > 65535) return QP_ERR_UNSUPPORTED;
   if (!workspace || (((uintptr_t)workspace) & 255u)) return QP_ERR_INVALID_ARG;
-  if (workspace_bytes < qp_workspace_bytes(L, (int32_t)max_group, rule == QP_SCORE_WINDOW_ATTN ? n_window : 0))
+  if (workspace_bytes < qp_workspace_bytes(L, (int32_t)max_group, window_rule ? n_window : 0))
     return QP_ERR_CAPACITY;
   if ((int64_t)cache->len + qp_cache_capacity(n_frames, tokens_per_frame, group_frames, retention) > cache->capacity)
     return QP_ERR_CAPACITY;

@@ -145,6 +145,9 @@ struct WindowArgs {
   float scale_log2;
 };
 size_t window_workspace_bytes(int h_q, int h_kv, int n_g, int w);
+size_t window_logit_workspace_bytes(int h_kv, int d);  // the summed window rows, [h_kv][d] f32
+void launch_score_window_logit(const WindowArgs& a, int dtype, float scale, hipStream_t s);
+void launch_share_heads(float* scores, int h_kv, int n_g, hipStream_t s);
 void launch_score_window(const WindowArgs& a, int dtype, hipStream_t s);
 bool window_mfma_supported(int dtype, int h_q, int h_kv, int d, int w);
 size_t window_mfma_workspace_bytes(int h_q, int h_kv, int n_g, int w);

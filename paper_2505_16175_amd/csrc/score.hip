@@ -79,6 +79,118 @@ void launch_score_norm(const void* x, int dtype, int n_g, int h_kv, int d, float
 }
 
 // ---------------------------------------------------------------------------------------------
+// Softmax-free attention score: s[h][j] = scale * sum_{t, qh in head group h} Q_win[t, qh, :] . K_g[j, h, :]
+//                                        = scale * qsum[h] . K_g[j, h, :],  qsum[h] = sum of the R*W window rows.
+// Two launches: the window rows are summed once per KV head (f32, fixed order), then the keys are streamed like the
+// norm rules (one KV head and consecutive tokens per wavefront, contiguous stores). HBM-bound.
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void window_qsum_kernel(const T* __restrict__ q_win, int w, int h_q, int h_kv,
+                                                          float* __restrict__ qsum) {
+  constexpr int PER = Elem<T>::kPer16B;
+  constexpr int LPR = D / PER;       // lanes per row
+  constexpr int RPI = 256 / LPR;     // rows per iteration of the workgroup
+  __shared__ float part[RPI][D];
+  const int h = blockIdx.x, r_heads = h_q / h_kv;
+  const int sub = threadIdx.x % LPR, rg = threadIdx.x / LPR;
+  float acc[PER];
+#pragma unroll
+  for (int e = 0; e < PER; ++e) acc[e] = 0.f;
+  for (int row = rg; row < r_heads * w; row += RPI) {  // row = t * R + j, the memory order of the head group's rows
+    const int t = row / r_heads, j = row - t * r_heads;
+    const uint4 raw = *(const uint4*)(q_win + ((size_t)t * h_q + (size_t)h * r_heads + j) * D + sub * PER);
+    float v[PER];
+    widen16<T>(raw, v);
+#pragma unroll
+    for (int e = 0; e < PER; ++e) acc[e] += v[e];
+  }
+#pragma unroll
+  for (int e = 0; e < PER; ++e) part[rg][sub * PER + e] = acc[e];
+  __syncthreads();
+  for (int e = threadIdx.x; e < D; e += 256) {
+    float tot = 0.f;
+    for (int g = 0; g < RPI; ++g) tot += part[g][e];
+    qsum[(size_t)h * D + e] = tot;
+  }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void score_dot_kernel(const T* __restrict__ x, const float* __restrict__ qsum, int n_g,
+                                                        int h_kv, float scale, float* __restrict__ scores) {
+  constexpr int PER = Elem<T>::kPer16B;
+  constexpr int LPR = D / PER;
+  constexpr int TW = 64 / LPR * NORM_UNROLL;
+  const int lane = threadIdx.x & 63, sub = lane % LPR, lg = lane / LPR;
+  const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int n_waves = (gridDim.x * blockDim.x) >> 6;
+  const int n_tb = (n_g + TW - 1) / TW;
+  const long n_items = (long)n_tb * h_kv;
+  for (long item = wave; item < n_items; item += n_waves) {
+    const int h = (int)(item % h_kv);
+    const int t0 = (int)(item / h_kv) * TW + lg * NORM_UNROLL;
+    float qs[PER];
+#pragma unroll
+    for (int e = 0; e < PER; ++e) qs[e] = qsum[(size_t)h * D + sub * PER + e];
+    uint4 raw[NORM_UNROLL];
+#pragma unroll
+    for (int u = 0; u < NORM_UNROLL; ++u)
+      raw[u] = t0 + u < n_g ? *(const uint4*)(x + ((size_t)(t0 + u) * h_kv + h) * D + sub * PER) : make_uint4(0, 0, 0, 0);
+    float mine = 0.f;
+#pragma unroll
+    for (int u = 0; u < NORM_UNROLL; ++u) {
+      float v[PER];
+      widen16<T>(raw[u], v);
+      float dot = 0.f;
+#pragma unroll
+      for (int e = 0; e < PER; ++e) dot = fmaf(v[e], qs[e], dot);
+#pragma unroll
+      for (int o = LPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+      if (sub == u) mine = dot;
+    }
+    if (sub < NORM_UNROLL && t0 + sub < n_g) scores[(size_t)h * n_g + t0 + sub] = scale * mine + 0.f;
+  }
+}
+
+template <typename T, int D>
+static void launch_logit(const WindowArgs& a, float scale, hipStream_t s) {
+  constexpr int TW = 64 / (D / Elem<T>::kPer16B) * NORM_UNROLL;
+  float* qsum = (float*)a.workspace;
+  hipLaunchKernelGGL((window_qsum_kernel<T, D>), dim3(a.h_kv), dim3(256), 0, s, (const T*)a.q_win, a.w, a.h_q, a.h_kv, qsum);
+  const long items = (long)((a.n_g + TW - 1) / TW) * a.h_kv;
+  long wgs = (items + 3) / 4;
+  if (wgs > 8192) wgs = 8192;
+  hipLaunchKernelGGL((score_dot_kernel<T, D>), dim3((unsigned)wgs), dim3(256), 0, s, (const T*)a.k, qsum, a.n_g, a.h_kv,
+                     scale, a.scores);
+}
+
+size_t window_logit_workspace_bytes(int h_kv, int d) { return ((size_t)h_kv * d * sizeof(float) + 255) / 256 * 256; }
+
+// a.scale_log2 is not used here: `scale` is the softmax scale itself
+void launch_score_window_logit(const WindowArgs& a, int dtype, float scale, hipStream_t s) {
+  if (dtype == QP_F32) {
+    if (a.d == 64) launch_logit<float, 64>(a, scale, s);
+    else launch_logit<float, 128>(a, scale, s);
+  } else {
+    if (a.d == 64) launch_logit<bf16_t, 64>(a, scale, s);
+    else launch_logit<bf16_t, 128>(a, scale, s);
+  }
+}
+
+// Head-shared selection: scores[h][j] <- sum over h' of scores[h'][j], in head order, for every h.
+__global__ __launch_bounds__(256) void share_heads_kernel(float* __restrict__ scores, int h_kv, int n_g) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= n_g) return;
+  float tot = 0.f;
+  for (int h = 0; h < h_kv; ++h) tot += scores[(size_t)h * n_g + j];
+  tot += 0.f;
+  for (int h = 0; h < h_kv; ++h) scores[(size_t)h * n_g + j] = tot;
+}
+
+void launch_share_heads(float* scores, int h_kv, int n_g, hipStream_t s) {
+  hipLaunchKernelGGL(share_heads_kernel, dim3((n_g + 255) / 256), dim3(256), 0, s, scores, h_kv, n_g);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Window rule, scalar version.
 
 // lse2[qh][t] = log2( sum_j exp2(scale_log2 * q.k_j) ) over the group's n_g keys.

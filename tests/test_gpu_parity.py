@@ -169,6 +169,60 @@ def test_window_scores_match_oracle(dtype, h_q, h_kv, d, w, n_g, sharp):
     np.testing.assert_allclose(got.sum(axis=1), (h_q // h_kv) * w, rtol=1e-5)   # total attention mass
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype,h_q,h_kv,d,w", [("f32", 4, 2, 64, 16), ("bf16", 28, 4, 128, 64), ("bf16", 64, 8, 128, 128),
+                                                ("f32", 6, 3, 128, 5)])
+@pytest.mark.parametrize("n_g", [1, 33, 2048, 5000])
+def test_window_logit_scores_match_oracle(dtype, h_q, h_kv, d, w, n_g):
+    """The softmax-free variant of the attention-score rule (one dot product per key against the summed window)."""
+    print(f"case dtype={dtype} heads={h_q}/{h_kv} d={d} w={w} n_g={n_g}", flush=True)
+    g = torch.Generator().manual_seed(n_g + 13 * w)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    k = torch.randn(n_g, h_kv, d, generator=g).to(tdt)
+    qw = torch.randn(w, h_q, d, generator=g).to(tdt)
+    want = O.score_kv("window_logit", _f64(k), None, _f64(qw))
+    layout = B.make_layout(h_q, h_kv, d, dtype)
+    ws = B.make_workspace(layout, n_g, w)
+    scores = torch.full((h_kv, n_g), float("nan"), dtype=torch.float32, device=DEV)
+    B.score_kv(layout, "window_logit", k.to(DEV), None, qw.to(DEV), scores, ws)
+    torch.cuda.synchronize()
+    # f32 sums of (R*W) rows and of d products: relative to the size of the terms, not of the (cancelling) result
+    bound = 2e-6 * np.abs(_f64(qw)).sum(axis=(0, 1)).max() * np.abs(_f64(k)).max() * d / math.sqrt(d)
+    np.testing.assert_allclose(scores.cpu().numpy(), want, rtol=1e-5, atol=max(bound, 1e-6))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("rule", ["key_norm_small+shared", "window_attn+shared", "window_logit+shared"])
+def test_head_shared_scores_and_selection(rule):
+    """QP_SCORE_SHARED_HEADS: every head's score row becomes the f32 sum over heads (in head order), so the per-head
+    TopK keeps one index set; checked bit-exactly against the same sum done by hand, and against the oracle."""
+    h_q, h_kv, d, w, n_g, keep = 28, 4, 128, 64, 1500, 300
+    g = torch.Generator().manual_seed(5)
+    k = torch.randn(n_g, h_kv, d, generator=g).to(torch.bfloat16)
+    v = torch.randn(n_g, h_kv, d, generator=g).to(torch.bfloat16)
+    qw = torch.randn(w, h_q, d, generator=g).to(torch.bfloat16)
+    layout = B.make_layout(h_q, h_kv, d, "bf16")
+    ws = B.make_workspace(layout, n_g, w)
+    base = torch.empty(h_kv, n_g, dtype=torch.float32, device=DEV)
+    shared = torch.empty_like(base)
+    B.score_kv(layout, rule.split("+")[0], k.to(DEV), v.to(DEV), qw.to(DEV), base, ws)
+    B.score_kv(layout, rule, k.to(DEV), v.to(DEV), qw.to(DEV), shared, ws)
+    torch.cuda.synchronize()
+    by_hand = base[0].clone()
+    for h in range(1, h_kv):
+        by_hand += base[h]
+    assert torch.equal(shared, by_hand.expand_as(shared))
+    want = O.score_kv(rule, _f64(k), _f64(v), _f64(qw))
+    np.testing.assert_allclose(shared.cpu().numpy(), want, rtol=2e-4, atol=2e-4)
+    cache = B.Cache(layout, keep)
+    kept = torch.empty(h_kv, keep, dtype=torch.int32, device=DEV)
+    B.topk_compact(layout, shared, k.to(DEV), v.to(DEV), keep, 0, cache, kept)
+    torch.cuda.synchronize()
+    got = kept.cpu().numpy()
+    assert (got == got[0]).all()                               # one index set for all heads
+    np.testing.assert_array_equal(got, O.topk_select(shared.cpu().double().numpy(), keep))
+
+
 # --------------------------------------------------------------------------------------------- S3 + S4
 @pytest.mark.parametrize("dtype,h_kv,d", [("bf16", 4, 128), ("f32", 2, 64)])
 @pytest.mark.parametrize("n_g,keep,ties", [(4, 2, True), (1, 1, False), (100, 100, True), (1000, 1, True),
@@ -268,11 +322,11 @@ def _run_prefill(w, q, k, v, qw, rule, kernel=B.QP_ATTEND_AUTO):
     layout = B.make_layout(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
     cap = B.cache_capacity(w.n_frames, w.tokens_per_frame, w.group_frames, w.retention)
     cache = B.Cache(layout, cap)
-    ws = B.make_workspace(layout, min(w.group_tokens, w.n_tokens), w.n_window if rule == "window_attn" else 0)
+    ws = B.make_workspace(layout, min(w.group_tokens, w.n_tokens), w.n_window if rule.startswith("window") else 0)
     out = torch.full_like(q, float("nan"))
     B.select_attend_kernel(kernel)
     B.prefill_video(layout, w.n_frames, w.tokens_per_frame, w.group_frames, w.retention, rule, q, k, v,
-                    qw if rule == "window_attn" else None, cache, out, ws)
+                    qw if rule.startswith("window") else None, cache, out, ws)
     torch.cuda.synchronize()
     return out, cache
 
@@ -362,6 +416,20 @@ def test_reduced_configs_whole_path_full_oracle(name, frames, tokens_per_frame, 
             # a near-tie changes the cache, hence later outputs: then the oracle attends over the validated choice
             ref = want if near == 0 else _oracle_outputs(w, q, k, v, sel_valid)
             assert_attn_close(_f64(out), ref, w.dtype, f"{name} kernel {kern}")
+
+
+@pytest.mark.parametrize("rule", ["window_logit", "key_norm_small+shared", "window_attn+shared"])
+def test_rule_variants_whole_path(rule):
+    """The rule variants through qp_prefill_video on a reduced config-2 shape, every output element against the oracle."""
+    w = scaled(CONFIGS["cfg2_7b_32k"], n_frames=12, tokens_per_frame=40, group_frames=5)
+    q, k, v, qw = make_layer(w, sharp=True)
+    dq, dk, dv, dqw = q.to(DEV), k.to(DEV), v.to(DEV), qw.to(DEV)
+    out, cache = _run_prefill(w, dq, dk, dv, dqw, rule)
+    _, _, near, sel_valid = _check_cache_against_oracle(w, k, v, qw, rule, cache)
+    if rule.endswith("+shared"):
+        pos = cache.pos.cpu().numpy()[:, :cache.len]
+        assert (pos == pos[0]).all()
+    assert_attn_close(_f64(out), _oracle_outputs(w, q, k, v, sel_valid), w.dtype, rule)
 
 
 def _full_size_check(w, rule, sharp, n_rows, layer=0):
