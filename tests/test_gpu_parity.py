@@ -99,6 +99,31 @@ def test_group_attend_key_split_matches_oracle(h_q, h_kv, n_g, c):
 
 
 @pytest.mark.gpu
+def test_group_attend_key_split_at_the_chunk_limit():
+    """One workgroup's worth of rows against 24566 cache entries: the large kernel splits into its maximum of 128
+    chunks, and the merge kernel takes two batches per wavefront."""
+    h_q, h_kv, d, n_g, c = 64, 1, 128, 2, 24566
+    g = torch.Generator().manual_seed(99)
+    mk = lambda *s: torch.randn(*s, generator=g).to(torch.bfloat16)
+    q, k, v, ck, cv = mk(n_g, h_q, d), mk(n_g, h_kv, d), mk(n_g, h_kv, d), mk(h_kv, c, d), mk(h_kv, c, d)
+    want, want_lse = O.attend_group(_f64(q), _f64(k), _f64(v), _f64(ck), _f64(cv), return_lse=True)
+    layout = B.make_layout(h_q, h_kv, d, "bf16")
+    cache = B.Cache(layout, c)
+    cache.k.copy_(ck)
+    cache.v.copy_(cv)
+    cache.c.len = c
+    ws = B.make_workspace(layout, 32, 0)
+    plan = B.attend_plan(layout, n_g, c, ws.numel())
+    assert plan["kernel"] == B.QP_ATTEND_MFMA and plan["key_chunks"] == 128
+    out = torch.full((n_g, h_q, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    lse = torch.full((h_q, n_g), float("nan"), dtype=torch.float32, device=DEV)
+    B.group_attend(layout, q.to(DEV), k.to(DEV), v.to(DEV), cache, out, lse, ws)
+    torch.cuda.synchronize()
+    assert_attn_close(_f64(out), want, "bf16", "128 chunks")
+    np.testing.assert_allclose(_f64(lse), want_lse, rtol=2e-5, atol=2e-3)
+
+
+@pytest.mark.gpu
 @pytest.mark.parametrize("h_q,h_kv,n_g", [(28, 4, 1), (28, 4, 4), (64, 8, 3), (6, 3, 16), (4, 4, 32), (32, 1, 1)])
 @pytest.mark.parametrize("c", [0, 1, 31, 32, 33, 127, 128, 129, 1000, 4097])
 def test_decode_shaped_attend_matches_oracle(h_q, h_kv, n_g, c):
