@@ -100,7 +100,8 @@ SideStreams* side_streams() {
   return g.ok ? &g : nullptr;
 }
 
-// Workspace layout of qp_prefill_video: [scores H_kv*n_g f32][kept indices H_kv*n_g i32][window scratch].
+// Workspace layout of qp_prefill_video: [scores H_kv*n_g f32][kept indices H_kv*n_g i32][scoring scratch] ... and, at
+// the end, one key-split area of kAttendSplitBytes per attention stream.
 size_t scores_bytes(const qp_layout* L, int32_t n_g) { return round256((size_t)L->n_kv_heads * n_g * sizeof(float)); }
 
 }  // namespace
@@ -216,7 +217,7 @@ qp_status qp_group_attend(const qp_layout* L, const void* q_g, const void* k_g, 
   if (!aligned16(q_g) || !aligned16(k_g) || !aligned16(v_g) || !aligned16(out_g)) return QP_ERR_INVALID_ARG;
   if (lse && (((uintptr_t)lse) & 3u)) return QP_ERR_INVALID_ARG;
 
-  qp::AttendArgs a;
+  qp::AttendArgs a{};
   a.q = q_g;
   a.k = k_g;
   a.v = v_g;
