@@ -127,3 +127,12 @@ def test_product_path_does_not_touch_the_oracle():
             if f.endswith((".py", ".hip", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.replace("the CPU oracle's tests", ""), f
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: `bench.py --gpus N` with N > 1 says so and exits without touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
