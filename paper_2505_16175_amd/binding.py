@@ -1,7 +1,7 @@
 """Thin ctypes binding of libqp_hip.so: argument marshalling only.
 
 Every function has the name and argument order of its C-ABI counterpart in include/qp.h
-and takes torch tensors on the GPU (device memory and streams are all torch is used for).
+(the path) or include/qp_layer.h (the decoder layer around it) and takes torch tensors on the GPU (device memory and streams are all torch is used for).
 There is no CPU fallback: if the library is missing, loading raises.
 """
 from __future__ import annotations
@@ -41,6 +41,16 @@ class qp_attend_plan_info(ctypes.Structure):
                 ("scratch_bytes", ctypes.c_size_t)]
 
 
+class qp_layer_shape(ctypes.Structure):
+    _fields_ = [("d_model", ctypes.c_int32), ("d_ff", ctypes.c_int32), ("rms_eps", ctypes.c_float),
+                ("rope_theta", ctypes.c_float), ("mrope_section", ctypes.c_int32 * 3)]
+
+
+class qp_layer_weights(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_void_p) for name in
+                ("ln1_w", "w_qkv", "b_qkv", "w_o", "ln2_w", "w_gate_up", "w_down")]
+
+
 class QPError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
@@ -50,6 +60,7 @@ class QPError(RuntimeError):
 _lib = None
 _vp, _i32, _i64, _f64, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_double, ctypes.c_size_t
 _LP, _CP = ctypes.POINTER(qp_layout), ctypes.POINTER(qp_cache)
+_SP, _WP, _f32 = ctypes.POINTER(qp_layer_shape), ctypes.POINTER(qp_layer_weights), ctypes.c_float
 
 SIGNATURES = {
     "qp_keep_count": (_i64, [_i64, _f64]),
@@ -64,6 +75,16 @@ SIGNATURES = {
     "qp_status_string": (ctypes.c_char_p, [_i32]),
     "qp_last_hip_error": (ctypes.c_int, []),
     "qp_version": (ctypes.c_char_p, []),
+    # include/qp_layer.h
+    "qp_rms_norm": (_i32, [_vp, _vp, _vp, _i32, _i32, _f32, _vp]),
+    "qp_linear": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp]),
+    "qp_rope_table": (_i32, [_vp, _i64, _i32, _f32, ctypes.POINTER(ctypes.c_int32), _vp, _vp]),
+    "qp_qkv_rope": (_i32, [_LP, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]),
+    "qp_swiglu_gate_up": (_i32, [_vp, _vp, _vp, _i32, _i32, _i32, _vp]),
+    "qp_layer_workspace_bytes": (_sz, [_LP, _SP, _i32, _i32]),
+    "qp_layer_group": (_i32, [_LP, _SP, _WP, _vp, _vp, _i64, _i32, _i32, _vp, _i32, _i32, _i32, _CP, _vp, _vp, _vp,
+                              _sz, _vp]),
+    "qp_layer_window_queries": (_i32, [_LP, _SP, _WP, _vp, _vp, _i64, _i32, _vp, _vp, _sz, _vp]),
 }
 
 
@@ -205,3 +226,79 @@ def prefill_video(layout, n_frames, tokens_per_frame, group_frames, retention, r
                                 0 if q_win is None else q_win.shape[0], ctypes.byref(cache.c), _ptr(out), wp, wb,
                                 _stream())
     _check(st, "qp_prefill_video")
+
+
+# ---- include/qp_layer.h: the decoder layer around the path -------------------------------------------------
+def make_layer_shape(d_model, d_ff, rms_eps=1e-6, rope_theta=1e6, mrope_section=(16, 24, 24)) -> qp_layer_shape:
+    return qp_layer_shape(d_model, d_ff, rms_eps, rope_theta, (ctypes.c_int32 * 3)(*mrope_section))
+
+
+class LayerWeights:
+    """Keeps a layer's weight tensors alive next to the qp_layer_weights struct that points at them."""
+
+    def __init__(self, ln1_w, w_qkv, b_qkv, w_o, ln2_w, w_gate_up, w_down):
+        self.tensors = dict(ln1_w=ln1_w, w_qkv=w_qkv, b_qkv=b_qkv, w_o=w_o, ln2_w=ln2_w, w_gate_up=w_gate_up,
+                            w_down=w_down)
+        self.c = qp_layer_weights(**{name: _ptr(t).value for name, t in self.tensors.items()})
+
+
+def rms_norm(x, w, out, eps):
+    _check(lib().qp_rms_norm(_ptr(x), _ptr(w), _ptr(out), x.shape[0], x.shape[1], eps, _stream()), "qp_rms_norm")
+
+
+def linear(x, w, bias, residual, out):
+    _check(lib().qp_linear(_ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(out), x.shape[0], w.shape[0], x.shape[1],
+                           _stream()), "qp_linear")
+
+
+def _pos_ptr(pos, first, axis_stride):
+    """pos: int32 [3][N] on the GPU; the group starts at token `first`."""
+    if pos.dtype != torch.int32 or not pos.is_cuda or not pos.is_contiguous() or pos.shape[0] != 3:
+        raise ValueError("expected a contiguous int32 [3][N] GPU tensor of position indices")
+    return ctypes.c_void_p(pos.data_ptr() + 4 * first), (pos.shape[1] if axis_stride is None else axis_stride)
+
+
+def rope_table(pos, first, n_tokens, theta, mrope_section, cos_sin):
+    pp, stride = _pos_ptr(pos, first, None)
+    _check(lib().qp_rope_table(pp, stride, n_tokens, theta, (ctypes.c_int32 * 3)(*mrope_section), _ptr(cos_sin),
+                               _stream()), "qp_rope_table")
+
+
+def qkv_rope(layout, h, w_qkv, b_qkv, cos_sin, q, k, v):
+    _check(lib().qp_qkv_rope(ctypes.byref(layout), _ptr(h), _ptr(w_qkv), _ptr(b_qkv), _ptr(cos_sin), h.shape[0],
+                             h.shape[1], _ptr(q), _ptr(k), _ptr(v), _stream()), "qp_qkv_rope")
+
+
+def swiglu_gate_up(h, w_gate_up, act):
+    _check(lib().qp_swiglu_gate_up(_ptr(h), _ptr(w_gate_up), _ptr(act), h.shape[0], h.shape[1],
+                                   w_gate_up.shape[0] // 2, _stream()), "qp_swiglu_gate_up")
+
+
+def layer_workspace_bytes(layout, shape, max_group_tokens, n_window) -> int:
+    return lib().qp_layer_workspace_bytes(ctypes.byref(layout), ctypes.byref(shape), max_group_tokens, n_window)
+
+
+def make_layer_workspace(layout, shape, max_group_tokens, n_window, device="cuda") -> torch.Tensor:
+    n = layer_workspace_bytes(layout, shape, max_group_tokens, n_window)
+    if n == 0:
+        raise QPError(QP_ERR_INVALID_ARG, "qp_layer_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def layer_group(layout, shape, weights: LayerWeights, x_g, pos, first, group_token_base, q_win, rule, keep,
+                cache: Cache, x_out, kept_idx, workspace):
+    wp, wb = _ws(workspace)
+    pp, stride = _pos_ptr(pos, first, None)
+    st = lib().qp_layer_group(ctypes.byref(layout), ctypes.byref(shape), ctypes.byref(weights.c), _ptr(x_g), pp, stride,
+                              x_g.shape[0], group_token_base, _ptr(q_win), 0 if q_win is None else q_win.shape[0],
+                              RULES.get(rule, rule), keep, ctypes.byref(cache.c), _ptr(x_out), _ptr(kept_idx), wp, wb,
+                              _stream())
+    _check(st, "qp_layer_group")
+
+
+def layer_window_queries(layout, shape, weights: LayerWeights, x_win, pos_win, q_win_out, workspace):
+    wp, wb = _ws(workspace)
+    pp, stride = _pos_ptr(pos_win, 0, None)
+    st = lib().qp_layer_window_queries(ctypes.byref(layout), ctypes.byref(shape), ctypes.byref(weights.c), _ptr(x_win),
+                                       pp, stride, x_win.shape[0], _ptr(q_win_out), wp, wb, _stream())
+    _check(st, "qp_layer_window_queries")

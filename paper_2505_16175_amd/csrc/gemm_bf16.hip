@@ -1,0 +1,287 @@
+// bf16 MFMA matrix product for the projections of the decoder layer around the path (gfx950):
+//   Y[m][n] = sum_k X[m][k] W[n][k]      X [M][K] activations (tokens slow), W [N][K] weights ([out][in]),
+// f32 accumulation, with the layer's elementwise steps fused into the store:
+//   PLAIN    Y (+ bias[n]) (+ residual[m][n]) -> bf16 [M][N]          (o_proj and down_proj with the residual add)
+//   QKV_ROPE Y + bias, rotary embedding on the query and key heads, scattered to Q [M][H_q][128],
+//            K [M][H_kv][128], V [M][H_kv][128] (the token-major layout the attention kernels read)
+//   SWIGLU   W = [gate rows ; up rows] (2 d_ff rows): SiLU(gate) * up -> bf16 [M][d_ff]
+//            (Appendix D.1 of the paper: SwiGLU(x) = W_down(SiLU(W_gate x) * W_up x))
+//
+// Tiling. A workgroup of 8 wavefronts owns a 256 x 256 output tile and walks K in steps of 64. Both operand
+// tiles (256 rows x 128 bytes each) go global -> LDS with global_load_lds_dwordx4 into a ring of buffers, the
+// next step's tiles in flight while this step's are multiplied; one barrier per step. Rows are unpadded; the
+// 16-byte chunk c of row r sits at position c ^ ((r >> 1) & 7), which makes both the 1 KB stores of the loads
+// and the fragment reads (32 rows x 16 bytes per half wavefront) conflict-free.
+// Wavefront (wm, wn) of the 2 x 4 arrangement computes 128 tokens x 64 outputs as 4 x 2 blocks of
+// v_mfma_f32_32x32x16_bf16 with the WEIGHT rows as the A operand and the token rows as B, so that a lane ends
+// up with one token (m = lane & 31) and, per block, 16 outputs in runs of 4: stores are 8-byte runs of a token's
+// row, and the fused steps below only ever combine values of the same lane:
+//   * QKV_ROPE: the 256 tile columns are two heads; wavefront wn serves head wn >> 1 and, of its 128 dims, the
+//     32 dims [32 (wn & 1), +32) in block 0 and their rotary partners (+64) in block 1. The weight rows are
+//     fetched into LDS in that order (a permutation inside the tile, contiguous in runs of 32 rows).
+//   * SWIGLU: block 0 holds gate columns [n0/2 + 32 wn, +32), block 1 the up columns of the same outputs.
+// Workgroup ids are dealt round-robin over the 8 XCDs; inside an XCD consecutive workgroups walk the token
+// tiles of one weight tile, so a weight tile is fetched into that XCD's L2 once while the (smaller)
+// activations are shared by all of them.
+#include "qp_internal.h"
+
+namespace qp {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int GM_BM = 256, GM_BN = 256, GM_BK = 64;
+constexpr int GM_NW = 8;
+constexpr int GM_ROWB = GM_BK * 2;                    // bytes per tile row
+constexpr int GM_XT = GM_BM * GM_ROWB;                // bytes of the activation tile
+constexpr int GM_STAGE = (GM_BM + GM_BN) * GM_ROWB;   // one ring slot: activation tile + weight tile
+constexpr int GM_STAGES = 2;
+
+template <int N>
+__device__ __forceinline__ void gm_wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// LDS row j of the weight tile <- which weight row (relative to the tile's first), per mode
+template <int MODE>
+__device__ __forceinline__ int weight_row(int j, int n0, int d_ff) {
+  if (MODE == GEMM_QKV_ROPE) return n0 + (j & ~127) + ((j >> 5) & 1) * 64 + ((j >> 6) & 1) * 32 + (j & 31);
+  if (MODE == GEMM_SWIGLU) return ((j >> 5) & 1) * d_ff + (n0 >> 1) + (j >> 6) * 32 + (j & 31);
+  return n0 + j;
+}
+
+template <int MODE>
+__global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, g = lane >> 5;
+  const int wm = wave >> 2, wn = wave & 3;
+
+  // workgroup id -> (weight tile, token tile)
+  const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+  const int tn = xcd + 8 * (idx / a.tiles_m), tm = idx % a.tiles_m;
+  if (tn >= a.tiles_n) return;  // padding of the XCD mapping (whole workgroup, before any barrier)
+  const int m0 = tm * GM_BM, n0 = tn * GM_BN;
+  const int d_ff = a.n >> 1;
+
+  // staging: load instruction q of this wavefront covers tile rows 32 wave + 8 q + (lane >> 3), position lane & 7
+  const unsigned char* xg = (const unsigned char*)a.x;
+  const unsigned char* wg = (const unsigned char*)a.w;
+  const size_t row_b = (size_t)a.k * 2;
+  unsigned x_off[4], w_off[4];
+  const int wb = MODE == GEMM_SWIGLU ? (n0 >> 1) : n0;  // first weight row this tile touches
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int r = 32 * wave + 8 * q + (lane >> 3);
+    const unsigned chunk = (unsigned)((lane & 7) ^ ((r >> 1) & 7)) * 16;
+    const int xr = min(m0 + r, a.m - 1);  // rows past the end: computed, not stored
+    const int wr = min(weight_row<MODE>(r, n0, d_ff), a.n - 1);
+    // offsets relative to the tile's first row (the launcher checks that they fit 32 bits)
+    x_off[q] = (unsigned)((size_t)(xr - m0) * row_b) + chunk;
+    w_off[q] = (unsigned)((size_t)(wr - wb) * row_b) + chunk;
+  }
+  const unsigned char* x_base = xg + (size_t)m0 * row_b;
+  const unsigned char* w_base = wg + (size_t)wb * row_b;
+  const int st_lds = wave * 4096;
+
+#define GM_ISSUE(step_, slot_)                                                     \
+  {                                                                                \
+    const unsigned koff_ = (unsigned)(step_) * GM_ROWB;                            \
+    unsigned char* xd_ = smem + (slot_)*GM_STAGE + st_lds;                         \
+    unsigned char* wd_ = xd_ + GM_XT;                                              \
+    _Pragma("unroll") for (int q_ = 0; q_ < 4; ++q_) {                             \
+      lds_dma16(x_base, x_off[q_] + koff_, xd_ + 1024 * q_);                       \
+      lds_dma16(w_base, w_off[q_] + koff_, wd_ + 1024 * q_);                       \
+    }                                                                              \
+  }
+
+  // fragment addresses inside a slot: row (l32 + 32 block), chunk 2 s + g of k-step s
+  int f_off[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) f_off[s] = l32 * GM_ROWB + (((2 * s + g) ^ ((l32 >> 1) & 7)) << 4);
+  const int x_frag = wm * 128 * GM_ROWB;
+  const int w_frag = GM_XT + wn * 64 * GM_ROWB;
+
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
+
+  const int n_steps = a.k / GM_BK;
+  GM_ISSUE(0, 0)
+  for (int step = 0; step < n_steps; ++step) {
+    const int slot = step & 1;
+    gm_wait_vmcnt<0>();   // this wavefront's part of the step's tiles has landed
+    __syncthreads();      // ... everyone's has, and everyone is done reading the other slot
+    if (step + 1 < n_steps) GM_ISSUE(step + 1, slot ^ 1)
+    const unsigned char* st = smem + slot * GM_STAGE;
+    // fragments of k-step s+1 are read while the products of k-step s run (two register sets)
+    u32x4 wf[2][2], xf[2][4];
+#define GM_READ(s_, b_)                                                                                      \
+  {                                                                                                          \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j) wf[b_][j] = *(const u32x4*)(st + w_frag + j * 32 * GM_ROWB + f_off[s_]); \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) xf[b_][i] = *(const u32x4*)(st + x_frag + i * 32 * GM_ROWB + f_off[s_]); \
+  }
+    GM_READ(0, 0)
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      if (s < 3) GM_READ(s + 1, (s + 1) & 1)
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[s & 1][j]),
+                                                              __builtin_bit_cast(bf16x8, xf[s & 1][i]), acc[j][i], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#undef GM_READ
+  }
+#undef GM_ISSUE
+
+  // ---- store: lane owns token m = m0 + 128 wm + 32 i + l32 and, in block j, outputs 8 (r >> 2) + 4 g + (r & 3)
+  if (MODE == GEMM_PLAIN) {
+    const bf16_t* bias = (const bf16_t*)a.bias;
+    const bf16_t* res = (const bf16_t*)a.residual;
+    bf16_t* out = (bf16_t*)a.out;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int n = n0 + wn * 64 + j * 32 + 8 * q4 + 4 * g;
+        if (n >= a.n) continue;
+        float b[4] = {0.f, 0.f, 0.f, 0.f};
+        if (bias != nullptr) {
+          const uint2 raw = *(const uint2*)(bias + n);
+          b[0] = bf16lo_to_f32(raw.x), b[1] = bf16hi_to_f32(raw.x), b[2] = bf16lo_to_f32(raw.y), b[3] = bf16hi_to_f32(raw.y);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int m = m0 + wm * 128 + i * 32 + l32;
+          if (m >= a.m) continue;
+          float y[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) y[e] = acc[j][i][4 * q4 + e] + b[e];
+          if (res != nullptr) {
+            const uint2 raw = *(const uint2*)(res + (size_t)m * a.n + n);
+            y[0] += bf16lo_to_f32(raw.x), y[1] += bf16hi_to_f32(raw.x), y[2] += bf16lo_to_f32(raw.y), y[3] += bf16hi_to_f32(raw.y);
+          }
+          bf16x4 pk;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) pk[e] = (__bf16)y[e];
+          *(uint2*)(out + (size_t)m * a.n + n) = __builtin_bit_cast(uint2, pk);
+        }
+      }
+  } else if (MODE == GEMM_QKV_ROPE) {
+    // head of this wavefront and where its rows go
+    const int head = (n0 >> 7) + (wn >> 1);
+    const int dim0 = (wn & 1) * 32;  // block 0: dims dim0 + ..., block 1: dim0 + 64 + ...
+    const bf16_t* bias = (const bf16_t*)a.bias + (size_t)head * 128;
+    bf16_t* dst;
+    int heads_dst, head_dst;
+    bool rotate = true;
+    if (head < a.h_q) dst = (bf16_t*)a.q, heads_dst = a.h_q, head_dst = head;
+    else if (head < a.h_q + a.h_kv) dst = (bf16_t*)a.k_out, heads_dst = a.h_kv, head_dst = head - a.h_q;
+    else dst = (bf16_t*)a.v_out, heads_dst = a.h_kv, head_dst = head - a.h_q - a.h_kv, rotate = false;
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int f = dim0 + 8 * q4 + 4 * g;  // rotary frequency index of the run's first element
+      float b0[4], b1[4];
+      {
+        const uint2 r0 = *(const uint2*)(bias + f), r1 = *(const uint2*)(bias + 64 + f);
+        b0[0] = bf16lo_to_f32(r0.x), b0[1] = bf16hi_to_f32(r0.x), b0[2] = bf16lo_to_f32(r0.y), b0[3] = bf16hi_to_f32(r0.y);
+        b1[0] = bf16lo_to_f32(r1.x), b1[1] = bf16hi_to_f32(r1.x), b1[2] = bf16lo_to_f32(r1.y), b1[3] = bf16hi_to_f32(r1.y);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int m = m0 + wm * 128 + i * 32 + l32;
+        if (m >= a.m) continue;
+        float lo[4], hi[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) lo[e] = acc[0][i][4 * q4 + e] + b0[e], hi[e] = acc[1][i][4 * q4 + e] + b1[e];
+        if (rotate) {
+          const float4 cs0 = *(const float4*)(a.cos_sin + ((size_t)m * 64 + f) * 2);
+          const float4 cs1 = *(const float4*)(a.cos_sin + ((size_t)m * 64 + f + 2) * 2);
+          const float c[4] = {cs0.x, cs0.z, cs1.x, cs1.z}, s[4] = {cs0.y, cs0.w, cs1.y, cs1.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float x0 = lo[e], x1 = hi[e];
+            lo[e] = x0 * c[e] - x1 * s[e];
+            hi[e] = x1 * c[e] + x0 * s[e];
+          }
+        }
+        bf16x4 p0, p1;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) p0[e] = (__bf16)lo[e], p1[e] = (__bf16)hi[e];
+        bf16_t* row = dst + ((size_t)m * heads_dst + head_dst) * 128;
+        *(uint2*)(row + f) = __builtin_bit_cast(uint2, p0);
+        *(uint2*)(row + 64 + f) = __builtin_bit_cast(uint2, p1);
+      }
+    }
+  } else {  // GEMM_SWIGLU
+    bf16_t* out = (bf16_t*)a.out;
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int n = (n0 >> 1) + wn * 32 + 8 * q4 + 4 * g;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int m = m0 + wm * 128 + i * 32 + l32;
+        if (m >= a.m) continue;
+        bf16x4 pk;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float gate = acc[0][i][4 * q4 + e], up = acc[1][i][4 * q4 + e];
+          pk[e] = (__bf16)(gate / (1.f + __expf(-gate)) * up);
+        }
+        *(uint2*)(out + (size_t)m * d_ff + n) = __builtin_bit_cast(uint2, pk);
+      }
+    }
+  }
+}
+
+bool gemm_supported(const GemmArgs& a, int mode) {
+  if (a.m <= 0 || a.n <= 0 || a.k <= 0 || a.k % GM_BK != 0) return false;
+  // byte offsets inside a tile's row range are 32-bit (plus the k offset of the step)
+  const size_t span = (size_t)(mode == GEMM_SWIGLU ? a.n / 2 + GM_BN : GM_BN) * a.k * 2 + (size_t)a.k * 2;
+  if (span >= ((size_t)1 << 32)) return false;
+  if (mode == GEMM_PLAIN) return a.n % 8 == 0;
+  if (mode == GEMM_QKV_ROPE) return a.h_q > 0 && a.h_kv > 0 && a.n == (a.h_q + 2 * a.h_kv) * 128 && a.n % GM_BN == 0;
+  if (mode == GEMM_SWIGLU) return a.n % (2 * 128) == 0 && a.n % GM_BN == 0;
+  return false;
+}
+
+template <int MODE>
+static hipError_t launch_mode(GemmArgs a, hipStream_t s) {
+  static bool attr_done[QP_MAX_DEVICES] = {};
+  const int dev = current_device();
+  if (dev < 0) return hipErrorInvalidDevice;
+  const int lds = GM_STAGES * GM_STAGE;
+  if (!attr_done[dev]) {
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_kernel<MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    attr_done[dev] = true;
+  }
+  a.tiles_m = (a.m + GM_BM - 1) / GM_BM;
+  a.tiles_n = (a.n + GM_BN - 1) / GM_BN;
+  const int groups = (a.tiles_n + 7) / 8;
+  hipLaunchKernelGGL(gemm_bf16_kernel<MODE>, dim3(8 * groups * a.tiles_m), dim3(GM_NW * 64), lds, s, a);
+  return hipSuccess;
+}
+
+hipError_t launch_gemm_bf16(const GemmArgs& a, int mode, hipStream_t s) {
+  switch (mode) {
+    case GEMM_PLAIN: return launch_mode<GEMM_PLAIN>(a, s);
+    case GEMM_QKV_ROPE: return launch_mode<GEMM_QKV_ROPE>(a, s);
+    case GEMM_SWIGLU: return launch_mode<GEMM_SWIGLU>(a, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace qp

@@ -108,6 +108,8 @@ size_t scores_bytes(const qp_layout* L, int32_t n_g) { return round256((size_t)L
 
 namespace qp {
 
+void note_hip_error(int e) { g_last_hip_error = e; }
+
 int current_device() {
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess) {

@@ -133,6 +133,7 @@ void launch_attend_decode(const AttendArgs& a, void* split_ws, size_t split_ws_b
 constexpr int QP_MAX_DEVICES = 64;
 int current_device();   // index of the current HIP device, -1 if there is none or it does not fit the arrays
 int device_cu_count();  // compute units of the current device; 256 (MI355X) if it cannot be asked
+void note_hip_error(int e);  // what qp_last_hip_error() reports on this thread
 
 void launch_score_norm(const void* x, int dtype, int n_g, int h_kv, int d, float sign, float* scores, hipStream_t s);
 
@@ -164,5 +165,27 @@ struct TopkArgs {
 };
 size_t topk_workspace_bytes(int h_kv, int keep);
 hipError_t launch_topk_compact(const TopkArgs& a, int dtype, int32_t* kept_ws, hipStream_t s);
+
+// ---- decoder layer around the path: projections with fused elementwise steps, RMSNorm, rotary table ----
+enum GemmMode { GEMM_PLAIN = 0, GEMM_QKV_ROPE = 1, GEMM_SWIGLU = 2 };
+struct GemmArgs {
+  const void* x;         // [m][k] bf16 activations
+  const void* w;         // [n][k] bf16 weights ([out][in]); SWIGLU: n = 2 d_ff, gate rows then up rows
+  const void* bias;      // [n] bf16 or nullptr (PLAIN); required for QKV_ROPE
+  const void* residual;  // [m][n] bf16 or nullptr (PLAIN)
+  void* out;             // PLAIN: [m][n]; SWIGLU: [m][n / 2]
+  void* q;               // QKV_ROPE: [m][h_q][128]
+  void* k_out;           //           [m][h_kv][128]
+  void* v_out;           //           [m][h_kv][128]
+  const float* cos_sin;  // QKV_ROPE: [m][64][2] f32, (cos, sin) of each token's 64 rotation angles
+  int m, n, k;
+  int h_q, h_kv;
+  int tiles_m, tiles_n;  // filled by the launcher
+};
+bool gemm_supported(const GemmArgs& a, int mode);
+hipError_t launch_gemm_bf16(const GemmArgs& a, int mode, hipStream_t s);
+void launch_rms_norm(const void* x, const void* w, void* out, int n_tokens, int d_model, float eps, hipStream_t s);
+void launch_rope_table(const int32_t* pos, long axis_stride, int n_tokens, float theta, int s0, int s1, float* cos_sin,
+                       hipStream_t s);
 
 }  // namespace qp

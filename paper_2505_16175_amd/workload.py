@@ -154,3 +154,63 @@ def to_f64(t: Optional[torch.Tensor]):
     if t is None:
         return None
     return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+# ---- inputs of the decoder layer around the path (weights, hidden states, position indices) -----------------
+@dataclasses.dataclass(frozen=True)
+class LayerDims:
+    """Sizes of a Qwen2.5-style decoder layer (head_dim 128)."""
+    d_model: int
+    d_ff: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int = 128
+    rms_eps: float = 1e-6
+    rope_theta: float = 1e6
+    mrope_section: tuple = (16, 24, 24)
+
+
+LAYER_DIMS = {
+    "7b": LayerDims(3584, 18944, 28, 4),
+    "72b": LayerDims(8192, 29568, 64, 8),
+}
+
+
+def make_decoder_layer(dims: LayerDims, layer: int = 0, device: str = "cpu", seed: Optional[int] = None):
+    """Random-init bf16 weights of one layer, [out][in]: N(0, 1/in) matrices, norm weights 1 + 0.1 N(0,1),
+    biases 0.1 N(0,1). Keys: ln1_w, w_qkv (query heads, key heads, value heads), b_qkv, w_o, ln2_w,
+    w_gate_up (gate rows, then up rows), w_down."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed((BASE_SEED if seed is None else seed) + 7919 * (layer + 1))
+    dm, dff = dims.d_model, dims.d_ff
+    n_qkv = (dims.n_q_heads + 2 * dims.n_kv_heads) * dims.head_dim
+    rn = lambda *s: torch.randn(*s, generator=gen, dtype=torch.float32, device=device)
+    w = dict(ln1_w=1.0 + 0.1 * rn(dm), w_qkv=rn(n_qkv, dm) / math.sqrt(dm), b_qkv=0.1 * rn(n_qkv),
+             w_o=rn(dm, dims.n_q_heads * dims.head_dim) / math.sqrt(dims.n_q_heads * dims.head_dim),
+             ln2_w=1.0 + 0.1 * rn(dm), w_gate_up=rn(2 * dff, dm) / math.sqrt(dm), w_down=rn(dm, dff) / math.sqrt(dff))
+    return {name: t.to(torch.bfloat16) for name, t in w.items()}
+
+
+def make_hidden(n_frames, tokens_per_frame, d_model, corr_a=0.9, corr_b=0.44, device="cpu", seed=None):
+    """Hidden states [N, d_model] entering a layer: N(0,1) channels with the same AR(1) inter-frame
+    correlation as the Q/K/V recipe above, bf16."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed((BASE_SEED if seed is None else seed) + 104729)
+    return _ar1(gen, n_frames, tokens_per_frame, 1, d_model, corr_a, corr_b, device).view(-1, d_model).to(torch.bfloat16)
+
+
+def video_positions(n_frames, tokens_per_frame, device="cpu", first_frame=0):
+    """Position indices [3][N] int32 of a video's tokens: (frame index, row, column) of a token grid as square as
+    tokens_per_frame allows (row-major inside a frame)."""
+    gw = int(math.isqrt(tokens_per_frame))
+    while tokens_per_frame % gw:
+        gw -= 1
+    slot = torch.arange(tokens_per_frame, dtype=torch.int32, device=device)
+    t = torch.arange(first_frame, first_frame + n_frames, dtype=torch.int32, device=device).repeat_interleave(tokens_per_frame)
+    return torch.stack([t, (slot // gw).repeat(n_frames), (slot % gw).repeat(n_frames)]).contiguous()
+
+
+def text_positions(n_tokens, start, device="cpu"):
+    """Text tokens carry the same index on all three axes."""
+    p = torch.arange(start, start + n_tokens, dtype=torch.int32, device=device)
+    return torch.stack([p, p, p]).contiguous()

@@ -12,15 +12,30 @@ from paper_2505_16175_amd.workload import CONFIGS
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "qp.h")).read()
-    body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(qp_[a-z_0-9]+)\s*\(", body))
-    assert {"qp_group_attend", "qp_score_kv", "qp_topk_compact", "qp_prefill_video"} <= declared
+    declared = set()
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        header = open(os.path.join(ROOT, "include", name)).read()
+        body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        declared |= set(re.findall(r"\b(qp_[a-z_0-9]+)\s*\(", body))
+    assert {"qp_group_attend", "qp_score_kv", "qp_topk_compact", "qp_prefill_video", "qp_layer_group"} <= declared
     handle = ctypes.CDLL(B.LIB_PATH)
     for name in sorted(declared):
-        assert hasattr(handle, name), f"{name} declared in qp.h but not exported"
-    assert declared == set(B.SIGNATURES), "binding and header disagree on the entry points"
+        assert hasattr(handle, name), f"{name} declared in include/ but not exported"
+    assert declared == set(B.SIGNATURES), "binding and headers disagree on the entry points"
     assert B.version().startswith("quickprefill")
+
+
+def test_layer_workspace_and_shape_errors():
+    L = B.make_layout(28, 4, 128, "bf16")
+    S = B.make_layer_shape(3584, 18944)
+    n = B.layer_workspace_bytes(L, S, 2048, 64)
+    acts = 2048 * 2 * (2 * 3584 + 2 * 28 * 128 + 2 * 4 * 128 + 18944)          # h (reused for h2), x1, q, attn, k, v, act
+    assert n >= acts + B.workspace_bytes(L, 2048, 64)
+    assert n < acts + B.workspace_bytes(L, 2048, 64) + (4 << 20)
+    assert B.layer_workspace_bytes(L, S, 0, 0) == 0
+    assert B.layer_workspace_bytes(B.make_layout(28, 4, 64, "bf16"), S, 128, 0) == 0       # head_dim 128 only
+    assert B.layer_workspace_bytes(L, B.make_layer_shape(3584, 18944, mrope_section=(16, 24, 20)), 128, 0) == 0
+    assert B.layer_workspace_bytes(L, B.make_layer_shape(3584 + 8, 18944), 128, 0) == 0
 
 
 def test_host_arithmetic_matches_oracle_and_golden():

@@ -1,0 +1,268 @@
+"""GPU parity of the decoder layer around the path (include/qp_layer.h) against the fp64 layer oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer_oracle as LO
+from oracle import qp_oracle as O
+from paper_2505_16175_amd import binding as B
+from paper_2505_16175_amd import workload as W
+from paper_2505_16175_amd.workload import to_f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+# A stored bf16 value is the rounding of an f32-accumulated sum; the oracle rounds the exact sum at the same place.
+# The two differ only where the f32 and the exact value straddle a rounding boundary: one bf16 ulp (<= 2^-7 of the
+# value). The absolute floor covers outputs that are small by cancellation (f32 summation error relative to the
+# tensor's RMS). A wrong index, operand or epilogue produces errors of the size of the RMS itself.
+def assert_stored_close(got, want, what, ulps=1.0, floor=2e-4, nrm=3e-3):
+    got, want = np.asarray(got, dtype=np.float64), np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape, (got.shape, want.shape)
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    rms = np.sqrt(np.mean(want * want))
+    err = np.abs(got - want)
+    bad = err > ulps * 2.0 ** -7 * np.abs(want) + floor * rms
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} out of tolerance, max err {err.max():.3e} (rms {rms:.3e})"
+    rel = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-300)
+    assert rel <= nrm, f"{what}: normalised error {rel:.3e}"
+    return rel
+
+
+def _bf(*shape, gen, scale=1.0):
+    return (torch.randn(*shape, generator=gen) * scale).to(torch.bfloat16)
+
+
+@pytest.mark.parametrize("n,d", [(1, 64), (5, 3584), (300, 256), (257, 8192), (4, 72)])
+def test_rms_norm(n, d):
+    print(f"case n={n} d={d}", flush=True)
+    g = torch.Generator().manual_seed(n * 131 + d)
+    x, w = _bf(n, d, gen=g, scale=3.0), (1.0 + 0.1 * torch.randn(d, generator=g)).to(torch.bfloat16)
+    out = torch.full((n, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    B.rms_norm(x.to(DEV), w.to(DEV), out, 1e-6)
+    torch.cuda.synchronize()
+    assert_stored_close(to_f64(out), LO.bf16_round(LO.rms_norm(to_f64(x), to_f64(w), 1e-6)), "rms_norm")
+
+
+@pytest.mark.parametrize("m,n,k,bias,res", [(1, 8, 64, False, False), (300, 512, 192, True, True), (257, 200, 128, True, False),
+                                            (256, 256, 64, False, True), (513, 264, 3584, True, True),
+                                            (40, 3584, 18944, False, True), (1000, 1024, 320, False, False)])
+def test_linear(m, n, k, bias, res):
+    print(f"case m={m} n={n} k={k} bias={bias} residual={res}", flush=True)
+    g = torch.Generator().manual_seed(m + 7 * n + 13 * k)
+    x, w = _bf(m, k, gen=g), _bf(n, k, gen=g, scale=k ** -0.5)
+    b = _bf(n, gen=g, scale=0.5) if bias else None
+    r = _bf(m, n, gen=g) if res else None
+    want = LO.linear(to_f64(x), to_f64(w), None if b is None else to_f64(b))
+    if r is not None:
+        want = want + to_f64(r)
+    out = torch.full((m, n), float("nan"), dtype=torch.bfloat16, device=DEV)
+    dv = lambda t: None if t is None else t.to(DEV)
+    B.linear(dv(x), dv(w), dv(b), dv(r), out)
+    torch.cuda.synchronize()
+    assert_stored_close(to_f64(out), LO.bf16_round(want), "linear")
+    if r is not None:   # the residual may alias the output
+        out2 = r.to(DEV).clone()
+        B.linear(dv(x), dv(w), dv(b), out2, out2)
+        torch.cuda.synchronize()
+        assert torch.equal(out2, out)
+
+
+@pytest.mark.parametrize("n,theta,sections", [(300, 1e6, (16, 24, 24)), (7, 1e4, (64, 0, 0)), (1025, 1e6, (0, 32, 32))])
+def test_rope_table(n, theta, sections):
+    print(f"case n={n} theta={theta} sections={sections}", flush=True)
+    g = torch.Generator().manual_seed(n)
+    pos = torch.stack([torch.randint(0, 100000, (n + 9,), generator=g), torch.randint(0, 64, (n + 9,), generator=g),
+                       torch.randint(0, 64, (n + 9,), generator=g)]).to(torch.int32)
+    cs = torch.full((n, 64, 2), float("nan"), dtype=torch.float32, device=DEV)
+    B.rope_table(pos.to(DEV), 4, n, theta, sections, cs)          # a slice of a longer [3][N] array
+    torch.cuda.synchronize()
+    cos, sin = LO.mrope_cos_sin(pos[:, 4:4 + n].numpy(), 128, theta, sections)
+    got = to_f64(cs)
+    # the angle is formed in f64 on both sides; f32 rounding of the result is all that is left (+ theta as f32)
+    np.testing.assert_allclose(got[..., 0], cos, atol=2e-7 if theta == 1e6 or theta == 1e4 else 1e-4, rtol=0)
+    np.testing.assert_allclose(got[..., 1], sin, atol=2e-7 if theta == 1e6 or theta == 1e4 else 1e-4, rtol=0)
+
+
+def _oracle_qkv(h, w_qkv, b_qkv, pos3, h_q, h_kv, theta, sections):
+    n = h.shape[0]
+    y = LO.linear(h, w_qkv, b_qkv)
+    cos, sin = LO.mrope_cos_sin(pos3, 128, theta, sections)
+    q = LO.apply_rotary(y[:, :h_q * 128].reshape(n, h_q, 128), cos, sin)
+    k = LO.apply_rotary(y[:, h_q * 128:(h_q + h_kv) * 128].reshape(n, h_kv, 128), cos, sin)
+    v = y[:, (h_q + h_kv) * 128:].reshape(n, h_kv, 128)
+    return LO.bf16_round(q), LO.bf16_round(k), LO.bf16_round(v)
+
+
+@pytest.mark.parametrize("n,d_model,h_q,h_kv", [(300, 320, 4, 2), (1, 64, 2, 1), (257, 3584, 28, 4), (600, 192, 6, 3),
+                                                (130, 512, 8, 8)])
+def test_qkv_rope(n, d_model, h_q, h_kv):
+    print(f"case n={n} d_model={d_model} heads={h_q}/{h_kv}", flush=True)
+    g = torch.Generator().manual_seed(n + d_model + h_q)
+    theta, sections = 1e6, (16, 24, 24)
+    h = _bf(n, d_model, gen=g)
+    nq = (h_q + 2 * h_kv) * 128
+    w, b = _bf(nq, d_model, gen=g, scale=d_model ** -0.5), _bf(nq, gen=g, scale=0.5)
+    pos = W.video_positions((n + 15) // 16, 16)[:, :n].contiguous()
+    pos[0] += 3000                                              # long-video temporal indices
+    want = _oracle_qkv(to_f64(h), to_f64(w), to_f64(b), pos.numpy(), h_q, h_kv, theta, sections)
+    layout = B.make_layout(h_q, h_kv, 128, "bf16")
+    cs = torch.empty(n, 64, 2, dtype=torch.float32, device=DEV)
+    B.rope_table(pos.to(DEV), 0, n, theta, sections, cs)
+    q = torch.full((n, h_q, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    k = torch.full((n, h_kv, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    v = torch.full((n, h_kv, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    B.qkv_rope(layout, h.to(DEV), w.to(DEV), b.to(DEV), cs, q, k, v)
+    torch.cuda.synchronize()
+    for name, got, ref in zip("qkv", (q, k, v), want):
+        assert_stored_close(to_f64(got), ref, name)
+
+
+@pytest.mark.parametrize("n,d_model,d_ff", [(300, 192, 384), (1, 64, 128), (257, 3584, 18944), (513, 256, 1152)])
+def test_swiglu_gate_up(n, d_model, d_ff):
+    print(f"case n={n} d_model={d_model} d_ff={d_ff}", flush=True)
+    g = torch.Generator().manual_seed(n + d_model + d_ff)
+    h = _bf(n, d_model, gen=g)
+    w = _bf(2 * d_ff, d_model, gen=g, scale=2.0 * d_model ** -0.5)
+    want = LO.silu(LO.linear(to_f64(h), to_f64(w[:d_ff]))) * LO.linear(to_f64(h), to_f64(w[d_ff:]))
+    act = torch.full((n, d_ff), float("nan"), dtype=torch.bfloat16, device=DEV)
+    B.swiglu_gate_up(h.to(DEV), w.to(DEV), act)
+    torch.cuda.synchronize()
+    # exp and the division add a few f32 ulps before the rounding: still far inside one bf16 ulp
+    assert_stored_close(to_f64(act), LO.bf16_round(want), "swiglu")
+
+
+def test_unsupported_shapes_are_refused_before_launch():
+    x = torch.zeros(4, 72, dtype=torch.bfloat16, device=DEV)
+    w = torch.zeros(8, 72, dtype=torch.bfloat16, device=DEV)
+    out = torch.zeros(4, 8, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(B.QPError) as e:
+        B.linear(x, w, None, None, out)                          # k not a multiple of 64
+    assert e.value.status == B.QP_ERR_UNSUPPORTED
+    with pytest.raises(B.QPError) as e:
+        B.swiglu_gate_up(torch.zeros(4, 64, dtype=torch.bfloat16, device=DEV),
+                         torch.zeros(2 * 64, 64, dtype=torch.bfloat16, device=DEV),
+                         torch.zeros(4, 64, dtype=torch.bfloat16, device=DEV))   # d_ff not a multiple of 128
+    assert e.value.status == B.QP_ERR_UNSUPPORTED
+
+
+# ------------------------------------------------------------------------------------------------ the layer
+def _oracle_weights(w, dims):
+    hq, hkv = dims.n_q_heads * 128, dims.n_kv_heads * 128
+    f = {k: to_f64(v) for k, v in w.items()}
+    return dict(ln1=f["ln1_w"], ln2=f["ln2_w"], w_q=f["w_qkv"][:hq], b_q=f["b_qkv"][:hq],
+                w_k=f["w_qkv"][hq:hq + hkv], b_k=f["b_qkv"][hq:hq + hkv], w_v=f["w_qkv"][hq + hkv:],
+                b_v=f["b_qkv"][hq + hkv:], w_o=f["w_o"], w_gate=f["w_gate_up"][:dims.d_ff],
+                w_up=f["w_gate_up"][dims.d_ff:], w_down=f["w_down"])
+
+
+def _oracle_shape(dims):
+    return dict(n_q_heads=dims.n_q_heads, n_kv_heads=dims.n_kv_heads, head_dim=128, d_model=dims.d_model,
+                rms_eps=dims.rms_eps, rope_theta=dims.rope_theta, mrope_section=dims.mrope_section)
+
+
+# Through a whole layer the attention kernel's own tolerance applies (it rounds the softmax numerators to bf16:
+# up to 2e-2 absolute / 1e-2 relative on the attention output), carried through W_o and the MLP; everything else
+# is one-ulp rounding flips. Layers add their errors, so the absolute floor grows with the depth of the stack;
+# the normalised error stays under the attention kernel's 1e-2. A wrong operand, index or epilogue gives errors
+# of the size of the RMS itself.
+def assert_layer_close(got, want, what, layers=1):
+    got, want = np.asarray(got, dtype=np.float64), np.asarray(want, dtype=np.float64)
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    rms = np.sqrt(np.mean(want * want))
+    err = np.abs(got - want)
+    rel = np.linalg.norm(got - want) / np.linalg.norm(want)
+    print(f"{what}: normalised error {rel:.2e}, max abs error {err.max():.2e}, rms {rms:.2e}", flush=True)
+    bad = err > 2e-2 * np.abs(want) + 2e-2 * layers * rms
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} out of tolerance, max err {err.max():.3e} (rms {rms:.3e})"
+    assert rel <= 1e-2, f"{what}: normalised error {rel:.3e}"
+    return rel
+
+
+def _gpu_stack(dims, layers_t, x, pos, bounds, x_win, pos_win, rule, retention):
+    """The group-major schedule of Sec. 3.2 driven through the C ABI: every group runs through all layers."""
+    layout = B.make_layout(dims.n_q_heads, dims.n_kv_heads, 128, "bf16")
+    shape = B.make_layer_shape(dims.d_model, dims.d_ff, dims.rms_eps, dims.rope_theta, dims.mrope_section)
+    n_win = 0 if x_win is None else x_win.shape[1]
+    n_max = max(n for _, n in bounds)
+    ws = B.make_layer_workspace(layout, shape, n_max, n_win)
+    weights = [B.LayerWeights(**{k: v.to(DEV) for k, v in w.items()}) for w in layers_t]
+    cap = sum(B.keep_count(n, retention) for _, n in bounds)
+    caches = [B.Cache(layout, cap) for _ in layers_t]
+    q_wins = [None] * len(layers_t)
+    if x_win is not None:
+        pw = pos_win.to(DEV)
+        for l, wt in enumerate(weights):
+            q_wins[l] = torch.empty(n_win, dims.n_q_heads, 128, dtype=torch.bfloat16, device=DEV)
+            B.layer_window_queries(layout, shape, wt, x_win[l].to(DEV), pw, q_wins[l], ws)
+    xd, pd = x.to(DEV), pos.to(DEV)
+    out = torch.empty_like(xd)
+    kept = []
+    for base, n_g in bounds:
+        cur = xd[base:base + n_g].contiguous()
+        keep = B.keep_count(n_g, retention)
+        for l, wt in enumerate(weights):
+            idx = torch.empty(dims.n_kv_heads, keep, dtype=torch.int32, device=DEV)
+            nxt = torch.empty_like(cur)
+            B.layer_group(layout, shape, wt, cur, pd, base, base, q_wins[l], rule, keep, caches[l], nxt, idx, ws)
+            kept.append((base, l, idx))
+            cur = nxt
+        out[base:base + n_g] = cur
+    torch.cuda.synchronize()
+    return out, caches, kept
+
+
+SMALL = W.LayerDims(256, 384, 4, 2)
+
+
+@pytest.mark.parametrize("rule", ["key_norm_small", "window_attn"])
+def test_layer_stack_full_retention_matches_oracle(rule):
+    """Three layers, three ragged groups, nothing pruned: every activation and every cache row must match."""
+    print(f"case rule={rule}", flush=True)
+    dims, frames, tpf, gf = SMALL, 10, 36, 4
+    layers_t = [W.make_decoder_layer(dims, l) for l in range(3)]
+    x = W.make_hidden(frames, tpf, dims.d_model)
+    pos = W.video_positions(frames, tpf)
+    x_win = torch.stack([W.make_hidden(1, 20, dims.d_model, seed=50 + l) for l in range(3)])
+    pos_win = W.text_positions(20, frames)
+    bounds = O.group_bounds(frames, tpf, gf)
+    use_win = rule.startswith("window")
+    got, caches, _ = _gpu_stack(dims, layers_t, x, pos, bounds, x_win if use_win else None, pos_win, rule, 1.0)
+    want, want_caches = LO.layer_stack(to_f64(x), pos.numpy(), [_oracle_weights(w, dims) for w in layers_t],
+                                       _oracle_shape(dims), bounds, to_f64(x_win) if use_win else None, pos_win.numpy(),
+                                       rule, 1.0, store=LO.bf16_round)
+    assert_layer_close(to_f64(got), want, "stack output", layers=3)
+    for l, (cache, (ck, cv, cp)) in enumerate(zip(caches, want_caches)):
+        assert cache.len == frames * tpf
+        np.testing.assert_array_equal(cache.pos.cpu().numpy()[:, :cache.len], cp)
+        assert_layer_close(to_f64(cache.k)[:, :cache.len], ck, f"layer {l} cached K", layers=l + 1)
+        assert_layer_close(to_f64(cache.v)[:, :cache.len], cv, f"layer {l} cached V", layers=l + 1)
+
+
+def test_layer_group_pruned_first_group_and_parts():
+    """One group through one 7B-shaped layer at rho = 0.3: output, kept set, cache rows."""
+    dims = W.LayerDims(3584, 18944, 28, 4)
+    n_g = 300
+    wt = W.make_decoder_layer(dims, 0)
+    x = W.make_hidden(3, 100, dims.d_model)
+    pos = W.video_positions(3, 100)
+    got, caches, kept = _gpu_stack(dims, [wt], x, pos, [(0, n_g)], None, None, "key_norm_small", 0.3)
+    shape = _oracle_shape(dims)
+    empty = np.zeros((dims.n_kv_heads, 0, 128))
+    want, idx, nk, nv, mid = LO.layer_group(to_f64(x), pos.numpy(), _oracle_weights(wt, dims), shape, empty, empty, None,
+                                            "key_norm_small", 0.3, store=LO.bf16_round)
+    assert_layer_close(to_f64(got), want, "layer output")
+    # the kept set is decided on each side's own bf16 keys, which differ by one-ulp flips in a few elements:
+    # a disagreement is accepted only between keys whose oracle scores are within 2e-3 (relative) of the k-th
+    got_idx = kept[0][2].cpu().numpy()
+    for h in range(dims.n_kv_heads):
+        diff = np.setxor1d(got_idx[h], idx[h])
+        assert (np.diff(got_idx[h]) > 0).all()
+        if diff.size:
+            s_k = np.sort(mid["scores"][h])[::-1][idx.shape[1] - 1]
+            assert (np.abs(mid["scores"][h][diff] - s_k) < 2e-3 * abs(s_k)).all(), (h, diff)
+        same = np.isin(got_idx[h], idx[h])
+        rows = np.searchsorted(idx[h], got_idx[h][same])
+        assert_layer_close(to_f64(caches[0].k)[h, :90][same], nk[h][rows], f"head {h} cached K")
+        assert_layer_close(to_f64(caches[0].v)[h, :90][same], nv[h][rows], f"head {h} cached V")
+    assert caches[0].len == 90
