@@ -74,6 +74,11 @@ qp_status qp_qkv_rope(const qp_layout* layout, const void* h, const void* w_qkv,
 qp_status qp_swiglu_gate_up(const void* h, const void* w_gate_up, void* act, int32_t n_tokens, int32_t d_model,
                             int32_t d_ff, void* hip_stream);
 
+/* The projections run 256 x 256 output tiles per workgroup, or 128 (tokens) x 256 when the larger tile would leave
+ * compute units idle; the launcher chooses per call. This pins the choice for later calls of this process (tests
+ * cover both): 0 = choose per call, 128 or 256. INVALID_ARG for any other value. */
+qp_status qp_select_linear_tile(int32_t token_rows);
+
 /* ---- the layer ------------------------------------------------------------------------------------------- */
 
 /* Workspace of qp_layer_group / qp_layer_window_queries for groups of at most max_group_tokens tokens and a

@@ -81,6 +81,7 @@ SIGNATURES = {
     "qp_rope_table": (_i32, [_vp, _i64, _i32, _f32, ctypes.POINTER(ctypes.c_int32), _vp, _vp]),
     "qp_qkv_rope": (_i32, [_LP, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]),
     "qp_swiglu_gate_up": (_i32, [_vp, _vp, _vp, _i32, _i32, _i32, _vp]),
+    "qp_select_linear_tile": (_i32, [_i32]),
     "qp_layer_workspace_bytes": (_sz, [_LP, _SP, _i32, _i32]),
     "qp_layer_group": (_i32, [_LP, _SP, _WP, _vp, _vp, _i64, _i32, _i32, _vp, _i32, _i32, _i32, _CP, _vp, _vp, _vp,
                               _sz, _vp]),
@@ -272,6 +273,10 @@ def qkv_rope(layout, h, w_qkv, b_qkv, cos_sin, q, k, v):
 def swiglu_gate_up(h, w_gate_up, act):
     _check(lib().qp_swiglu_gate_up(_ptr(h), _ptr(w_gate_up), _ptr(act), h.shape[0], h.shape[1],
                                    w_gate_up.shape[0] // 2, _stream()), "qp_swiglu_gate_up")
+
+
+def select_linear_tile(token_rows: int):
+    _check(lib().qp_select_linear_tile(token_rows), "qp_select_linear_tile")
 
 
 def layer_workspace_bytes(layout, shape, max_group_tokens, n_window) -> int:

@@ -9,7 +9,8 @@
 //
 // Tiling. A workgroup of 8 wavefronts owns a 256 x 256 output tile and walks K in steps of 64. Both operand
 // tiles (256 rows x 128 bytes each) go global -> LDS with global_load_lds_dwordx4 into a ring of buffers, the
-// next step's tiles in flight while this step's are multiplied; one barrier per step. Rows are unpadded; the
+// next step's tiles in flight while this step's are multiplied; one barrier per step, placed before the step's last
+// quarter of products so that the matrix pipe stays busy across it. Rows are unpadded; the
 // 16-byte chunk c of row r sits at position c ^ ((r >> 1) & 7), which makes both the 1 KB stores of the loads
 // and the fragment reads (32 rows x 16 bytes per half wavefront) conflict-free.
 // Wavefront (wm, wn) of the 2 x 4 arrangement computes 128 tokens x 64 outputs as 4 x 2 blocks of
@@ -20,9 +21,8 @@
 //     32 dims [32 (wn & 1), +32) in block 0 and their rotary partners (+64) in block 1. The weight rows are
 //     fetched into LDS in that order (a permutation inside the tile, contiguous in runs of 32 rows).
 //   * SWIGLU: block 0 holds gate columns [n0/2 + 32 wn, +32), block 1 the up columns of the same outputs.
-// Workgroup ids are dealt round-robin over the 8 XCDs; inside an XCD consecutive workgroups walk the token
-// tiles of one weight tile, so a weight tile is fetched into that XCD's L2 once while the (smaller)
-// activations are shared by all of them.
+// Workgroup ids are dealt round-robin over the 8 XCDs; the workgroups an XCD runs side by side cover a block of
+// token tiles x weight tiles, which bounds what its L2 has to fetch per k-step.
 #include "qp_internal.h"
 
 namespace qp {
@@ -32,12 +32,31 @@ typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int GM_BM = 256, GM_BN = 256, GM_BK = 64;
+constexpr int GM_BN = 256, GM_BK = 64;                // weight rows per tile, k per step
 constexpr int GM_NW = 8;
 constexpr int GM_ROWB = GM_BK * 2;                    // bytes per tile row
-constexpr int GM_XT = GM_BM * GM_ROWB;                // bytes of the activation tile
-constexpr int GM_STAGE = (GM_BM + GM_BN) * GM_ROWB;   // one ring slot: activation tile + weight tile
-constexpr int GM_STAGES = 2;
+// Token rows per tile BM is 256 (two ring slots of 64 KB, the next step in flight) or, for launches that would
+// leave compute units idle with 256-row tiles, 128 (three slots of 48 KB, two steps in flight).
+template <int BM>
+struct Tile {
+  static constexpr int XT = BM * GM_ROWB;                 // bytes of the activation tile
+  static constexpr int STAGE = (BM + GM_BN) * GM_ROWB;    // one ring slot: activation tile + weight tile
+  static constexpr int STAGES = BM == 256 ? 2 : 3;
+  static constexpr int MI = BM / 64;                      // 32-token blocks per wavefront (wavefront rows: BM / 2)
+  static constexpr int XQ = BM / 64;                      // activation load instructions per wavefront and step
+  static constexpr int PER_WAVE = XQ + 4;                 // + 4 weight load instructions
+};
+
+// 64 lanes x 16 bytes global -> LDS at the wave-uniform LDS byte address lds_addr (lane L lands at lds_addr + 16 L)
+__device__ __forceinline__ void gm_dma16(const unsigned char* base, unsigned byte_off, unsigned lds_addr) {
+  asm volatile(
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, %1"
+      :
+      : "v"(byte_off), "s"(base), "s"(lds_addr)
+      : "memory");
+}
 
 template <int N>
 __device__ __forceinline__ void gm_wait_vmcnt() {
@@ -52,8 +71,9 @@ __device__ __forceinline__ int weight_row(int j, int n0, int d_ff) {
   return n0 + j;
 }
 
-template <int MODE>
+template <int MODE, int BM>
 __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
+  typedef Tile<BM> T;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -61,92 +81,156 @@ __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
   const int l32 = lane & 31, g = lane >> 5;
   const int wm = wave >> 2, wn = wave & 3;
 
-  // workgroup id -> (weight tile, token tile)
+  // workgroup id -> (weight tile, token tile). Ids go round-robin over the 8 XCDs; the 32 workgroups that an XCD
+  // runs side by side form a block of up to 8 token tiles x 4 weight tiles, so that per k-step the XCD's L2 fetches
+  // 8 + 4 operand tiles for 32 products.
   const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-  const int tn = xcd + 8 * (idx / a.tiles_m), tm = idx % a.tiles_m;
-  if (tn >= a.tiles_n) return;  // padding of the XCD mapping (whole workgroup, before any barrier)
-  const int m0 = tm * GM_BM, n0 = tn * GM_BN;
+  const int mi = idx % a.m_block, t = idx / a.m_block;
+  const int ni = t & 3, b = t >> 2;
+  const int mc = b / a.n_quads, nq = b - mc * a.n_quads;
+  const int tm = mc * a.m_block + mi, tn = xcd + 8 * (nq * 4 + ni);
+  if (tm >= a.tiles_m || tn >= a.tiles_n) return;  // padding of the mapping (whole workgroup, before any barrier)
+  const int m0 = tm * BM, n0 = tn * GM_BN;
   const int d_ff = a.n >> 1;
 
-  // staging: load instruction q of this wavefront covers tile rows 32 wave + 8 q + (lane >> 3), position lane & 7
+  // staging: activation load q of this wavefront covers tile rows (BM/8) wave + 8 q + (lane >> 3), weight load q
+  // rows 32 wave + 8 q + (lane >> 3); LDS position lane & 7 of the row holds chunk position ^ swizzle(row)
   const unsigned char* xg = (const unsigned char*)a.x;
   const unsigned char* wg = (const unsigned char*)a.w;
   const size_t row_b = (size_t)a.k * 2;
-  unsigned x_off[4], w_off[4];
+  unsigned x_off[T::XQ], w_off[4];
   const int wb = MODE == GEMM_SWIGLU ? (n0 >> 1) : n0;  // first weight row this tile touches
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    const int r = 32 * wave + 8 * q + (lane >> 3);
-    const unsigned chunk = (unsigned)((lane & 7) ^ ((r >> 1) & 7)) * 16;
-    const int xr = min(m0 + r, a.m - 1);  // rows past the end: computed, not stored
-    const int wr = min(weight_row<MODE>(r, n0, d_ff), a.n - 1);
     // offsets relative to the tile's first row (the launcher checks that they fit 32 bits)
-    x_off[q] = (unsigned)((size_t)(xr - m0) * row_b) + chunk;
-    w_off[q] = (unsigned)((size_t)(wr - wb) * row_b) + chunk;
+    if (q < T::XQ) {
+      const int r = (BM / 8) * wave + 8 * q + (lane >> 3);
+      const int xr = min(m0 + r, a.m - 1);  // rows past the end: computed, not stored
+      x_off[q] = (unsigned)((size_t)(xr - m0) * row_b) + (unsigned)((lane & 7) ^ ((r >> 1) & 7)) * 16;
+    }
+    const int r = 32 * wave + 8 * q + (lane >> 3);
+    const int wr = min(weight_row<MODE>(r, n0, d_ff), a.n - 1);
+    w_off[q] = (unsigned)((size_t)(wr - wb) * row_b) + (unsigned)((lane & 7) ^ ((r >> 1) & 7)) * 16;
   }
   const unsigned char* x_base = xg + (size_t)m0 * row_b;
   const unsigned char* w_base = wg + (size_t)wb * row_b;
-  const int st_lds = wave * 4096;
+  const unsigned smem_lds = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
+  const unsigned x_lds = smem_lds + wave * (BM / 8) * GM_ROWB, w_lds = smem_lds + T::XT + wave * 32 * GM_ROWB;
 
-#define GM_ISSUE(step_, slot_)                                                     \
-  {                                                                                \
-    const unsigned koff_ = (unsigned)(step_) * GM_ROWB;                            \
-    unsigned char* xd_ = smem + (slot_)*GM_STAGE + st_lds;                         \
-    unsigned char* wd_ = xd_ + GM_XT;                                              \
-    _Pragma("unroll") for (int q_ = 0; q_ < 4; ++q_) {                             \
-      lds_dma16(x_base, x_off[q_] + koff_, xd_ + 1024 * q_);                       \
-      lds_dma16(w_base, w_off[q_] + koff_, wd_ + 1024 * q_);                       \
-    }                                                                              \
+  // load instruction p_ of a step (activation loads first, then weight loads) into ring slot slot_
+#define GM_ISSUE_ONE(p_, step_, slot_)                                                                          \
+  {                                                                                                             \
+    const unsigned koff_ = (unsigned)(step_) * GM_ROWB;                                                         \
+    if ((p_) < T::XQ) gm_dma16(x_base, x_off[(p_) < T::XQ ? (p_) : 0] + koff_, x_lds + (slot_)*T::STAGE + 1024 * (p_)); \
+    else gm_dma16(w_base, w_off[(p_) - T::XQ] + koff_, w_lds + (slot_)*T::STAGE + 1024 * ((p_) - T::XQ));       \
   }
+#define GM_ISSUE(step_, slot_) \
+  { _Pragma("unroll") for (int p_ = 0; p_ < T::PER_WAVE; ++p_) GM_ISSUE_ONE(p_, step_, slot_) }
 
   // fragment addresses inside a slot: row (l32 + 32 block), chunk 2 s + g of k-step s
   int f_off[4];
 #pragma unroll
   for (int s = 0; s < 4; ++s) f_off[s] = l32 * GM_ROWB + (((2 * s + g) ^ ((l32 >> 1) & 7)) << 4);
-  const int x_frag = wm * 128 * GM_ROWB;
-  const int w_frag = GM_XT + wn * 64 * GM_ROWB;
+  const int x_frag = wm * (BM / 2) * GM_ROWB;
+  const int w_frag = T::XT + wn * 64 * GM_ROWB;
 
-  f32x16 acc[2][4];
+  f32x16 acc[2][T::MI];
 #pragma unroll
   for (int j = 0; j < 2; ++j)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < T::MI; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
 
+  // Ring schedule. All slots are free at the start, so the first STAGES steps are requested at once. Inside the
+  // loop the barrier sits before the LAST k-step's products of a step: by then every wavefront has read all its
+  // fragments of the step (its slot can be refilled), the next step's tiles have landed, and the wait at the
+  // barrier, the refill requests and the latency of the next step's first fragment reads all run under those
+  // products instead of leaving the matrix pipe idle between steps.
   const int n_steps = a.k / GM_BK;
-  GM_ISSUE(0, 0)
-  for (int step = 0; step < n_steps; ++step) {
-    const int slot = step & 1;
-    gm_wait_vmcnt<0>();   // this wavefront's part of the step's tiles has landed
-    __syncthreads();      // ... everyone's has, and everyone is done reading the other slot
-    if (step + 1 < n_steps) GM_ISSUE(step + 1, slot ^ 1)
-    const unsigned char* st = smem + slot * GM_STAGE;
-    // fragments of k-step s+1 are read while the products of k-step s run (two register sets)
-    u32x4 wf[2][2], xf[2][4];
-#define GM_READ(s_, b_)                                                                                      \
-  {                                                                                                          \
-    _Pragma("unroll") for (int j = 0; j < 2; ++j) wf[b_][j] = *(const u32x4*)(st + w_frag + j * 32 * GM_ROWB + f_off[s_]); \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) xf[b_][i] = *(const u32x4*)(st + x_frag + i * 32 * GM_ROWB + f_off[s_]); \
+  constexpr int S = T::STAGES, PW = T::PER_WAVE;
+#pragma unroll
+  for (int p = 0; p < S; ++p)
+    if (p < n_steps) GM_ISSUE(p, p)
+  if (n_steps >= S) gm_wait_vmcnt<(S - 1) * PW>();
+  else if (S > 2 && n_steps == S - 1) gm_wait_vmcnt<(S - 2) * PW>();
+  else gm_wait_vmcnt<0>();
+  __syncthreads();
+  u32x4 wf[2][2], xf[2][T::MI];  // fragments of k-step s+1 are read while the products of k-step s run (two sets)
+#define GM_READ(st_, s_, b_)                                                                                   \
+  {                                                                                                            \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j) wf[b_][j] = *(const u32x4*)((st_) + w_frag + j * 32 * GM_ROWB + f_off[s_]); \
+    _Pragma("unroll") for (int i = 0; i < T::MI; ++i) xf[b_][i] = *(const u32x4*)((st_) + x_frag + i * 32 * GM_ROWB + f_off[s_]); \
   }
-    GM_READ(0, 0)
+#define GM_MFMA(b_)                                                                                            \
+  _Pragma("unroll") for (int i = 0; i < T::MI; ++i) _Pragma("unroll") for (int j = 0; j < 2; ++j) acc[j][i] =  \
+      __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[b_][j]), __builtin_bit_cast(bf16x8, xf[b_][i]), acc[j][i], 0, 0, 0);
+  // one product / one fragment read, by index, so that the work after the barrier can be interleaved by hand
+#define GM_MFMA_ONE(b_, mf_)                                                                                   \
+  acc[(mf_) & 1][(mf_) >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                        \
+      __builtin_bit_cast(bf16x8, wf[b_][(mf_) & 1]), __builtin_bit_cast(bf16x8, xf[b_][(mf_) >> 1]), acc[(mf_) & 1][(mf_) >> 1], 0, 0, 0);
+#define GM_READ_ONE(st_, r_)                                                                                   \
+  {                                                                                                            \
+    if ((r_) < 2) wf[0][(r_) < 2 ? (r_) : 0] = *(const u32x4*)((st_) + w_frag + (r_) * 32 * GM_ROWB + f_off[0]);   \
+    else xf[0][(r_) >= 2 ? (r_) - 2 : 0] = *(const u32x4*)((st_) + x_frag + ((r_) - 2) * 32 * GM_ROWB + f_off[0]); \
+  }
+  constexpr int NM = 2 * T::MI;                       // products per k-step
+  constexpr int PIECES = PW + 2 + T::MI;              // refill requests + first fragment reads of the next step
+  constexpr int PER = (PIECES + NM - 1) / NM;         // of them behind each product
+  GM_READ(smem, 0, 0)
+  int slot = 0;
+  for (int step = 0; step + 1 < n_steps; ++step) {
+    const unsigned char* st = smem + slot * T::STAGE;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      if (s < 3) GM_READ(s + 1, (s + 1) & 1)
+    for (int s = 0; s < 3; ++s) {
+      GM_READ(st, s + 1, (s + 1) & 1)
       __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[s & 1][j]),
-                                                              __builtin_bit_cast(bf16x8, xf[s & 1][i]), acc[j][i], 0, 0, 0);
+      GM_MFMA(s & 1)
       __builtin_amdgcn_sched_barrier(0);
     }
-#undef GM_READ
+    const int next = slot == S - 1 ? 0 : slot + 1;
+    // this wavefront's part of the next step's tiles has landed (later steps' may still be in flight) ...
+    if (step + S - 1 < n_steps) gm_wait_vmcnt<(S - 2) * PW>();
+    else gm_wait_vmcnt<0>();
+    __syncthreads();  // ... everyone's has, and everyone has read its last fragments of this step's slot
+    const bool refill = step + S < n_steps;
+    const unsigned char* st_next = smem + next * T::STAGE;
+#pragma unroll
+    for (int mf = 0; mf < NM; ++mf) {
+      GM_MFMA_ONE(1, mf)
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < PER; ++u) {
+        const int p = mf * PER + u;
+        if (p < PW) {
+          if (refill) GM_ISSUE_ONE(p, step + S, slot)
+        } else if (p < PIECES) {
+          GM_READ_ONE(st_next, p - PW)
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    slot = next;
   }
+  {  // last step: nothing left to request or to wait for
+    const unsigned char* st = smem + slot * T::STAGE;
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+      GM_READ(st, s + 1, (s + 1) & 1)
+      __builtin_amdgcn_sched_barrier(0);
+      GM_MFMA(s & 1)
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    GM_MFMA(1)
+  }
+#undef GM_MFMA_ONE
+#undef GM_READ_ONE
+#undef GM_ISSUE_ONE
+#undef GM_READ
+#undef GM_MFMA
 #undef GM_ISSUE
 
-  // ---- store: lane owns token m = m0 + 128 wm + 32 i + l32 and, in block j, outputs 8 (r >> 2) + 4 g + (r & 3)
+  // ---- store: lane owns token m = m0 + (BM/2) wm + 32 i + l32 and, in block j, outputs 8 (r >> 2) + 4 g + (r & 3)
   if (MODE == GEMM_PLAIN) {
     const bf16_t* bias = (const bf16_t*)a.bias;
     const bf16_t* res = (const bf16_t*)a.residual;
@@ -163,8 +247,8 @@ __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
           b[0] = bf16lo_to_f32(raw.x), b[1] = bf16hi_to_f32(raw.x), b[2] = bf16lo_to_f32(raw.y), b[3] = bf16hi_to_f32(raw.y);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int m = m0 + wm * 128 + i * 32 + l32;
+        for (int i = 0; i < T::MI; ++i) {
+          const int m = m0 + wm * (BM / 2) + i * 32 + l32;
           if (m >= a.m) continue;
           float y[4];
 #pragma unroll
@@ -200,8 +284,8 @@ __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
         b1[0] = bf16lo_to_f32(r1.x), b1[1] = bf16hi_to_f32(r1.x), b1[2] = bf16lo_to_f32(r1.y), b1[3] = bf16hi_to_f32(r1.y);
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int m = m0 + wm * 128 + i * 32 + l32;
+      for (int i = 0; i < T::MI; ++i) {
+        const int m = m0 + wm * (BM / 2) + i * 32 + l32;
         if (m >= a.m) continue;
         float lo[4], hi[4];
 #pragma unroll
@@ -231,8 +315,8 @@ __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
     for (int q4 = 0; q4 < 4; ++q4) {
       const int n = (n0 >> 1) + wn * 32 + 8 * q4 + 4 * g;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int m = m0 + wm * 128 + i * 32 + l32;
+      for (int i = 0; i < T::MI; ++i) {
+        const int m = m0 + wm * (BM / 2) + i * 32 + l32;
         if (m >= a.m) continue;
         bf16x4 pk;
 #pragma unroll
@@ -249,7 +333,7 @@ __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
 bool gemm_supported(const GemmArgs& a, int mode) {
   if (a.m <= 0 || a.n <= 0 || a.k <= 0 || a.k % GM_BK != 0) return false;
   // byte offsets inside a tile's row range are 32-bit (plus the k offset of the step)
-  const size_t span = (size_t)(mode == GEMM_SWIGLU ? a.n / 2 + GM_BN : GM_BN) * a.k * 2 + (size_t)a.k * 2;
+  const size_t span = (size_t)(mode == GEMM_SWIGLU ? a.n / 2 + GM_BN : GM_BN) * a.k * 2 + (size_t)a.k * 2;  // GM_BN >= BM
   if (span >= ((size_t)1 << 32)) return false;
   if (mode == GEMM_PLAIN) return a.n % 8 == 0;
   if (mode == GEMM_QKV_ROPE) return a.h_q > 0 && a.h_kv > 0 && a.n == (a.h_q + 2 * a.h_kv) * 128 && a.n % GM_BN == 0;
@@ -257,22 +341,43 @@ bool gemm_supported(const GemmArgs& a, int mode) {
   return false;
 }
 
-template <int MODE>
-static hipError_t launch_mode(GemmArgs a, hipStream_t s) {
+template <int MODE, int BM>
+static hipError_t launch_tile(GemmArgs a, hipStream_t s) {
   static bool attr_done[QP_MAX_DEVICES] = {};
   const int dev = current_device();
   if (dev < 0) return hipErrorInvalidDevice;
-  const int lds = GM_STAGES * GM_STAGE;
+  const int lds = Tile<BM>::STAGES * Tile<BM>::STAGE;
   if (!attr_done[dev]) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_kernel<MODE>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_kernel<MODE, BM>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     attr_done[dev] = true;
   }
-  a.tiles_m = (a.m + GM_BM - 1) / GM_BM;
+  a.tiles_m = (a.m + BM - 1) / BM;
   a.tiles_n = (a.n + GM_BN - 1) / GM_BN;
-  const int groups = (a.tiles_n + 7) / 8;
-  hipLaunchKernelGGL(gemm_bf16_kernel<MODE>, dim3(8 * groups * a.tiles_m), dim3(GM_NW * 64), lds, s, a);
+  a.m_block = a.tiles_m < 8 ? a.tiles_m : 8;
+  a.n_quads = ((a.tiles_n + 7) / 8 + 3) / 4;  // weight tiles per XCD, in fours
+  const int m_chunks = (a.tiles_m + a.m_block - 1) / a.m_block;
+  hipLaunchKernelGGL((gemm_bf16_kernel<MODE, BM>), dim3(8 * m_chunks * a.m_block * a.n_quads * 4), dim3(GM_NW * 64), lds, s, a);
   return hipSuccess;
+}
+
+// 256-row tiles unless 128-row tiles finish sooner: a launch lasts ceil(tiles / CUs) rounds of one tile each, and a
+// 128-row tile costs about 0.6 of a 256-row one (half the products, less reuse of the weight fragments).
+static int g_forced_tile_rows = 0;  // 0: choose per launch; 128 / 256: tests cover both tilings
+void gemm_force_tile_rows(int rows) { g_forced_tile_rows = rows; }
+
+int gemm_tile_rows(const GemmArgs& a) {
+  if (g_forced_tile_rows != 0) return g_forced_tile_rows;
+  const int cus = device_cu_count();
+  const long tiles_n = (a.n + GM_BN - 1) / GM_BN;
+  const long t256 = (long)((a.m + 255) / 256) * tiles_n, t128 = (long)((a.m + 127) / 128) * tiles_n;
+  const double cost256 = (double)((t256 + cus - 1) / cus), cost128 = 0.6 * (double)((t128 + cus - 1) / cus);
+  return cost128 < cost256 ? 128 : 256;
+}
+
+template <int MODE>
+static hipError_t launch_mode(const GemmArgs& a, hipStream_t s) {
+  return gemm_tile_rows(a) == 128 ? launch_tile<MODE, 128>(a, s) : launch_tile<MODE, 256>(a, s);
 }
 
 hipError_t launch_gemm_bf16(const GemmArgs& a, int mode, hipStream_t s) {

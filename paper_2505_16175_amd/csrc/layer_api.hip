@@ -124,6 +124,12 @@ qp_status qp_swiglu_gate_up(const void* h, const void* w_gate_up, void* act, int
   return finish(qp::launch_gemm_bf16(a, qp::GEMM_SWIGLU, (hipStream_t)hip_stream));
 }
 
+qp_status qp_select_linear_tile(int32_t token_rows) {
+  if (token_rows != 0 && token_rows != 128 && token_rows != 256) return QP_ERR_INVALID_ARG;
+  qp::gemm_force_tile_rows(token_rows);
+  return QP_OK;
+}
+
 size_t qp_layer_workspace_bytes(const qp_layout* layout, const qp_layer_shape* shape, int32_t max_group_tokens,
                                 int32_t n_window) {
   if (check_layer(layout, shape) != QP_OK || max_group_tokens <= 0 || max_group_tokens > QP_MAX_GROUP_TOKENS ||

@@ -180,10 +180,12 @@ struct GemmArgs {
   const float* cos_sin;  // QKV_ROPE: [m][64][2] f32, (cos, sin) of each token's 64 rotation angles
   int m, n, k;
   int h_q, h_kv;
-  int tiles_m, tiles_n;  // filled by the launcher
+  int tiles_m, tiles_n, m_block, n_quads;  // filled by the launcher (tile counts and the XCD block mapping)
 };
 bool gemm_supported(const GemmArgs& a, int mode);
 hipError_t launch_gemm_bf16(const GemmArgs& a, int mode, hipStream_t s);
+int gemm_tile_rows(const GemmArgs& a);    // token rows per workgroup tile the launcher would use: 128 or 256
+void gemm_force_tile_rows(int rows);      // 0 = choose per launch (default), 128 or 256
 void launch_rms_norm(const void* x, const void* w, void* out, int n_tokens, int d_model, float eps, hipStream_t s);
 void launch_rope_table(const int32_t* pos, long axis_stride, int n_tokens, float theta, int s0, int s1, float* cos_sin,
                        hipStream_t s);

@@ -29,6 +29,14 @@ def assert_stored_close(got, want, what, ulps=1.0, floor=2e-4, nrm=3e-3):
     return rel
 
 
+@pytest.fixture(params=[128, 256, 0], ids=["tile128", "tile256", "tile_auto"])
+def tile(request):
+    """Every projection test runs with both workgroup tilings forced, and with the launcher's own choice."""
+    B.select_linear_tile(request.param)
+    yield request.param
+    B.select_linear_tile(0)
+
+
 def _bf(*shape, gen, scale=1.0):
     return (torch.randn(*shape, generator=gen) * scale).to(torch.bfloat16)
 
@@ -47,7 +55,7 @@ def test_rms_norm(n, d):
 @pytest.mark.parametrize("m,n,k,bias,res", [(1, 8, 64, False, False), (300, 512, 192, True, True), (257, 200, 128, True, False),
                                             (256, 256, 64, False, True), (513, 264, 3584, True, True),
                                             (40, 3584, 18944, False, True), (1000, 1024, 320, False, False)])
-def test_linear(m, n, k, bias, res):
+def test_linear(m, n, k, bias, res, tile):
     print(f"case m={m} n={n} k={k} bias={bias} residual={res}", flush=True)
     g = torch.Generator().manual_seed(m + 7 * n + 13 * k)
     x, w = _bf(m, k, gen=g), _bf(n, k, gen=g, scale=k ** -0.5)
@@ -96,7 +104,7 @@ def _oracle_qkv(h, w_qkv, b_qkv, pos3, h_q, h_kv, theta, sections):
 
 @pytest.mark.parametrize("n,d_model,h_q,h_kv", [(300, 320, 4, 2), (1, 64, 2, 1), (257, 3584, 28, 4), (600, 192, 6, 3),
                                                 (130, 512, 8, 8)])
-def test_qkv_rope(n, d_model, h_q, h_kv):
+def test_qkv_rope(n, d_model, h_q, h_kv, tile):
     print(f"case n={n} d_model={d_model} heads={h_q}/{h_kv}", flush=True)
     g = torch.Generator().manual_seed(n + d_model + h_q)
     theta, sections = 1e6, (16, 24, 24)
@@ -119,7 +127,7 @@ def test_qkv_rope(n, d_model, h_q, h_kv):
 
 
 @pytest.mark.parametrize("n,d_model,d_ff", [(300, 192, 384), (1, 64, 128), (257, 3584, 18944), (513, 256, 1152)])
-def test_swiglu_gate_up(n, d_model, d_ff):
+def test_swiglu_gate_up(n, d_model, d_ff, tile):
     print(f"case n={n} d_model={d_model} d_ff={d_ff}", flush=True)
     g = torch.Generator().manual_seed(n + d_model + d_ff)
     h = _bf(n, d_model, gen=g)
@@ -216,7 +224,7 @@ SMALL = W.LayerDims(256, 384, 4, 2)
 
 
 @pytest.mark.parametrize("rule", ["key_norm_small", "window_attn"])
-def test_layer_stack_full_retention_matches_oracle(rule):
+def test_layer_stack_full_retention_matches_oracle(rule, tile):
     """Three layers, three ragged groups, nothing pruned: every activation and every cache row must match."""
     print(f"case rule={rule}", flush=True)
     dims, frames, tpf, gf = SMALL, 10, 36, 4
