@@ -171,6 +171,188 @@ def characterise_after_prefill(torch, B, w, layout, cache, ws, reps=50):
     return out
 
 
+def layer_dims_of(w):
+    """The decoder-layer sizes that go with a config's head counts (None if there is no such model)."""
+    from paper_2505_16175_amd.workload import LAYER_DIMS
+    for dims in LAYER_DIMS.values():
+        if (dims.n_q_heads, dims.n_kv_heads, dims.head_dim) == (w.n_q_heads, w.n_kv_heads, w.head_dim):
+            return dims
+    return None
+
+
+def _time_us(torch, fn, reps):
+    for _ in range(2):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps
+
+
+def characterise_layer(torch, B, w, rule, cache_len, reps=10):
+    """One group of the config through one decoder layer around the path (Sec. 3.2: a block's activations exist
+    for one group at a time; Appendix D.1 prices them): RMSNorm, QKV projection + rotary embedding, the path
+    (attention over a cache of cache_len entries per head, scoring, top-k, compaction), o_proj + residual,
+    RMSNorm, fused gate/up + SwiGLU, down_proj + residual. Random-init weights of the model's shape."""
+    from paper_2505_16175_amd import workload as W
+    dims = layer_dims_of(w)
+    if dims is None or w.dtype != "bf16":
+        return None
+    n_g, dm, dff, hq, hkv = w.group_tokens, dims.d_model, dims.d_ff, dims.n_q_heads, dims.n_kv_heads
+    layout = B.make_layout(hq, hkv, 128, "bf16")
+    shape = B.make_layer_shape(dm, dff, dims.rms_eps, dims.rope_theta, dims.mrope_section)
+    wt = W.make_decoder_layer(dims, 0, device="cuda")
+    weights = B.LayerWeights(**wt)
+    x = W.make_hidden(w.group_frames, w.tokens_per_frame, dm, device="cuda")
+    pos = W.video_positions(w.group_frames, w.tokens_per_frame, device="cuda", first_frame=w.n_frames // 2)
+    windowed = rule.startswith("window")
+    n_win = w.n_window if windowed else 0
+    ws = B.make_layer_workspace(layout, shape, n_g, n_win)
+    keep = B.keep_count(n_g, w.retention)
+    cache = B.Cache(layout, cache_len + keep)
+    cache.k.normal_()
+    cache.v.normal_()
+    q_win = None
+    if windowed:
+        q_win = torch.empty(n_win, hq, 128, dtype=torch.bfloat16, device="cuda")
+        B.layer_window_queries(layout, shape, weights, W.make_hidden(1, n_win, dm, device="cuda", seed=77),
+                               W.text_positions(n_win, w.n_frames, device="cuda"), q_win, ws)
+    x_out = torch.empty_like(x)
+
+    def whole():
+        cache.c.len = cache_len
+        B.layer_group(layout, shape, weights, x, pos, 0, 0, q_win, rule, keep, cache, x_out, None, ws)
+
+    t_layer = _time_us(torch, whole, reps)
+    # the parts, on buffers of their own
+    h = torch.empty_like(x)
+    cs = torch.empty(n_g, 64, 2, dtype=torch.float32, device="cuda")
+    q = torch.empty(n_g, hq, 128, dtype=torch.bfloat16, device="cuda")
+    k = torch.empty(n_g, hkv, 128, dtype=torch.bfloat16, device="cuda")
+    v = torch.empty_like(k)
+    attn = torch.empty_like(q)
+    act = torch.empty(n_g, dff, dtype=torch.bfloat16, device="cuda")
+    scores = torch.empty(hkv, n_g, dtype=torch.float32, device="cuda")
+    B.rope_table(pos, 0, n_g, dims.rope_theta, dims.mrope_section, cs)
+    B.rms_norm(x, wt["ln1_w"], h, dims.rms_eps)
+    B.qkv_rope(layout, h, wt["w_qkv"], wt["b_qkv"], cs, q, k, v)
+    pws = B.make_workspace(layout, n_g, n_win)
+
+    def path_rest():
+        cache.c.len = cache_len
+        B.score_kv(layout, rule, k, v, q_win, scores, pws)
+        B.topk_compact(layout, scores, k, v, keep, 0, cache, None, pws)
+
+    def attend():
+        cache.c.len = cache_len
+        B.group_attend(layout, q, k, v, cache, attn, None, pws)
+
+    parts = {
+        "rms_norm": (lambda: B.rms_norm(x, wt["ln1_w"], h, dims.rms_eps), 0.0),
+        "qkv_rope": (lambda: B.qkv_rope(layout, h, wt["w_qkv"], wt["b_qkv"], cs, q, k, v), 2.0 * n_g * dm * (hq + 2 * hkv) * 128),
+        "group_attend": (attend, attend_flops(w, cache_len, n_g)),
+        "score_topk_compact": (path_rest, 0.0),
+        "o_proj_residual": (lambda: B.linear(attn.view(n_g, hq * 128), wt["w_o"], None, x, x_out), 2.0 * n_g * dm * hq * 128),
+        "gate_up_swiglu": (lambda: B.swiglu_gate_up(h, wt["w_gate_up"], act), 2.0 * n_g * dm * 2 * dff),
+        "down_residual": (lambda: B.linear(act, wt["w_down"], None, x, x_out), 2.0 * n_g * dm * dff),
+    }
+    out = {"shape": f"{n_g} tokens x d_model {dm}, d_ff {dff}, {hq}q/{hkv}kv heads, cache {cache_len} per head, rule {rule}",
+           "layer_us": t_layer, "tokens_per_s": n_g / (t_layer * 1e-6), "parts": {}}
+    proj_flops = proj_us = 0.0
+    for name, (fn, flops) in parts.items():
+        us = _time_us(torch, fn, reps)
+        out["parts"][name] = {"us": us}
+        if flops:
+            out["parts"][name].update({"TFLOPs": flops / us / 1e6, "frac_of_mfma_peak": flops / us / 1e6 / PEAK_BF16_TFLOPS})
+        if name in ("qkv_rope", "o_proj_residual", "gate_up_swiglu", "down_residual"):
+            proj_flops += flops
+            proj_us += us
+    out["parts"]["rms_norm"]["us_both"] = 2 * out["parts"]["rms_norm"]["us"]
+    out["projections"] = {"flops": proj_flops, "us": proj_us, "TFLOPs": proj_flops / proj_us / 1e6,
+                          "frac_of_mfma_peak": proj_flops / proj_us / 1e6 / PEAK_BF16_TFLOPS}
+    # activation memory of the group against Appendix D.1's model (fp16/bf16 elements)
+    act_bytes = B.layer_workspace_bytes(layout, shape, n_g, n_win) - B.workspace_bytes(layout, n_g, n_win)
+    model_group = (3 * n_g * hq * 128 + hq * 1024 * 1024) * 2 + n_g * (2 * dm + 4 * dff) * 2
+    model_video = (3 * w.n_tokens * hq * 128 + hq * 1024 * 1024) * 2 + w.n_tokens * (2 * dm + 4 * dff) * 2
+    out["activation_bytes"] = {"workspace_of_one_group": act_bytes, "appendix_d1_model_one_group": model_group,
+                               "appendix_d1_model_whole_video": model_video,
+                               "note": "model: Q,K,V at the query head count + one 1024x1024 score block per head, and "
+                                       "(2 d_model + 4 d_ff) per token for the MLP; the fused kernels keep one d_ff-wide "
+                                       "tensor (gate, up and SiLU never reach memory) and K,V at the KV head count"}
+    return out
+
+
+def run_stack(torch, B, w, rule, n_layers, steps, warmup):
+    """Group-major schedule of Sec. 3.2 through a stack of decoder layers: every group runs through all layers
+    (layer l+1 consumes layer l's output) before the next group starts; each layer keeps its own pruned cache."""
+    from paper_2505_16175_amd import workload as W
+    dims = layer_dims_of(w)
+    if dims is None or w.dtype != "bf16":
+        print("bench.py --stack: the config has no decoder-layer shape", file=sys.stderr)
+        sys.exit(2)
+    dm, hq, hkv = dims.d_model, dims.n_q_heads, dims.n_kv_heads
+    layout = B.make_layout(hq, hkv, 128, "bf16")
+    shape = B.make_layer_shape(dm, dims.d_ff, dims.rms_eps, dims.rope_theta, dims.mrope_section)
+    weights = [B.LayerWeights(**W.make_decoder_layer(dims, l, device="cuda")) for l in range(n_layers)]
+    x = W.make_hidden(w.n_frames, w.tokens_per_frame, dm, device="cuda")
+    pos = W.video_positions(w.n_frames, w.tokens_per_frame, device="cuda")
+    windowed = rule.startswith("window")
+    n_win = w.n_window if windowed else 0
+    ws = B.make_layer_workspace(layout, shape, w.group_tokens, n_win)
+    cap = B.cache_capacity(w.n_frames, w.tokens_per_frame, w.group_frames, w.retention)
+    caches = [B.Cache(layout, cap) for _ in range(n_layers)]
+    q_wins = [None] * n_layers
+    if windowed:
+        pw = W.text_positions(n_win, w.n_frames, device="cuda")
+        for l in range(n_layers):
+            q_wins[l] = torch.empty(n_win, hq, 128, dtype=torch.bfloat16, device="cuda")
+            B.layer_window_queries(layout, shape, weights[l], W.make_hidden(1, n_win, dm, device="cuda", seed=900 + l),
+                                   pw, q_wins[l], ws)
+    bounds = w.group_bounds()
+    bufs = [torch.empty(w.group_tokens, dm, dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+    out = torch.empty_like(x)
+
+    def step():
+        for c in caches:
+            c.reset()
+        for base, n_g in bounds:
+            cur = x[base:base + n_g]
+            keep = B.keep_count(n_g, w.retention)
+            for l in range(n_layers):
+                nxt = out[base:base + n_g] if l == n_layers - 1 else bufs[l & 1][:n_g]
+                B.layer_group(layout, shape, weights[l], cur, pos, base, base, q_wins[l], rule, keep, caches[l], nxt,
+                              None, ws)
+                cur = nxt
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    flops_proj = 2.0 * w.n_tokens * n_layers * (dm * (hq + 2 * hkv) * 128 + dm * hq * 128 + 3 * dm * dims.d_ff)
+    print(json.dumps({
+        "metric": "video tokens prefilled/sec through the decoder stack (group-major; layer l+1 consumes layer l)",
+        "value": w.n_tokens * steps / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": elapsed / steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name} as a stack: {n_layers} decoder layers (d_model {dm}, d_ff {dims.d_ff}, {hq}q/{hkv}kv "
+                               f"heads), {w.n_frames} frames x {w.tokens_per_frame} tokens, group {w.group_frames} frames, "
+                               f"retention {w.retention}, rule {rule}",
+                   "n_tokens": w.n_tokens, "groups": len(bounds), "layers": n_layers,
+                   "weight_bytes": n_layers * sum(t.numel() * 2 for t in weights[0].tensors.values()),
+                   "resident_cache_bytes": sum(c.nbytes() for c in caches),
+                   "group_workspace_bytes": ws.numel()},
+        "projection_TFLOPs_over_whole_step": flops_proj * steps / elapsed / 1e12,
+    }))
+
+
 def cpu_baseline(w, q, k, v, qw, rule):
     """The oracle on the host: all groups scored and selected, a sample of groups attended in full."""
     import numpy as np  # noqa: F401
@@ -229,6 +411,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (every layer's qp_prefill_video, library streams included) into a HIP graph "
                          "and time its replays: removes the host's launch cost, which bounds configs of many small groups")
+    ap.add_argument("--stack", type=int, default=None, metavar="LAYERS",
+                    help="instead of the headline path, run the config's video through a stack of this many decoder "
+                         "layers around the path (group-major, each layer feeding the next) and print that line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mfma-probe", action="store_true",
                     help="run the stand-alone matrix-pipe probe (bf16 MFMA rate with constant / random operands) and exit")
@@ -255,6 +440,9 @@ def main():
         w = dataclasses.replace(w, group_frames=args.group_frames or w.group_frames,
                                 retention=args.retention or w.retention)
     rule = args.rule or w.rules[0]
+    if args.stack is not None:
+        run_stack(torch, B, w, rule, args.stack, min(args.steps, 3), min(args.warmup, 1))
+        return
     n_layers = args.layers or w.n_layers
     layers = [make_layer(w, layer=l, device="cuda") for l in range(n_layers)]
     q, k, v, qw = layers[0]
@@ -373,6 +561,9 @@ def main():
     result["stages"]["hbm_characterisation"] = characterise_hbm(torch, B)
     if w.dtype == "bf16":
         result["stages"]["after_prefill"] = characterise_after_prefill(torch, B, w, layout, cache, ws)
+        layer = characterise_layer(torch, B, w, rule, cache.len // 2)
+        if layer is not None:
+            result["stages"]["decoder_layer"] = layer
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, q, k, v, qwin, rule)
     print(json.dumps(result))
