@@ -92,6 +92,10 @@ size_t qp_layer_workspace_bytes(const qp_layout* layout, const qp_layer_shape* s
  *   pos / axis_stride: the group's position indices, as in qp_rope_table
  *   q_win [n_window][H_q][128]: this layer's scoring queries (qp_layer_window_queries), WINDOW rules only
  *   keep, group_token_base, cache, kept_idx_or_null: as in qp_topk_compact; the cache is this layer's
+ * Scoring, top-k and compaction depend on the group's K and V only; they are enqueued on a library-owned side
+ * stream (one per device, default priority, the one qp_prefill_video uses) forked from hip_stream after the QKV
+ * projection and joined back into it before the call returns, so they run beside the attention and the
+ * projections. Calls from several host threads are serialised while they enqueue.
  * Errors: INVALID_ARG, UNSUPPORTED (shape), CAPACITY (cache or workspace too small); on any error nothing is
  * launched and the cache is untouched. */
 qp_status qp_layer_group(const qp_layout* layout, const qp_layer_shape* shape, const qp_layer_weights* weights,

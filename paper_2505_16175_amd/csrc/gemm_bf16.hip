@@ -32,19 +32,30 @@ typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int GM_BN = 256, GM_BK = 64;                // weight rows per tile, k per step
+#ifndef GM_BK
+#define GM_BK 64
+#endif
+constexpr int GM_BN = 256;  // weight rows per tile
 constexpr int GM_NW = 8;
-constexpr int GM_ROWB = GM_BK * 2;                    // bytes per tile row
-// Token rows per tile BM is 256 (two ring slots of 64 KB, the next step in flight) or, for launches that would
-// leave compute units idle with 256-row tiles, 128 (three slots of 48 KB, two steps in flight).
-template <int BM>
+// Token rows per tile BM: 256, or 128 for launches that would leave compute units idle with 256-row tiles.
+// k per ring slot BK: 64 or 32. The ring is as deep as 160 KB of LDS allow; all its free slots are in flight.
+template <int BM, int BK>
 struct Tile {
-  static constexpr int XT = BM * GM_ROWB;                 // bytes of the activation tile
-  static constexpr int STAGE = (BM + GM_BN) * GM_ROWB;    // one ring slot: activation tile + weight tile
-  static constexpr int STAGES = BM == 256 ? 2 : 3;
-  static constexpr int MI = BM / 64;                      // 32-token blocks per wavefront (wavefront rows: BM / 2)
-  static constexpr int XQ = BM / 64;                      // activation load instructions per wavefront and step
-  static constexpr int PER_WAVE = XQ + 4;                 // + 4 weight load instructions
+  static constexpr int ROWB = BK * 2;                       // bytes per tile row
+  static constexpr int CPR = ROWB / 16;                     // 16-byte chunks per row
+  static constexpr int RPI = 64 / CPR;                      // rows one load instruction covers
+  static constexpr int RPL = 256 / ROWB;                    // rows per 256 bytes of LDS (one sweep of the banks)
+  static constexpr int KS = BK / 16;                        // k-steps of the MFMA per slot
+  static constexpr int XT = BM * ROWB;                      // bytes of the activation tile
+  static constexpr int STAGE = (BM + GM_BN) * ROWB;         // one ring slot: activation tile + weight tile
+  static constexpr int STAGES = (160 * 1024) / STAGE < 6 ? (160 * 1024) / STAGE : 6;
+  static constexpr int MI = BM / 64;                        // 32-token blocks per wavefront (wavefront rows: BM / 2)
+  static constexpr int XQ = BM / 8 / RPI;                   // activation load instructions per wavefront and slot
+  static constexpr int WQ = 32 / RPI;                       // weight load instructions per wavefront and slot
+  static constexpr int PER_WAVE = XQ + WQ;
+  // chunk c of row r sits at position c ^ swizzle(r): 16 consecutive rows' reads of one chunk index, and the 1 KB
+  // written by one load instruction, then touch every bank group once
+  __device__ static constexpr int swizzle(int r) { return (r / RPL) & (CPR - 1); }
 };
 
 // 64 lanes x 16 bytes global -> LDS at the wave-uniform LDS byte address lds_addr (lane L lands at lds_addr + 16 L)
@@ -71,9 +82,10 @@ __device__ __forceinline__ int weight_row(int j, int n0, int d_ff) {
   return n0 + j;
 }
 
-template <int MODE, int BM>
+template <int MODE, int BM, int BK>
 __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
-  typedef Tile<BM> T;
+  typedef Tile<BM, BK> T;
+  constexpr int ROWB = T::ROWB;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -93,34 +105,35 @@ __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
   const int m0 = tm * BM, n0 = tn * GM_BN;
   const int d_ff = a.n >> 1;
 
-  // staging: activation load q of this wavefront covers tile rows (BM/8) wave + 8 q + (lane >> 3), weight load q
-  // rows 32 wave + 8 q + (lane >> 3); LDS position lane & 7 of the row holds chunk position ^ swizzle(row)
+  // staging: activation load q of this wavefront covers tile rows (BM/8) wave + RPI q + lane / CPR, weight load q
+  // rows 32 wave + RPI q + lane / CPR; LDS position lane % CPR of the row holds chunk position ^ swizzle(row)
   const unsigned char* xg = (const unsigned char*)a.x;
   const unsigned char* wg = (const unsigned char*)a.w;
   const size_t row_b = (size_t)a.k * 2;
-  unsigned x_off[T::XQ], w_off[4];
+  unsigned x_off[T::XQ], w_off[T::WQ];
   const int wb = MODE == GEMM_SWIGLU ? (n0 >> 1) : n0;  // first weight row this tile touches
+  // offsets relative to the tile's first row (the launcher checks that they fit 32 bits)
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    // offsets relative to the tile's first row (the launcher checks that they fit 32 bits)
-    if (q < T::XQ) {
-      const int r = (BM / 8) * wave + 8 * q + (lane >> 3);
-      const int xr = min(m0 + r, a.m - 1);  // rows past the end: computed, not stored
-      x_off[q] = (unsigned)((size_t)(xr - m0) * row_b) + (unsigned)((lane & 7) ^ ((r >> 1) & 7)) * 16;
-    }
-    const int r = 32 * wave + 8 * q + (lane >> 3);
+  for (int q = 0; q < T::XQ; ++q) {
+    const int r = (BM / 8) * wave + T::RPI * q + lane / T::CPR;
+    const int xr = min(m0 + r, a.m - 1);  // rows past the end: computed, not stored
+    x_off[q] = (unsigned)((size_t)(xr - m0) * row_b) + (unsigned)((lane % T::CPR) ^ T::swizzle(r)) * 16;
+  }
+#pragma unroll
+  for (int q = 0; q < T::WQ; ++q) {
+    const int r = 32 * wave + T::RPI * q + lane / T::CPR;
     const int wr = min(weight_row<MODE>(r, n0, d_ff), a.n - 1);
-    w_off[q] = (unsigned)((size_t)(wr - wb) * row_b) + (unsigned)((lane & 7) ^ ((r >> 1) & 7)) * 16;
+    w_off[q] = (unsigned)((size_t)(wr - wb) * row_b) + (unsigned)((lane % T::CPR) ^ T::swizzle(r)) * 16;
   }
   const unsigned char* x_base = xg + (size_t)m0 * row_b;
   const unsigned char* w_base = wg + (size_t)wb * row_b;
   const unsigned smem_lds = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
-  const unsigned x_lds = smem_lds + wave * (BM / 8) * GM_ROWB, w_lds = smem_lds + T::XT + wave * 32 * GM_ROWB;
+  const unsigned x_lds = smem_lds + wave * (BM / 8) * ROWB, w_lds = smem_lds + T::XT + wave * 32 * ROWB;
 
   // load instruction p_ of a step (activation loads first, then weight loads) into ring slot slot_
 #define GM_ISSUE_ONE(p_, step_, slot_)                                                                          \
   {                                                                                                             \
-    const unsigned koff_ = (unsigned)(step_) * GM_ROWB;                                                         \
+    const unsigned koff_ = (unsigned)(step_) * ROWB;                                                         \
     if ((p_) < T::XQ) gm_dma16(x_base, x_off[(p_) < T::XQ ? (p_) : 0] + koff_, x_lds + (slot_)*T::STAGE + 1024 * (p_)); \
     else gm_dma16(w_base, w_off[(p_) - T::XQ] + koff_, w_lds + (slot_)*T::STAGE + 1024 * ((p_) - T::XQ));       \
   }
@@ -128,11 +141,11 @@ __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
   { _Pragma("unroll") for (int p_ = 0; p_ < T::PER_WAVE; ++p_) GM_ISSUE_ONE(p_, step_, slot_) }
 
   // fragment addresses inside a slot: row (l32 + 32 block), chunk 2 s + g of k-step s
-  int f_off[4];
+  int f_off[T::KS];
 #pragma unroll
-  for (int s = 0; s < 4; ++s) f_off[s] = l32 * GM_ROWB + (((2 * s + g) ^ ((l32 >> 1) & 7)) << 4);
-  const int x_frag = wm * (BM / 2) * GM_ROWB;
-  const int w_frag = T::XT + wn * 64 * GM_ROWB;
+  for (int s = 0; s < T::KS; ++s) f_off[s] = l32 * ROWB + (((2 * s + g) ^ T::swizzle(l32)) << 4);
+  const int x_frag = wm * (BM / 2) * ROWB;
+  const int w_frag = T::XT + wn * 64 * ROWB;
 
   f32x16 acc[2][T::MI];
 #pragma unroll
@@ -147,20 +160,26 @@ __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
   // fragments of the step (its slot can be refilled), the next step's tiles have landed, and the wait at the
   // barrier, the refill requests and the latency of the next step's first fragment reads all run under those
   // products instead of leaving the matrix pipe idle between steps.
-  const int n_steps = a.k / GM_BK;
+  const int n_steps = a.k / BK;
   constexpr int S = T::STAGES, PW = T::PER_WAVE;
 #pragma unroll
   for (int p = 0; p < S; ++p)
     if (p < n_steps) GM_ISSUE(p, p)
-  if (n_steps >= S) gm_wait_vmcnt<(S - 1) * PW>();
-  else if (S > 2 && n_steps == S - 1) gm_wait_vmcnt<(S - 2) * PW>();
-  else gm_wait_vmcnt<0>();
+  // the first slot's tiles have landed: all but the min(S, n_steps) - 1 later requests are complete
+  switch (n_steps < S ? n_steps : S) {
+    case 1: gm_wait_vmcnt<0>(); break;
+    case 2: gm_wait_vmcnt<PW>(); break;
+    case 3: gm_wait_vmcnt<2 * PW>(); break;
+    case 4: gm_wait_vmcnt<3 * PW>(); break;
+    case 5: gm_wait_vmcnt<4 * PW>(); break;
+    default: gm_wait_vmcnt<5 * PW>(); break;
+  }
   __syncthreads();
   u32x4 wf[2][2], xf[2][T::MI];  // fragments of k-step s+1 are read while the products of k-step s run (two sets)
 #define GM_READ(st_, s_, b_)                                                                                   \
   {                                                                                                            \
-    _Pragma("unroll") for (int j = 0; j < 2; ++j) wf[b_][j] = *(const u32x4*)((st_) + w_frag + j * 32 * GM_ROWB + f_off[s_]); \
-    _Pragma("unroll") for (int i = 0; i < T::MI; ++i) xf[b_][i] = *(const u32x4*)((st_) + x_frag + i * 32 * GM_ROWB + f_off[s_]); \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j) wf[b_][j] = *(const u32x4*)((st_) + w_frag + j * 32 * ROWB + f_off[s_]); \
+    _Pragma("unroll") for (int i = 0; i < T::MI; ++i) xf[b_][i] = *(const u32x4*)((st_) + x_frag + i * 32 * ROWB + f_off[s_]); \
   }
 #define GM_MFMA(b_)                                                                                            \
   _Pragma("unroll") for (int i = 0; i < T::MI; ++i) _Pragma("unroll") for (int j = 0; j < 2; ++j) acc[j][i] =  \
@@ -171,8 +190,8 @@ __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
       __builtin_bit_cast(bf16x8, wf[b_][(mf_) & 1]), __builtin_bit_cast(bf16x8, xf[b_][(mf_) >> 1]), acc[(mf_) & 1][(mf_) >> 1], 0, 0, 0);
 #define GM_READ_ONE(st_, r_)                                                                                   \
   {                                                                                                            \
-    if ((r_) < 2) wf[0][(r_) < 2 ? (r_) : 0] = *(const u32x4*)((st_) + w_frag + (r_) * 32 * GM_ROWB + f_off[0]);   \
-    else xf[0][(r_) >= 2 ? (r_) - 2 : 0] = *(const u32x4*)((st_) + x_frag + ((r_) - 2) * 32 * GM_ROWB + f_off[0]); \
+    if ((r_) < 2) wf[0][(r_) < 2 ? (r_) : 0] = *(const u32x4*)((st_) + w_frag + (r_) * 32 * ROWB + f_off[0]);   \
+    else xf[0][(r_) >= 2 ? (r_) - 2 : 0] = *(const u32x4*)((st_) + x_frag + ((r_) - 2) * 32 * ROWB + f_off[0]); \
   }
   constexpr int NM = 2 * T::MI;                       // products per k-step
   constexpr int PIECES = PW + 2 + T::MI;              // refill requests + first fragment reads of the next step
@@ -182,7 +201,7 @@ __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
   for (int step = 0; step + 1 < n_steps; ++step) {
     const unsigned char* st = smem + slot * T::STAGE;
 #pragma unroll
-    for (int s = 0; s < 3; ++s) {
+    for (int s = 0; s < T::KS - 1; ++s) {
       GM_READ(st, s + 1, (s + 1) & 1)
       __builtin_amdgcn_sched_barrier(0);
       GM_MFMA(s & 1)
@@ -190,8 +209,16 @@ __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
     }
     const int next = slot == S - 1 ? 0 : slot + 1;
     // this wavefront's part of the next step's tiles has landed (later steps' may still be in flight) ...
-    if (step + S - 1 < n_steps) gm_wait_vmcnt<(S - 2) * PW>();
-    else gm_wait_vmcnt<0>();
+    {
+      const int behind = n_steps - 2 - step < S - 2 ? n_steps - 2 - step : S - 2;  // requests that may stay in flight
+      switch (behind) {
+        case 0: gm_wait_vmcnt<0>(); break;
+        case 1: gm_wait_vmcnt<PW>(); break;
+        case 2: gm_wait_vmcnt<2 * PW>(); break;
+        case 3: gm_wait_vmcnt<3 * PW>(); break;
+        default: gm_wait_vmcnt<4 * PW>(); break;
+      }
+    }
     __syncthreads();  // ... everyone's has, and everyone has read its last fragments of this step's slot
     const bool refill = step + S < n_steps;
     const unsigned char* st_next = smem + next * T::STAGE;
@@ -215,7 +242,7 @@ __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
   {  // last step: nothing left to request or to wait for
     const unsigned char* st = smem + slot * T::STAGE;
 #pragma unroll
-    for (int s = 0; s < 3; ++s) {
+    for (int s = 0; s < T::KS - 1; ++s) {
       GM_READ(st, s + 1, (s + 1) & 1)
       __builtin_amdgcn_sched_barrier(0);
       GM_MFMA(s & 1)
@@ -331,7 +358,7 @@ __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
 }
 
 bool gemm_supported(const GemmArgs& a, int mode) {
-  if (a.m <= 0 || a.n <= 0 || a.k <= 0 || a.k % GM_BK != 0) return false;
+  if (a.m <= 0 || a.n <= 0 || a.k <= 0 || a.k % 64 != 0) return false;
   // byte offsets inside a tile's row range are 32-bit (plus the k offset of the step)
   const size_t span = (size_t)(mode == GEMM_SWIGLU ? a.n / 2 + GM_BN : GM_BN) * a.k * 2 + (size_t)a.k * 2;  // GM_BN >= BM
   if (span >= ((size_t)1 << 32)) return false;
@@ -341,14 +368,14 @@ bool gemm_supported(const GemmArgs& a, int mode) {
   return false;
 }
 
-template <int MODE, int BM>
+template <int MODE, int BM, int BK>
 static hipError_t launch_tile(GemmArgs a, hipStream_t s) {
   static bool attr_done[QP_MAX_DEVICES] = {};
   const int dev = current_device();
   if (dev < 0) return hipErrorInvalidDevice;
-  const int lds = Tile<BM>::STAGES * Tile<BM>::STAGE;
+  const int lds = Tile<BM, BK>::STAGES * Tile<BM, BK>::STAGE;
   if (!attr_done[dev]) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_kernel<MODE, BM>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_kernel<MODE, BM, BK>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     attr_done[dev] = true;
   }
@@ -357,7 +384,7 @@ static hipError_t launch_tile(GemmArgs a, hipStream_t s) {
   a.m_block = a.tiles_m < 8 ? a.tiles_m : 8;
   a.n_quads = ((a.tiles_n + 7) / 8 + 3) / 4;  // weight tiles per XCD, in fours
   const int m_chunks = (a.tiles_m + a.m_block - 1) / a.m_block;
-  hipLaunchKernelGGL((gemm_bf16_kernel<MODE, BM>), dim3(8 * m_chunks * a.m_block * a.n_quads * 4), dim3(GM_NW * 64), lds, s, a);
+  hipLaunchKernelGGL((gemm_bf16_kernel<MODE, BM, BK>), dim3(8 * m_chunks * a.m_block * a.n_quads * 4), dim3(GM_NW * 64), lds, s, a);
   return hipSuccess;
 }
 
@@ -377,7 +404,7 @@ int gemm_tile_rows(const GemmArgs& a) {
 
 template <int MODE>
 static hipError_t launch_mode(const GemmArgs& a, hipStream_t s) {
-  return gemm_tile_rows(a) == 128 ? launch_tile<MODE, 128>(a, s) : launch_tile<MODE, 256>(a, s);
+  return gemm_tile_rows(a) == 128 ? launch_tile<MODE, 128, GM_BK>(a, s) : launch_tile<MODE, 256, GM_BK>(a, s);
 }
 
 hipError_t launch_gemm_bf16(const GemmArgs& a, int mode, hipStream_t s) {

@@ -187,19 +187,35 @@ qp_status qp_layer_group(const qp_layout* layout, const qp_layer_shape* shape, c
     return QP_ERR_UNSUPPORTED;
 
   hipStream_t s = (hipStream_t)hip_stream;
-  void* path_ws = ws + c.path;
+  // path workspace: the key-split scratch of the attention at its end, scoring / top-k scratch at its start
+  constexpr size_t kSplit = (size_t)32 << 20;
   const size_t path_bytes = workspace_bytes - c.path;
+  void* score_ws = ws + c.path;
+  const size_t score_bytes = path_bytes - kSplit;
+  void* split_ws = ws + c.path + (path_bytes - kSplit) / 256 * 256;
   qp::launch_rms_norm(x_g, weights->ln1_w, ws + c.h, n_g, dm, shape->rms_eps, s);
   qp::launch_rope_table(pos, (long)axis_stride, n_g, shape->rope_theta, shape->mrope_section[0], shape->mrope_section[1],
                         (float*)(ws + c.cs), s);
   st = finish(qp::launch_gemm_bf16(qkv, qp::GEMM_QKV_ROPE, s));
   if (st != QP_OK) return st;
-  st = qp_group_attend(layout, ws + c.q, ws + c.k, ws + c.v, n_g, cache, ws + c.attn, nullptr, path_ws, path_bytes, s);
+  // Scoring, top-k and compaction need the group's K and V only, not its attention: they run on the library's side
+  // stream beside the attention and the projections that follow, and are joined back before the call returns.
+  // The attention reads cache entries [0, len), the compaction writes [len, len + keep).
+  struct Side {
+    hipStream_t main, side;
+    explicit Side(hipStream_t m) : main(m), side(qp::side_fork(m)) {}
+    ~Side() {
+      if (side != nullptr) qp::side_join(main);
+    }
+    hipStream_t stream() const { return side != nullptr ? side : main; }
+  } fork(s);
+  st = qp_group_attend(layout, ws + c.q, ws + c.k, ws + c.v, n_g, cache, ws + c.attn, nullptr, split_ws, kSplit, s);
   if (st != QP_OK) return st;
-  st = qp_score_kv(layout, rule, ws + c.k, ws + c.v, n_g, q_win, nw, (float*)(ws + c.scores), path_ws, path_bytes, s);
+  st = qp_score_kv(layout, rule, ws + c.k, ws + c.v, n_g, q_win, nw, (float*)(ws + c.scores), score_ws, score_bytes,
+                   fork.stream());
   if (st != QP_OK) return st;
   st = qp_topk_compact(layout, (const float*)(ws + c.scores), ws + c.k, ws + c.v, n_g, keep, group_token_base, cache,
-                       kept_idx_or_null, path_ws, path_bytes, s);
+                       kept_idx_or_null, score_ws, score_bytes, fork.stream());
   if (st != QP_OK) return st;
   st = finish(qp::launch_gemm_bf16(oproj, qp::GEMM_PLAIN, s));
   if (st != QP_OK) return st;

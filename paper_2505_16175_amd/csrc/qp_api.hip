@@ -110,6 +110,32 @@ namespace qp {
 
 void note_hip_error(int e) { g_last_hip_error = e; }
 
+// Fork/join onto the device's library-owned scoring stream, for callers outside this file that have work which
+// may run beside the caller's stream. side_fork orders the side stream after everything enqueued on `main` so far
+// and returns it holding the enqueue mutex (the streams and events are shared by all calls on a device); side_join
+// makes `main` wait for the side stream and releases the mutex. nullptr: no side stream, nothing is held.
+hipStream_t side_fork(hipStream_t main) {
+  g_prefill_mutex.lock();
+  SideStreams* side = side_streams();
+  if (side == nullptr || hipEventRecord(side->fork, main) != hipSuccess ||
+      hipStreamWaitEvent(side->score, side->fork, 0) != hipSuccess) {
+    (void)hipGetLastError();
+    g_prefill_mutex.unlock();
+    return nullptr;
+  }
+  return side->score;
+}
+
+void side_join(hipStream_t main) {
+  SideStreams* side = side_streams();
+  if (side != nullptr) {
+    if (hipEventRecord(side->compacted[0], side->score) != hipSuccess ||
+        hipStreamWaitEvent(main, side->compacted[0], 0) != hipSuccess)
+      (void)hipGetLastError();
+  }
+  g_prefill_mutex.unlock();
+}
+
 int current_device() {
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess) {

@@ -134,6 +134,10 @@ constexpr int QP_MAX_DEVICES = 64;
 int current_device();   // index of the current HIP device, -1 if there is none or it does not fit the arrays
 int device_cu_count();  // compute units of the current device; 256 (MI355X) if it cannot be asked
 void note_hip_error(int e);  // what qp_last_hip_error() reports on this thread
+// The device's library-owned side stream, ordered after `main`'s work so far (nullptr if there is none); a non-null
+// return holds the library's enqueue mutex until side_join(main), which makes `main` wait for the side stream.
+hipStream_t side_fork(hipStream_t main);
+void side_join(hipStream_t main);
 
 void launch_score_norm(const void* x, int dtype, int n_g, int h_kv, int d, float sign, float* scores, hipStream_t s);
 
