@@ -51,6 +51,17 @@ class qp_layer_weights(ctypes.Structure):
                 ("ln1_w", "w_qkv", "b_qkv", "w_o", "ln2_w", "w_gate_up", "w_down")]
 
 
+class qp_feed_stats(ctypes.Structure):
+    _fields_ = [("groups", ctypes.c_int32), ("total_ms", ctypes.c_double), ("waited_ms", ctypes.c_double),
+                ("first_group_wait_ms", ctypes.c_double)]
+
+
+# qp_group_fn of include/qp_feed.h: (user, group, device_input, bytes, hip_stream) -> qp_status
+GROUP_FN = ctypes.CFUNCTYPE(ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t,
+                            ctypes.c_void_p)
+QP_FEED_PAGEABLE, QP_FEED_END, QP_FEED_TIMEOUT = 1, 100, 101
+
+
 class QPError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
@@ -86,6 +97,17 @@ SIGNATURES = {
     "qp_layer_group": (_i32, [_LP, _SP, _WP, _vp, _vp, _i64, _i32, _i32, _vp, _i32, _i32, _i32, _CP, _vp, _vp, _vp,
                               _sz, _vp]),
     "qp_layer_window_queries": (_i32, [_LP, _SP, _WP, _vp, _vp, _i64, _i32, _vp, _vp, _sz, _vp]),
+    # include/qp_feed.h
+    "qp_feed_create": (_i32, [_i32, _sz, _i32, ctypes.POINTER(_vp)]),
+    "qp_feed_destroy": (None, [_vp]),
+    "qp_feed_begin_write": (_i32, [_vp, ctypes.POINTER(_vp)]),
+    "qp_feed_publish": (_i32, [_vp, _sz]),
+    "qp_feed_close": (_i32, [_vp]),
+    "qp_feed_next": (_i32, [_vp, _i32, ctypes.POINTER(_vp), ctypes.POINTER(_sz), ctypes.POINTER(_i32)]),
+    "qp_feed_release": (_i32, [_vp, _i32]),
+    "qp_feed_consume": (_i32, [_vp, _vp, _vp, _sz, GROUP_FN, _vp, _vp, ctypes.POINTER(qp_feed_stats)]),
+    "qp_feed_stub_producer": (_i32, [_vp, _vp, ctypes.POINTER(_sz), _i32, _i64, _i64]),
+    "qp_feed_stub_join": (_i32, [_vp, ctypes.POINTER(_f64)]),
 }
 
 
@@ -307,3 +329,69 @@ def layer_window_queries(layout, shape, weights: LayerWeights, x_win, pos_win, q
     st = lib().qp_layer_window_queries(ctypes.byref(layout), ctypes.byref(shape), ctypes.byref(weights.c), _ptr(x_win),
                                        pp, stride, x_win.shape[0], _ptr(q_win_out), wp, wb, _stream())
     _check(st, "qp_layer_window_queries")
+
+
+# ---- include/qp_feed.h: the consumer side of the loader / prefill pipeline ----------------------------------
+class Feed:
+    """Owner of a qp_feed handle. Producer calls may come from any Python thread (ctypes drops the GIL while a
+    call blocks); consume() runs the consumer loop on the calling thread."""
+
+    def __init__(self, n_slots, slot_bytes, flags=0):
+        self.h = ctypes.c_void_p()
+        _check(lib().qp_feed_create(n_slots, slot_bytes, flags, ctypes.byref(self.h)), "qp_feed_create")
+        self.slot_bytes = slot_bytes
+        self._keep = []
+
+    def destroy(self):
+        if self.h:
+            lib().qp_feed_destroy(self.h)
+            self.h = ctypes.c_void_p()
+
+    def begin_write(self) -> int:
+        p = ctypes.c_void_p()
+        _check(lib().qp_feed_begin_write(self.h, ctypes.byref(p)), "qp_feed_begin_write")
+        return p.value
+
+    def publish(self, nbytes):
+        _check(lib().qp_feed_publish(self.h, nbytes), "qp_feed_publish")
+
+    def close(self):
+        _check(lib().qp_feed_close(self.h), "qp_feed_close")
+
+    def next(self, timeout_ms=-1):
+        """(status, host_pointer, bytes, group); status is QP_OK, QP_FEED_END or QP_FEED_TIMEOUT."""
+        p, n, g = ctypes.c_void_p(), ctypes.c_size_t(), ctypes.c_int32()
+        st = lib().qp_feed_next(self.h, timeout_ms, ctypes.byref(p), ctypes.byref(n), ctypes.byref(g))
+        if st not in (QP_OK, QP_FEED_END, QP_FEED_TIMEOUT):
+            raise QPError(st, "qp_feed_next")
+        return st, p.value, n.value, g.value
+
+    def release(self, group):
+        _check(lib().qp_feed_release(self.h, group), "qp_feed_release")
+
+    def consume(self, buf0, buf1, group_fn) -> dict:
+        """group_fn(group, device_pointer, nbytes) enqueues the group's work on torch's current stream."""
+        def tramp(_user, group, dev, nbytes, _stream):
+            try:
+                group_fn(group, dev, nbytes)
+                return QP_OK
+            except QPError as e:
+                return e.status
+        cb = GROUP_FN(tramp)
+        stats = qp_feed_stats()
+        st = lib().qp_feed_consume(self.h, _ptr(buf0), _ptr(buf1), buf0.numel() * buf0.element_size(), cb, None,
+                                   _stream(), ctypes.byref(stats))
+        _check(st, "qp_feed_consume")
+        return {name: getattr(stats, name) for name, _ in qp_feed_stats._fields_}
+
+    def stub_producer(self, host_src: torch.Tensor, bytes_per_group, first_latency_us, per_group_latency_us):
+        """host_src: contiguous CPU tensor holding the groups back to back."""
+        arr = (ctypes.c_size_t * len(bytes_per_group))(*bytes_per_group)
+        self._keep = [host_src, arr]
+        _check(lib().qp_feed_stub_producer(self.h, ctypes.c_void_p(host_src.data_ptr()), arr, len(bytes_per_group),
+                                           first_latency_us, per_group_latency_us), "qp_feed_stub_producer")
+
+    def stub_join(self) -> float:
+        ms = ctypes.c_double()
+        _check(lib().qp_feed_stub_join(self.h, ctypes.byref(ms)), "qp_feed_stub_join")
+        return ms.value

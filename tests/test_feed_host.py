@@ -1,0 +1,133 @@
+"""The feed's queue (include/qp_feed.h) on the host: ordering, back-pressure, closing, time-outs, argument errors.
+Pageable slots, no GPU call."""
+import ctypes
+import threading
+import time
+
+import pytest
+
+from paper_2505_16175_amd import binding as B
+
+
+def _write(feed, payload: bytes):
+    p = feed.begin_write()
+    ctypes.memmove(p, payload, len(payload))
+    feed.publish(len(payload))
+
+
+def _read(ptr, n):
+    return ctypes.string_at(ptr, n)
+
+
+def test_groups_come_out_in_order_with_their_sizes():
+    feed = B.Feed(3, 64, B.QP_FEED_PAGEABLE)
+    try:
+        msgs = [bytes([i]) * (i + 1) for i in range(3)]
+        for m in msgs:
+            _write(feed, m)
+        for i, m in enumerate(msgs):
+            st, p, n, g = feed.next(0)
+            assert (st, n, g) == (B.QP_OK, len(m), i) and _read(p, n) == m
+        assert feed.next(10)[0] == B.QP_FEED_TIMEOUT          # nothing published, not closed
+        for i in range(3):
+            feed.release(i)
+        feed.close()
+        assert feed.next(-1)[0] == B.QP_FEED_END
+    finally:
+        feed.destroy()
+
+
+def test_producer_blocks_while_the_ring_is_full_and_resumes_on_release():
+    feed = B.Feed(2, 16, B.QP_FEED_PAGEABLE)
+    try:
+        produced = []
+
+        def producer():
+            for i in range(5):
+                _write(feed, bytes([i]) * 4)
+                produced.append(i)
+            feed.close()
+
+        t = threading.Thread(target=producer)
+        t.start()
+        time.sleep(0.2)
+        assert produced == [0, 1]                              # the third write waits for a free slot
+        got = []
+        while True:
+            st, p, n, g = feed.next(-1)
+            if st == B.QP_FEED_END:
+                break
+            got.append((g, _read(p, n)))
+            feed.release(g)                                    # hands the slot back: the producer moves on
+        t.join(5)
+        assert not t.is_alive()
+        assert got == [(i, bytes([i]) * 4) for i in range(5)]
+    finally:
+        feed.destroy()
+
+
+def test_consumer_blocks_until_published_and_ends_after_close():
+    feed = B.Feed(2, 16, B.QP_FEED_PAGEABLE)
+    try:
+        def late():
+            time.sleep(0.15)
+            _write(feed, b"xy")
+            feed.close()
+
+        t = threading.Thread(target=late)
+        t0 = time.perf_counter()
+        t.start()
+        st, p, n, g = feed.next(-1)
+        assert time.perf_counter() - t0 >= 0.14 and (st, n, g) == (B.QP_OK, 2, 0) and _read(p, n) == b"xy"
+        feed.release(0)
+        assert feed.next(-1)[0] == B.QP_FEED_END
+        t.join()
+    finally:
+        feed.destroy()
+
+
+def test_stub_producer_paces_the_groups():
+    import torch
+    feed = B.Feed(2, 8, B.QP_FEED_PAGEABLE)
+    try:
+        src = torch.arange(24, dtype=torch.uint8)
+        feed.stub_producer(src, [8, 8, 8], 100_000, 50_000)     # due at 100, 150, 200 ms
+        t0 = time.perf_counter()
+        due = []
+        while True:
+            st, p, n, g = feed.next(-1)
+            if st == B.QP_FEED_END:
+                break
+            due.append(time.perf_counter() - t0)
+            assert _read(p, n) == bytes(range(8 * g, 8 * g + 8))
+            feed.release(g)
+        ms = feed.stub_join()
+        assert len(due) == 3 and 0.09 < due[0] < 0.14 and 0.14 < due[1] < 0.19 and 0.19 < due[2] < 0.25
+        assert 195 < ms < 260
+    finally:
+        feed.destroy()
+
+
+def test_argument_errors():
+    with pytest.raises(B.QPError):
+        B.Feed(1, 16, B.QP_FEED_PAGEABLE)                      # at least two slots
+    with pytest.raises(B.QPError):
+        B.Feed(2, 0, B.QP_FEED_PAGEABLE)
+    feed = B.Feed(2, 4, B.QP_FEED_PAGEABLE)
+    try:
+        with pytest.raises(B.QPError):
+            feed.publish(1)                                    # no slot obtained
+        feed.begin_write()
+        with pytest.raises(B.QPError):
+            feed.begin_write()                                 # the previous slot was not published
+        with pytest.raises(B.QPError) as e:
+            feed.publish(5)                                    # larger than a slot
+        assert e.value.status == B.QP_ERR_CAPACITY
+        feed.publish(4)
+        with pytest.raises(B.QPError):
+            feed.release(0)                                    # not taken yet
+        feed.close()
+        with pytest.raises(B.QPError):
+            feed.begin_write()                                 # closed
+    finally:
+        feed.destroy()
