@@ -371,16 +371,25 @@ class Feed:
 
     def consume(self, buf0, buf1, group_fn) -> dict:
         """group_fn(group, device_pointer, nbytes) enqueues the group's work on torch's current stream."""
+        failure = []
+
         def tramp(_user, group, dev, nbytes, _stream):
+            # an exception cannot cross the C frames of qp_feed_consume: stop the run and re-raise it afterwards
             try:
                 group_fn(group, dev, nbytes)
                 return QP_OK
             except QPError as e:
+                failure.append(e)
                 return e.status
+            except BaseException as e:  # noqa: BLE001
+                failure.append(e)
+                return QP_ERR_INVALID_ARG
         cb = GROUP_FN(tramp)
         stats = qp_feed_stats()
         st = lib().qp_feed_consume(self.h, _ptr(buf0), _ptr(buf1), buf0.numel() * buf0.element_size(), cb, None,
                                    _stream(), ctypes.byref(stats))
+        if failure:
+            raise failure[0]
         _check(st, "qp_feed_consume")
         return {name: getattr(stats, name) for name, _ in qp_feed_stats._fields_}
 

@@ -274,3 +274,69 @@ def test_layer_group_pruned_first_group_and_parts():
         assert_layer_close(to_f64(caches[0].k)[h, :90][same], nk[h][rows], f"head {h} cached K")
         assert_layer_close(to_f64(caches[0].v)[h, :90][same], nv[h][rows], f"head {h} cached V")
     assert caches[0].len == 90
+
+
+def test_layer_group_full_size_sampled_rows():
+    """The launch configuration bench.py times for the layer: config 2's group (2048 tokens) through a 7B-shaped layer,
+    window-attention rule (64 window rows), against a pruned cache of 4920 entries per head. The oracle computes the
+    normalised states, Q, K, V and the scores for all tokens, and everything that follows (attention, o_proj, MLP)
+    for a sample of rows, one by one."""
+    dims = W.LAYER_DIMS["7b"]
+    w2 = W.CONFIGS["cfg2_7b_32k"]
+    n_g, c, n_win = w2.group_tokens, 4920, w2.n_window
+    hq, hkv, dm = dims.n_q_heads, dims.n_kv_heads, dims.d_model
+    gen = torch.Generator().manual_seed(4242)
+    wt = W.make_decoder_layer(dims, 3)
+    x = W.make_hidden(w2.group_frames, w2.tokens_per_frame, dm, seed=11)
+    pos = W.video_positions(w2.group_frames, w2.tokens_per_frame, first_frame=128)
+    x_win = W.make_hidden(1, n_win, dm, seed=12)
+    pos_win = W.text_positions(n_win, w2.n_frames)
+    ck = torch.randn(hkv, c, 128, generator=gen).to(torch.bfloat16)
+    cv = torch.randn(hkv, c, 128, generator=gen).to(torch.bfloat16)
+    keep = B.keep_count(n_g, w2.retention)
+
+    layout = B.make_layout(hq, hkv, 128, "bf16")
+    shape = B.make_layer_shape(dm, dims.d_ff, dims.rms_eps, dims.rope_theta, dims.mrope_section)
+    weights = B.LayerWeights(**{k_: v_.to(DEV) for k_, v_ in wt.items()})
+    ws = B.make_layer_workspace(layout, shape, n_g, n_win)
+    cache = B.Cache(layout, c + keep)
+    cache.k[:, :c].copy_(ck)
+    cache.v[:, :c].copy_(cv)
+    cache.c.len = c
+    q_win = torch.empty(n_win, hq, 128, dtype=torch.bfloat16, device=DEV)
+    B.layer_window_queries(layout, shape, weights, x_win.to(DEV), pos_win.to(DEV), q_win, ws)
+    out = torch.empty(n_g, dm, dtype=torch.bfloat16, device=DEV)
+    kept = torch.empty(hkv, keep, dtype=torch.int32, device=DEV)
+    B.layer_group(layout, shape, weights, x.to(DEV), pos.to(DEV), 0, 5000, q_win, "window_attn", keep, cache, out, kept, ws)
+    torch.cuda.synchronize()
+    assert cache.len == c + keep
+
+    rb = LO.bf16_round
+    ow, oshape = _oracle_weights(wt, dims), _oracle_shape(dims)
+    x64 = to_f64(x)
+    h = rb(LO.rms_norm(x64, ow["ln1"], dims.rms_eps))
+    cos, sin = LO.mrope_cos_sin(pos.numpy(), 128, dims.rope_theta, dims.mrope_section)
+    q = rb(LO.apply_rotary(LO.linear(h, ow["w_q"], ow["b_q"]).reshape(n_g, hq, 128), cos, sin))
+    k = rb(LO.apply_rotary(LO.linear(h, ow["w_k"], ow["b_k"]).reshape(n_g, hkv, 128), cos, sin))
+    v = rb(LO.linear(h, ow["w_v"], ow["b_v"]).reshape(n_g, hkv, 128))
+    qw = LO.window_queries(to_f64(x_win), pos_win.numpy(), ow, oshape, store=rb)
+    np.testing.assert_allclose(to_f64(q_win), qw, atol=2.0 ** -7 * np.abs(qw).max())     # one ulp at the largest value
+    scores = O.score_kv("window_attn", k, v, qw)
+    idx = O.topk_select(scores, keep)
+    got_idx = kept.cpu().numpy()
+    for hh in range(hkv):
+        diff = np.setxor1d(got_idx[hh], idx[hh])
+        assert (np.diff(got_idx[hh]) > 0).all()
+        if diff.size:        # each side scores its own bf16 keys and window queries: see the one-layer test above
+            s_k = np.sort(scores[hh])[::-1][keep - 1]
+            assert (np.abs(scores[hh][diff] - s_k) < 2e-3 * abs(s_k)).all(), (hh, diff)
+        np.testing.assert_array_equal(cache.pos.cpu().numpy()[hh, c:c + keep], 5000 + got_idx[hh])
+        same = np.isin(got_idx[hh], idx[hh])
+        assert_layer_close(to_f64(cache.k)[hh, c:c + keep][same], k[got_idx[hh][same], hh], f"head {hh} appended K")
+        assert_layer_close(to_f64(cache.v)[hh, c:c + keep][same], v[got_idx[hh][same], hh], f"head {hh} appended V")
+    rows = sorted({0, 1, 127, 128, 255, 256, 1023, 1024, n_g - 129, n_g - 1} | set(np.random.default_rng(5).integers(0, n_g, 54).tolist()))
+    a = rb(O.attend_group(q, k, v, to_f64(ck), to_f64(cv), rows=rows))                      # [len(rows), H_q, d]
+    x1 = rb(x64[rows] + LO.linear(a.reshape(len(rows), hq * 128), ow["w_o"]))
+    h2 = rb(LO.rms_norm(x1, ow["ln2"], dims.rms_eps))
+    want = rb(x1 + LO.swiglu_mlp(h2, ow["w_gate"], ow["w_up"], ow["w_down"], store=rb))
+    assert_layer_close(to_f64(out)[rows], want, "layer output, sampled rows")
