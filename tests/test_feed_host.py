@@ -131,3 +131,56 @@ def test_argument_errors():
             feed.begin_write()                                 # closed
     finally:
         feed.destroy()
+
+
+@pytest.mark.parametrize("n_slots", [2, 3, 5])
+def test_queue_under_random_pacing(n_slots):
+    """Many groups through a small ring with a producer and a consumer that stall at random: nothing is lost,
+    duplicated, reordered or overwritten while in use, and both sides terminate."""
+    import random
+    import struct
+    n_groups = 400
+    feed = B.Feed(n_slots, 64, B.QP_FEED_PAGEABLE)
+    rng_p, rng_c = random.Random(1), random.Random(2)
+    errors = []
+
+    def producer():
+        try:
+            for i in range(n_groups):
+                if rng_p.random() < 0.1:
+                    time.sleep(rng_p.random() * 0.002)
+                size = 8 + (i % 7) * 8
+                _write(feed, struct.pack("<q", i) * (size // 8))
+            feed.close()
+        except Exception as e:   # noqa: BLE001
+            errors.append(e)
+
+    t = threading.Thread(target=producer)
+    t.start()
+    held, seen = [], []
+    try:
+        while True:
+            st, p, n, g = feed.next(2000)
+            assert st != B.QP_FEED_TIMEOUT, "consumer starved: dead-lock between ring and queue"
+            if st == B.QP_FEED_END:
+                break
+            held.append((g, p, n))
+            if rng_c.random() < 0.1:
+                time.sleep(rng_c.random() * 0.002)
+            # keep up to n_slots - 1 groups in hand, check them when they are handed back (not overwritten meanwhile)
+            while len(held) > rng_c.randrange(0, n_slots):
+                g0, p0, n0 = held.pop(0)
+                assert n0 == 8 + (g0 % 7) * 8 and _read(p0, n0) == struct.pack("<q", g0) * (n0 // 8)
+                seen.append(g0)
+                feed.release(g0)
+        for g0, p0, n0 in held:
+            assert _read(p0, n0) == struct.pack("<q", g0) * (n0 // 8)
+            seen.append(g0)
+            feed.release(g0)
+        t.join(10)
+        assert not t.is_alive() and not errors
+        assert seen == list(range(n_groups))
+    finally:
+        feed.close()
+        t.join(10)
+        feed.destroy()

@@ -54,7 +54,8 @@ def test_rms_norm(n, d):
 
 @pytest.mark.parametrize("m,n,k,bias,res", [(1, 8, 64, False, False), (300, 512, 192, True, True), (257, 200, 128, True, False),
                                             (256, 256, 64, False, True), (513, 264, 3584, True, True),
-                                            (40, 3584, 18944, False, True), (1000, 1024, 320, False, False)])
+                                            (40, 3584, 18944, False, True), (1000, 1024, 320, False, False),
+                                            (40, 8192, 29568, False, True)])
 def test_linear(m, n, k, bias, res, tile):
     print(f"case m={m} n={n} k={k} bias={bias} residual={res}", flush=True)
     g = torch.Generator().manual_seed(m + 7 * n + 13 * k)
@@ -103,7 +104,7 @@ def _oracle_qkv(h, w_qkv, b_qkv, pos3, h_q, h_kv, theta, sections):
 
 
 @pytest.mark.parametrize("n,d_model,h_q,h_kv", [(300, 320, 4, 2), (1, 64, 2, 1), (257, 3584, 28, 4), (600, 192, 6, 3),
-                                                (130, 512, 8, 8)])
+                                                (130, 512, 8, 8), (130, 8192, 64, 8)])
 def test_qkv_rope(n, d_model, h_q, h_kv, tile):
     print(f"case n={n} d_model={d_model} heads={h_q}/{h_kv}", flush=True)
     g = torch.Generator().manual_seed(n + d_model + h_q)
@@ -126,7 +127,8 @@ def test_qkv_rope(n, d_model, h_q, h_kv, tile):
         assert_stored_close(to_f64(got), ref, name)
 
 
-@pytest.mark.parametrize("n,d_model,d_ff", [(300, 192, 384), (1, 64, 128), (257, 3584, 18944), (513, 256, 1152)])
+@pytest.mark.parametrize("n,d_model,d_ff", [(300, 192, 384), (1, 64, 128), (257, 3584, 18944), (513, 256, 1152),
+                                            (48, 8192, 29568)])
 def test_swiglu_gate_up(n, d_model, d_ff, tile):
     print(f"case n={n} d_model={d_model} d_ff={d_ff}", flush=True)
     g = torch.Generator().manual_seed(n + d_model + d_ff)
