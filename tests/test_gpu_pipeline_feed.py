@@ -143,9 +143,9 @@ def test_run_time_follows_the_overlap_equation(first_ms, group_ms):
           f"{producer_ms:.2f}); expected {expect:.2f} + delta, measured {stats['total_ms']:.2f} ms, waited "
           f"{stats['waited_ms']:.2f} ms (first group {stats['first_group_wait_ms']:.2f})", flush=True)
     assert stats["groups"] == n_groups
-    # delta: one group's host->device copy (29 MB, under 1 ms), launch and timer slack; far below the 40+ ms that
-    # running the two sides one after the other would add
-    assert expect - 1.0 <= stats["total_ms"] <= expect + 6.0
+    # delta: one group's host->device copy (15 MB, 0.3 ms), launch and timer slack (observed 0.7-1.5 ms; the bound
+    # leaves room for a noisy host). In the loader-bound case running the two sides one after the other adds 30 ms.
+    assert expect - 2.0 <= stats["total_ms"] <= expect + 12.0
     if t_dec + t_prefill - expect > 20.0:                       # where overlap has something to win, it is won
         assert stats["total_ms"] < t_dec + t_prefill - 15.0
-    assert abs(stats["first_group_wait_ms"] - first_ms) < 3.0
+    assert abs(stats["first_group_wait_ms"] - first_ms) < 5.0
