@@ -4,8 +4,10 @@
 namespace qp {
 
 // y[t][i] = x[t][i] / sqrt(mean_i x[t][i]^2 + eps) * w[i], f32 arithmetic, one rounding to bf16 at the store.
-// One wavefront per token; the row (d_model * 2 bytes) is read twice, the second time from cache.
+// One wavefront per token. Rows of up to RN_REG * 512 elements (8192 for RN_REG = 16) stay in registers between the
+// sum of squares and the scaling, so the row is read once; longer rows are read a second time (from cache).
 constexpr int RN_WAVES = 4;
+constexpr int RN_REG = 16;  // 16-byte chunks per lane held in registers
 __global__ __launch_bounds__(RN_WAVES * 64) void rms_norm_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w,
                                                                  bf16_t* __restrict__ out, int n_tokens, int d_model,
                                                                  float eps) {
@@ -14,26 +16,52 @@ __global__ __launch_bounds__(RN_WAVES * 64) void rms_norm_kernel(const bf16_t* _
   if (t >= n_tokens) return;
   const int chunks = d_model / 8;
   const uint4* xr = (const uint4*)(x + (size_t)t * d_model);
+  const uint4* wr = (const uint4*)w;
+  uint4* orow = (uint4*)(out + (size_t)t * d_model);
+  const bool in_regs = chunks <= RN_REG * 64;
+  uint4 held[RN_REG];
   float ss = 0.f;
-  for (int c = lane; c < chunks; c += 64) {
-    float f[8];
-    widen16<bf16_t>(xr[c], f);
+  if (in_regs) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) ss = fmaf(f[e], f[e], ss);
+    for (int i = 0; i < RN_REG; ++i) {
+      const int c = lane + 64 * i;
+      held[i] = c < chunks ? xr[c] : make_uint4(0u, 0u, 0u, 0u);
+    }
+#pragma unroll
+    for (int i = 0; i < RN_REG; ++i) {
+      float f[8];
+      widen16<bf16_t>(held[i], f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss = fmaf(f[e], f[e], ss);
+    }
+  } else {
+    for (int c = lane; c < chunks; c += 64) {
+      float f[8];
+      widen16<bf16_t>(xr[c], f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss = fmaf(f[e], f[e], ss);
+    }
   }
   ss = wave_sum(ss);
   const float inv = 1.f / sqrtf(ss / (float)d_model + eps);
-  uint4* orow = (uint4*)(out + (size_t)t * d_model);
-  const uint4* wr = (const uint4*)w;
-  for (int c = lane; c < chunks; c += 64) {
+  auto scale_store = [&](int c, const uint4& raw) {
     float f[8], g[8];
-    widen16<bf16_t>(xr[c], f);
+    widen16<bf16_t>(raw, f);
     widen16<bf16_t>(wr[c], g);
     uint32_t p[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e)
       p[e] = (uint32_t)f32_to_bf16_rne(f[2 * e] * inv * g[2 * e]) | ((uint32_t)f32_to_bf16_rne(f[2 * e + 1] * inv * g[2 * e + 1]) << 16);
     orow[c] = make_uint4(p[0], p[1], p[2], p[3]);
+  };
+  if (in_regs) {
+#pragma unroll
+    for (int i = 0; i < RN_REG; ++i) {
+      const int c = lane + 64 * i;
+      if (c < chunks) scale_store(c, held[i]);
+    }
+  } else {
+    for (int c = lane; c < chunks; c += 64) scale_store(c, xr[c]);
   }
 }
 

@@ -41,7 +41,7 @@ def _bf(*shape, gen, scale=1.0):
     return (torch.randn(*shape, generator=gen) * scale).to(torch.bfloat16)
 
 
-@pytest.mark.parametrize("n,d", [(1, 64), (5, 3584), (300, 256), (257, 8192), (4, 72)])
+@pytest.mark.parametrize("n,d", [(1, 64), (5, 3584), (300, 256), (257, 8192), (4, 72), (3, 8200), (2, 16384)])
 def test_rms_norm(n, d):
     print(f"case n={n} d={d}", flush=True)
     g = torch.Generator().manual_seed(n * 131 + d)
