@@ -342,3 +342,24 @@ def test_layer_group_full_size_sampled_rows():
     h2 = rb(LO.rms_norm(x1, ow["ln2"], dims.rms_eps))
     want = rb(x1 + LO.swiglu_mlp(h2, ow["w_gate"], ow["w_up"], ow["w_down"], store=rb))
     assert_layer_close(to_f64(out)[rows], want, "layer output, sampled rows")
+
+
+def test_layer_text_chunk_and_decode_steps_after_video():
+    """Sec. 2.1's later stages through the same layer call: after a video group, a chunk of text tokens and then
+    single tokens (n_group_tokens = 7, then 1, nothing pruned) attend to everything cached so far. Two layers, so
+    that the second layer's inputs are the first one's outputs at every step."""
+    dims = SMALL
+    layers_t = [W.make_decoder_layer(dims, l, seed=99) for l in range(2)]
+    steps = [(0, 150), (150, 7), (157, 1), (158, 1), (159, 1)]
+    n_tok = 160
+    x = W.make_hidden(10, 16, dims.d_model, seed=5)
+    pos = torch.cat([W.video_positions(10, 15)[:, :150], W.text_positions(10, 40)], dim=1).contiguous()
+    got, caches, _ = _gpu_stack(dims, layers_t, x, pos, steps, None, None, "value_norm", 1.0)
+    want, want_caches = LO.layer_stack(to_f64(x), pos.numpy(), [_oracle_weights(w_, dims) for w_ in layers_t],
+                                       _oracle_shape(dims), steps, None, None, "value_norm", 1.0, store=LO.bf16_round)
+    for base, n in steps:
+        assert_layer_close(to_f64(got)[base:base + n], want[base:base + n], f"tokens {base}..{base + n - 1}", layers=2)
+    for l, (cache, (ck, cv, cp)) in enumerate(zip(caches, want_caches)):
+        assert cache.len == n_tok
+        np.testing.assert_array_equal(cache.pos.cpu().numpy()[:, :n_tok], cp)
+        assert_layer_close(to_f64(cache.k)[:, :n_tok], ck, f"layer {l} cached K", layers=l + 1)
