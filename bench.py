@@ -274,6 +274,26 @@ def characterise_layer(torch, B, w, rule, cache_len, reps=10):
     out["parts"]["rms_norm"]["us_both"] = 2 * out["parts"]["rms_norm"]["us"]
     out["projections"] = {"flops": proj_flops, "us": proj_us, "TFLOPs": proj_flops / proj_us / 1e6,
                           "frac_of_mfma_peak": proj_flops / proj_us / 1e6 / PEAK_BF16_TFLOPS}
+    # the later stages of Sec. 2.1 through the same layer call: a text chunk and a single token against the cache
+    # (nothing pruned); few tokens, so streaming the layer's weights once is the bound (HBM)
+    weight_bytes = sum(t.numel() * t.element_size() for t in wt.values())
+    out["after_prefill_through_layer"] = {}
+    for label, n_t in (("decode_1_token", 1), (f"text_chunk_{max(w.n_window, 64)}_tokens", max(w.n_window, 64))):
+        xt = W.make_hidden(1, n_t, dm, device="cuda", seed=31)
+        pt = W.text_positions(n_t, w.n_frames, device="cuda")
+        ot = torch.empty_like(xt)
+        tcache = B.Cache(layout, cache_len + n_t)
+        tcache.k.normal_()
+        tcache.v.normal_()
+
+        def small():
+            tcache.c.len = cache_len
+            B.layer_group(layout, shape, weights, xt, pt, 0, 0, None, "key_norm_small", n_t, tcache, ot, None, ws)
+
+        us = _time_us(torch, small, 4 * reps)
+        out["after_prefill_through_layer"][label] = {
+            "us": us, "weight_bytes": weight_bytes, "weight_GBps": weight_bytes / us / 1e3,
+            "frac_of_hbm_peak": weight_bytes / us / 1e3 / PEAK_HBM_GBS}
     # activation memory of the group against Appendix D.1's model (fp16/bf16 elements)
     act_bytes = B.layer_workspace_bytes(layout, shape, n_g, n_win) - B.workspace_bytes(layout, n_g, n_win)
     model_group = (3 * n_g * hq * 128 + hq * 1024 * 1024) * 2 + n_g * (2 * dm + 4 * dff) * 2

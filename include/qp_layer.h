@@ -54,9 +54,15 @@ qp_status qp_rms_norm(const void* x, const void* w, void* out, int32_t n_tokens,
 
 /* out[m][n] = sum_k x[m][k] w[n][k] (+ bias[n]) (+ residual[m][n]), all bf16, f32 accumulation, one rounding.
  * x [m][k], w [n][k], bias [n] or NULL, residual [m][n] or NULL (may alias out), out [m][n].
+ *   workspace: optional device scratch (256-byte aligned), may be NULL. A call whose output tiles would occupy at
+ *     most a quarter of the compute units (few tokens against long rows: text chunks, decode steps, where streaming
+ *     the weights once is the bound) deals the contraction to k chunks, about one workgroup per compute unit in
+ *     all; their f32 partial sums ([chunks][m][n], as many chunks as fit) live in this scratch and a second launch
+ *     adds them in chunk order and applies bias / residual. Without scratch nothing is split. Same inputs, same
+ *     scratch size: bit-identical results.
  * UNSUPPORTED unless k is a multiple of 64 and n a multiple of 8. */
 qp_status qp_linear(const void* x, const void* w, const void* bias_or_null, const void* residual_or_null, void* out,
-                    int32_t m, int32_t n, int32_t k, void* hip_stream);
+                    int32_t m, int32_t n, int32_t k, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* cos_sin[t][i] = (cos, sin)(pos[axis(i)][t] * theta^(-i/64)), f32 [n_tokens][64][2], for head_dim 128.
  * pos: int32, position index of token t on axis a at pos[a * axis_stride + t] (a = 0 temporal, 1 height, 2 width),
@@ -65,10 +71,11 @@ qp_status qp_rope_table(const int32_t* pos, int64_t axis_stride, int32_t n_token
                         const int32_t mrope_section[3], float* cos_sin, void* hip_stream);
 
 /* q, k, v = h w_qkv^T + b_qkv split into heads, rotary embedding applied to q and k (pairs (i, i+64) of a head),
- * written token-major: q [n_tokens][H_q][128], k, v [n_tokens][H_kv][128]. h [n_tokens][d_model]. */
+ * written token-major: q [n_tokens][H_q][128], k, v [n_tokens][H_kv][128]. h [n_tokens][d_model].
+ * workspace: as in qp_linear (the rotary embedding then runs in the second launch). */
 qp_status qp_qkv_rope(const qp_layout* layout, const void* h, const void* w_qkv, const void* b_qkv,
                       const float* cos_sin, int32_t n_tokens, int32_t d_model, void* q, void* k, void* v,
-                      void* hip_stream);
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* act = SiLU(h w_gate^T) * (h w_up^T), bf16 [n_tokens][d_ff] (Appendix D.1); gate and up never reach memory. */
 qp_status qp_swiglu_gate_up(const void* h, const void* w_gate_up, void* act, int32_t n_tokens, int32_t d_model,
@@ -83,7 +90,8 @@ qp_status qp_select_linear_tile(int32_t token_rows);
 
 /* Workspace of qp_layer_group / qp_layer_window_queries for groups of at most max_group_tokens tokens and a
  * window of n_window rows: the group's activations (h, q, k, v, attention output, x1, the MLP activation, the
- * rotary table, the scores) plus qp_workspace_bytes(layout, max_group_tokens, n_window). 0 on bad arguments. */
+ * rotary table, the scores), 32 MiB for split contractions, plus qp_workspace_bytes(layout, max_group_tokens,
+ * n_window). 0 on bad arguments. */
 size_t qp_layer_workspace_bytes(const qp_layout* layout, const qp_layer_shape* shape, int32_t max_group_tokens,
                                 int32_t n_window);
 

@@ -88,9 +88,9 @@ SIGNATURES = {
     "qp_version": (ctypes.c_char_p, []),
     # include/qp_layer.h
     "qp_rms_norm": (_i32, [_vp, _vp, _vp, _i32, _i32, _f32, _vp]),
-    "qp_linear": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp]),
+    "qp_linear": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _sz, _vp]),
     "qp_rope_table": (_i32, [_vp, _i64, _i32, _f32, ctypes.POINTER(ctypes.c_int32), _vp, _vp]),
-    "qp_qkv_rope": (_i32, [_LP, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]),
+    "qp_qkv_rope": (_i32, [_LP, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
     "qp_swiglu_gate_up": (_i32, [_vp, _vp, _vp, _i32, _i32, _i32, _vp]),
     "qp_select_linear_tile": (_i32, [_i32]),
     "qp_layer_workspace_bytes": (_sz, [_LP, _SP, _i32, _i32]),
@@ -269,9 +269,10 @@ def rms_norm(x, w, out, eps):
     _check(lib().qp_rms_norm(_ptr(x), _ptr(w), _ptr(out), x.shape[0], x.shape[1], eps, _stream()), "qp_rms_norm")
 
 
-def linear(x, w, bias, residual, out):
+def linear(x, w, bias, residual, out, workspace=None):
+    wp, wb = _ws(workspace)
     _check(lib().qp_linear(_ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(out), x.shape[0], w.shape[0], x.shape[1],
-                           _stream()), "qp_linear")
+                           wp, wb, _stream()), "qp_linear")
 
 
 def _pos_ptr(pos, first, axis_stride):
@@ -287,9 +288,10 @@ def rope_table(pos, first, n_tokens, theta, mrope_section, cos_sin):
                                _stream()), "qp_rope_table")
 
 
-def qkv_rope(layout, h, w_qkv, b_qkv, cos_sin, q, k, v):
+def qkv_rope(layout, h, w_qkv, b_qkv, cos_sin, q, k, v, workspace=None):
+    wp, wb = _ws(workspace)
     _check(lib().qp_qkv_rope(ctypes.byref(layout), _ptr(h), _ptr(w_qkv), _ptr(b_qkv), _ptr(cos_sin), h.shape[0],
-                             h.shape[1], _ptr(q), _ptr(k), _ptr(v), _stream()), "qp_qkv_rope")
+                             h.shape[1], _ptr(q), _ptr(k), _ptr(v), wp, wb, _stream()), "qp_qkv_rope")
 
 
 def swiglu_gate_up(h, w_gate_up, act):

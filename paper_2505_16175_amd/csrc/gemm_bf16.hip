@@ -125,8 +125,10 @@ __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
     const int wr = min(weight_row<MODE>(r, n0, d_ff), a.n - 1);
     w_off[q] = (unsigned)((size_t)(wr - wb) * row_b) + (unsigned)((lane % T::CPR) ^ T::swizzle(r)) * 16;
   }
-  const unsigned char* x_base = xg + (size_t)m0 * row_b;
-  const unsigned char* w_base = wg + (size_t)wb * row_b;
+  // contraction split (launches of few tiles): grid.y deals the k-steps to chunks, each leaving an f32 partial tile
+  const int step_begin = blockIdx.y * a.steps_per_split;
+  const unsigned char* x_base = xg + (size_t)m0 * row_b + (size_t)step_begin * ROWB;
+  const unsigned char* w_base = wg + (size_t)wb * row_b + (size_t)step_begin * ROWB;
   const unsigned smem_lds = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
   const unsigned x_lds = smem_lds + wave * (BM / 8) * ROWB, w_lds = smem_lds + T::XT + wave * 32 * ROWB;
 
@@ -160,7 +162,7 @@ __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
   // fragments of the step (its slot can be refilled), the next step's tiles have landed, and the wait at the
   // barrier, the refill requests and the latency of the next step's first fragment reads all run under those
   // products instead of leaving the matrix pipe idle between steps.
-  const int n_steps = a.k / BK;
+  const int n_steps = min(a.steps_per_split, a.k / BK - step_begin);
   constexpr int S = T::STAGES, PW = T::PER_WAVE;
 #pragma unroll
   for (int p = 0; p < S; ++p)
@@ -258,6 +260,28 @@ __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
 #undef GM_ISSUE
 
   // ---- store: lane owns token m = m0 + (BM/2) wm + 32 i + l32 and, in block j, outputs 8 (r >> 2) + 4 g + (r & 3)
+  if (a.split_k > 1) {
+    // partial sums of this k chunk, f32 [chunk][m][n] with n the output's logical column (for QKV: head * 128 + dim);
+    // gemm_reduce_kernel adds the chunks in order and applies the mode's store
+    float* part = a.partial + (size_t)blockIdx.y * a.m * a.n;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        int n;
+        if (MODE == GEMM_QKV_ROPE) n = ((n0 >> 7) + (wn >> 1)) * 128 + (wn & 1) * 32 + j * 64 + 8 * q4 + 4 * g;
+        else n = n0 + wn * 64 + j * 32 + 8 * q4 + 4 * g;
+        if (n >= a.n) continue;
+#pragma unroll
+        for (int i = 0; i < T::MI; ++i) {
+          const int m = m0 + wm * (BM / 2) + i * 32 + l32;
+          if (m >= a.m) continue;
+          *(float4*)(part + (size_t)m * a.n + n) =
+              make_float4(acc[j][i][4 * q4], acc[j][i][4 * q4 + 1], acc[j][i][4 * q4 + 2], acc[j][i][4 * q4 + 3]);
+        }
+      }
+    return;
+  }
   if (MODE == GEMM_PLAIN) {
     const bf16_t* bias = (const bf16_t*)a.bias;
     const bf16_t* res = (const bf16_t*)a.residual;
@@ -357,6 +381,74 @@ __global__ __launch_bounds__(GM_NW * 64) void gemm_bf16_kernel(GemmArgs a) {
   }
 }
 
+// Second launch of a split contraction: sums the chunks' partial tiles in chunk order and applies the mode's store.
+// One thread per token and run of 4 outputs (QKV_ROPE: per run of 4 dims of a head's first half and their rotary
+// partners).
+template <int MODE>
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmArgs a) {
+  const long id = (long)blockIdx.x * 256 + threadIdx.x;
+  const int runs = MODE == GEMM_QKV_ROPE ? a.n / 8 : a.n / 4;  // per token
+  if (id >= (long)a.m * runs) return;
+  const int m = (int)(id / runs), r = (int)(id - (long)m * runs);
+  const size_t stride = (size_t)a.m * a.n;
+  if (MODE == GEMM_PLAIN) {
+    const int n = 4 * r;
+    const float* p = a.partial + (size_t)m * a.n + n;
+    float4 y = *(const float4*)p;
+    for (int c = 1; c < a.split_k; ++c) {
+      const float4 t = *(const float4*)(p + c * stride);
+      y.x += t.x, y.y += t.y, y.z += t.z, y.w += t.w;
+    }
+    if (a.bias != nullptr) {
+      const uint2 raw = *(const uint2*)((const bf16_t*)a.bias + n);
+      y.x += bf16lo_to_f32(raw.x), y.y += bf16hi_to_f32(raw.x), y.z += bf16lo_to_f32(raw.y), y.w += bf16hi_to_f32(raw.y);
+    }
+    if (a.residual != nullptr) {
+      const uint2 raw = *(const uint2*)((const bf16_t*)a.residual + (size_t)m * a.n + n);
+      y.x += bf16lo_to_f32(raw.x), y.y += bf16hi_to_f32(raw.x), y.z += bf16lo_to_f32(raw.y), y.w += bf16hi_to_f32(raw.y);
+    }
+    bf16x4 pk;
+    pk[0] = (__bf16)y.x, pk[1] = (__bf16)y.y, pk[2] = (__bf16)y.z, pk[3] = (__bf16)y.w;
+    *(uint2*)((bf16_t*)a.out + (size_t)m * a.n + n) = __builtin_bit_cast(uint2, pk);
+  } else if (MODE == GEMM_QKV_ROPE) {
+    const int head = r / 16, f = 4 * (r % 16);  // f: first of 4 rotary frequencies
+    const float* p = a.partial + (size_t)m * a.n + head * 128 + f;
+    float4 lo4 = *(const float4*)p, hi4 = *(const float4*)(p + 64);
+    for (int c = 1; c < a.split_k; ++c) {
+      const float4 t = *(const float4*)(p + c * stride), u = *(const float4*)(p + c * stride + 64);
+      lo4.x += t.x, lo4.y += t.y, lo4.z += t.z, lo4.w += t.w;
+      hi4.x += u.x, hi4.y += u.y, hi4.z += u.z, hi4.w += u.w;
+    }
+    float lo[4] = {lo4.x, lo4.y, lo4.z, lo4.w}, hi[4] = {hi4.x, hi4.y, hi4.z, hi4.w};
+    const bf16_t* bias = (const bf16_t*)a.bias + (size_t)head * 128;
+    const uint2 r0 = *(const uint2*)(bias + f), r1 = *(const uint2*)(bias + 64 + f);
+    lo[0] += bf16lo_to_f32(r0.x), lo[1] += bf16hi_to_f32(r0.x), lo[2] += bf16lo_to_f32(r0.y), lo[3] += bf16hi_to_f32(r0.y);
+    hi[0] += bf16lo_to_f32(r1.x), hi[1] += bf16hi_to_f32(r1.x), hi[2] += bf16lo_to_f32(r1.y), hi[3] += bf16hi_to_f32(r1.y);
+    bf16_t* dst;
+    int heads_dst, head_dst;
+    if (head < a.h_q) dst = (bf16_t*)a.q, heads_dst = a.h_q, head_dst = head;
+    else if (head < a.h_q + a.h_kv) dst = (bf16_t*)a.k_out, heads_dst = a.h_kv, head_dst = head - a.h_q;
+    else dst = (bf16_t*)a.v_out, heads_dst = a.h_kv, head_dst = head - a.h_q - a.h_kv;
+    if (head < a.h_q + a.h_kv) {
+      const float4 cs0 = *(const float4*)(a.cos_sin + ((size_t)m * 64 + f) * 2);
+      const float4 cs1 = *(const float4*)(a.cos_sin + ((size_t)m * 64 + f + 2) * 2);
+      const float c[4] = {cs0.x, cs0.z, cs1.x, cs1.z}, sn[4] = {cs0.y, cs0.w, cs1.y, cs1.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float x0 = lo[e], x1 = hi[e];
+        lo[e] = x0 * c[e] - x1 * sn[e];
+        hi[e] = x1 * c[e] + x0 * sn[e];
+      }
+    }
+    bf16x4 p0, p1;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) p0[e] = (__bf16)lo[e], p1[e] = (__bf16)hi[e];
+    bf16_t* row = dst + ((size_t)m * heads_dst + head_dst) * 128;
+    *(uint2*)(row + f) = __builtin_bit_cast(uint2, p0);
+    *(uint2*)(row + 64 + f) = __builtin_bit_cast(uint2, p1);
+  }
+}
+
 bool gemm_supported(const GemmArgs& a, int mode) {
   if (a.m <= 0 || a.n <= 0 || a.k <= 0 || a.k % 64 != 0) return false;
   // byte offsets inside a tile's row range are 32-bit (plus the k offset of the step)
@@ -366,6 +458,41 @@ bool gemm_supported(const GemmArgs& a, int mode) {
   if (mode == GEMM_QKV_ROPE) return a.h_q > 0 && a.h_kv > 0 && a.n == (a.h_q + 2 * a.h_kv) * 128 && a.n % GM_BN == 0;
   if (mode == GEMM_SWIGLU) return a.n % (2 * 128) == 0 && a.n % GM_BN == 0;
   return false;
+}
+
+static int g_forced_tile_rows = 0;  // 0: choose per launch; 128 / 256: tests cover both tilings
+void gemm_force_tile_rows(int rows) { g_forced_tile_rows = rows; }
+
+// 256-row tiles unless 128-row tiles finish sooner: a launch lasts ceil(tiles / CUs) rounds of one tile each, and a
+// 128-row tile costs about 0.6 of a 256-row one (half the products, less reuse of the weight fragments).
+int gemm_tile_rows(const GemmArgs& a) {
+  if (g_forced_tile_rows != 0) return g_forced_tile_rows;
+  const int cus = device_cu_count();
+  const long tiles_n = (a.n + GM_BN - 1) / GM_BN;
+  const long t256 = (long)((a.m + 255) / 256) * tiles_n, t128 = (long)((a.m + 127) / 128) * tiles_n;
+  const double cost256 = (double)((t256 + cus - 1) / cus), cost128 = 0.6 * (double)((t128 + cus - 1) / cus);
+  return cost128 < cost256 ? 128 : 256;
+}
+
+// Contraction split: launches whose tiles would occupy at most a quarter of the CUs (few tokens against a long k:
+// text chunks and decode steps through the layer, where the weights are streamed once and HBM is the bound) deal the
+// k-steps to chunks, about one workgroup per CU in all, at least 4 steps per chunk, as many chunks as the scratch holds.
+GemmSplit gemm_plan_split(const GemmArgs& a, int mode, size_t scratch_bytes) {
+  GemmSplit p{1, a.k / GM_BK, 0};
+  if (mode == GEMM_SWIGLU || scratch_bytes == 0) return p;
+  const int rows = gemm_tile_rows(a), cus = device_cu_count();
+  const long tiles = (long)((a.m + rows - 1) / rows) * ((a.n + GM_BN - 1) / GM_BN);
+  const int steps = a.k / GM_BK;
+  if (tiles * 4 > cus || steps < 8) return p;
+  long want = (cus + tiles - 1) / tiles;
+  if (want > steps / 4) want = steps / 4;
+  const size_t per_chunk = (size_t)a.m * a.n * sizeof(float);
+  if ((size_t)want * per_chunk > scratch_bytes) want = (long)(scratch_bytes / per_chunk);
+  if (want < 2) return p;
+  p.steps_per_split = (int)((steps + want - 1) / want);
+  p.split_k = (steps + p.steps_per_split - 1) / p.steps_per_split;  // every chunk non-empty
+  p.scratch_bytes = (size_t)p.split_k * per_chunk;
+  return p;
 }
 
 template <int MODE, int BM, int BK>
@@ -384,34 +511,27 @@ static hipError_t launch_tile(GemmArgs a, hipStream_t s) {
   a.m_block = a.tiles_m < 8 ? a.tiles_m : 8;
   a.n_quads = ((a.tiles_n + 7) / 8 + 3) / 4;  // weight tiles per XCD, in fours
   const int m_chunks = (a.tiles_m + a.m_block - 1) / a.m_block;
-  hipLaunchKernelGGL((gemm_bf16_kernel<MODE, BM, BK>), dim3(8 * m_chunks * a.m_block * a.n_quads * 4), dim3(GM_NW * 64), lds, s, a);
+  hipLaunchKernelGGL((gemm_bf16_kernel<MODE, BM, BK>), dim3(8 * m_chunks * a.m_block * a.n_quads * 4, a.split_k),
+                     dim3(GM_NW * 64), lds, s, a);
   return hipSuccess;
 }
 
-// 256-row tiles unless 128-row tiles finish sooner: a launch lasts ceil(tiles / CUs) rounds of one tile each, and a
-// 128-row tile costs about 0.6 of a 256-row one (half the products, less reuse of the weight fragments).
-static int g_forced_tile_rows = 0;  // 0: choose per launch; 128 / 256: tests cover both tilings
-void gemm_force_tile_rows(int rows) { g_forced_tile_rows = rows; }
-
-int gemm_tile_rows(const GemmArgs& a) {
-  if (g_forced_tile_rows != 0) return g_forced_tile_rows;
-  const int cus = device_cu_count();
-  const long tiles_n = (a.n + GM_BN - 1) / GM_BN;
-  const long t256 = (long)((a.m + 255) / 256) * tiles_n, t128 = (long)((a.m + 127) / 128) * tiles_n;
-  const double cost256 = (double)((t256 + cus - 1) / cus), cost128 = 0.6 * (double)((t128 + cus - 1) / cus);
-  return cost128 < cost256 ? 128 : 256;
-}
-
 template <int MODE>
-static hipError_t launch_mode(const GemmArgs& a, hipStream_t s) {
-  return gemm_tile_rows(a) == 128 ? launch_tile<MODE, 128, GM_BK>(a, s) : launch_tile<MODE, 256, GM_BK>(a, s);
+static hipError_t launch_mode(GemmArgs a, void* scratch, size_t scratch_bytes, hipStream_t s) {
+  const GemmSplit sp = gemm_plan_split(a, MODE, scratch != nullptr ? scratch_bytes : 0);
+  a.split_k = sp.split_k, a.steps_per_split = sp.steps_per_split, a.partial = (float*)scratch;
+  hipError_t e = gemm_tile_rows(a) == 128 ? launch_tile<MODE, 128, GM_BK>(a, s) : launch_tile<MODE, 256, GM_BK>(a, s);
+  if (e != hipSuccess || a.split_k == 1) return e;
+  const long threads = (long)a.m * (MODE == GEMM_QKV_ROPE ? a.n / 8 : a.n / 4);
+  hipLaunchKernelGGL(gemm_reduce_kernel<MODE>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, a);
+  return hipSuccess;
 }
 
-hipError_t launch_gemm_bf16(const GemmArgs& a, int mode, hipStream_t s) {
+hipError_t launch_gemm_bf16(const GemmArgs& a, int mode, void* scratch, size_t scratch_bytes, hipStream_t s) {
   switch (mode) {
-    case GEMM_PLAIN: return launch_mode<GEMM_PLAIN>(a, s);
-    case GEMM_QKV_ROPE: return launch_mode<GEMM_QKV_ROPE>(a, s);
-    case GEMM_SWIGLU: return launch_mode<GEMM_SWIGLU>(a, s);
+    case GEMM_PLAIN: return launch_mode<GEMM_PLAIN>(a, scratch, scratch_bytes, s);
+    case GEMM_QKV_ROPE: return launch_mode<GEMM_QKV_ROPE>(a, scratch, scratch_bytes, s);
+    case GEMM_SWIGLU: return launch_mode<GEMM_SWIGLU>(a, nullptr, 0, s);
   }
   return hipErrorInvalidValue;
 }

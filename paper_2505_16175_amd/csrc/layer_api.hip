@@ -31,9 +31,13 @@ qp_status check_layer(const qp_layout* L, const qp_layer_shape* S) {
   return QP_OK;
 }
 
-// Workspace of qp_layer_group, in order: h | q | k | v | attn | x1 | act | cos_sin | scores | path workspace
+// Workspace of qp_layer_group, in order: h | q | k | v | attn | x1 | act | cos_sin | scores | projection split
+// scratch | path workspace
+// Room for the partial sums of a split contraction (launches of few tokens; see gemm_plan_split)
+constexpr size_t kGemmSplitBytes = (size_t)32 << 20;
+
 struct Carve {
-  size_t h, q, k, v, attn, x1, act, cs, scores, path, total;
+  size_t h, q, k, v, attn, x1, act, cs, scores, gemm, path, total;
 };
 Carve carve(const qp_layout* L, const qp_layer_shape* S, int32_t n_g, int32_t n_window) {
   Carve c{};
@@ -52,6 +56,7 @@ Carve carve(const qp_layout* L, const qp_layer_shape* S, int32_t n_g, int32_t n_
   c.act = take((size_t)n_g * S->d_ff * 2);
   c.cs = take((size_t)n_g * 64 * 2 * sizeof(float));
   c.scores = take((size_t)L->n_kv_heads * n_g * sizeof(float));
+  c.gemm = take(kGemmSplitBytes);
   c.path = off;
   c.total = off + qp_workspace_bytes(L, n_g, n_window);
   return c;
@@ -71,15 +76,16 @@ qp_status qp_rms_norm(const void* x, const void* w, void* out, int32_t n_tokens,
 }
 
 qp_status qp_linear(const void* x, const void* w, const void* bias_or_null, const void* residual_or_null, void* out,
-                    int32_t m, int32_t n, int32_t k, void* hip_stream) {
+                    int32_t m, int32_t n, int32_t k, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!aligned16(x) || !aligned16(w) || !aligned16(out) || m <= 0 || n <= 0 || k <= 0) return QP_ERR_INVALID_ARG;
+  if (workspace != nullptr && (((uintptr_t)workspace) & 255u)) return QP_ERR_INVALID_ARG;
   if ((bias_or_null != nullptr && !aligned16(bias_or_null)) || (residual_or_null != nullptr && !aligned16(residual_or_null)))
     return QP_ERR_INVALID_ARG;
   qp::GemmArgs a{};
   a.x = x, a.w = w, a.bias = bias_or_null, a.residual = residual_or_null, a.out = out;
   a.m = m, a.n = n, a.k = k;
   if (!qp::gemm_supported(a, qp::GEMM_PLAIN)) return QP_ERR_UNSUPPORTED;
-  return finish(qp::launch_gemm_bf16(a, qp::GEMM_PLAIN, (hipStream_t)hip_stream));
+  return finish(qp::launch_gemm_bf16(a, qp::GEMM_PLAIN, workspace, workspace_bytes, (hipStream_t)hip_stream));
 }
 
 qp_status qp_rope_table(const int32_t* pos, int64_t axis_stride, int32_t n_tokens, float theta,
@@ -98,8 +104,9 @@ qp_status qp_rope_table(const int32_t* pos, int64_t axis_stride, int32_t n_token
 
 qp_status qp_qkv_rope(const qp_layout* layout, const void* h, const void* w_qkv, const void* b_qkv,
                       const float* cos_sin, int32_t n_tokens, int32_t d_model, void* q, void* k, void* v,
-                      void* hip_stream) {
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (layout == nullptr || layout->n_q_heads <= 0 || layout->n_kv_heads <= 0) return QP_ERR_INVALID_ARG;
+  if (workspace != nullptr && (((uintptr_t)workspace) & 255u)) return QP_ERR_INVALID_ARG;
   if (!aligned16(h) || !aligned16(w_qkv) || !aligned16(b_qkv) || !aligned16(cos_sin) || !aligned16(q) ||
       !aligned16(k) || !aligned16(v) || n_tokens <= 0 || d_model <= 0)
     return QP_ERR_INVALID_ARG;
@@ -109,7 +116,7 @@ qp_status qp_qkv_rope(const qp_layout* layout, const void* h, const void* w_qkv,
   a.m = n_tokens, a.n = (layout->n_q_heads + 2 * layout->n_kv_heads) * 128, a.k = d_model;
   a.h_q = layout->n_q_heads, a.h_kv = layout->n_kv_heads;
   if (!qp::gemm_supported(a, qp::GEMM_QKV_ROPE)) return QP_ERR_UNSUPPORTED;
-  return finish(qp::launch_gemm_bf16(a, qp::GEMM_QKV_ROPE, (hipStream_t)hip_stream));
+  return finish(qp::launch_gemm_bf16(a, qp::GEMM_QKV_ROPE, workspace, workspace_bytes, (hipStream_t)hip_stream));
 }
 
 qp_status qp_swiglu_gate_up(const void* h, const void* w_gate_up, void* act, int32_t n_tokens, int32_t d_model,
@@ -121,7 +128,7 @@ qp_status qp_swiglu_gate_up(const void* h, const void* w_gate_up, void* act, int
   a.x = h, a.w = w_gate_up, a.out = act;
   a.m = n_tokens, a.n = 2 * d_ff, a.k = d_model;
   if (!qp::gemm_supported(a, qp::GEMM_SWIGLU)) return QP_ERR_UNSUPPORTED;
-  return finish(qp::launch_gemm_bf16(a, qp::GEMM_SWIGLU, (hipStream_t)hip_stream));
+  return finish(qp::launch_gemm_bf16(a, qp::GEMM_SWIGLU, nullptr, 0, (hipStream_t)hip_stream));
 }
 
 qp_status qp_select_linear_tile(int32_t token_rows) {
@@ -196,7 +203,7 @@ qp_status qp_layer_group(const qp_layout* layout, const qp_layer_shape* shape, c
   qp::launch_rms_norm(x_g, weights->ln1_w, ws + c.h, n_g, dm, shape->rms_eps, s);
   qp::launch_rope_table(pos, (long)axis_stride, n_g, shape->rope_theta, shape->mrope_section[0], shape->mrope_section[1],
                         (float*)(ws + c.cs), s);
-  st = finish(qp::launch_gemm_bf16(qkv, qp::GEMM_QKV_ROPE, s));
+  st = finish(qp::launch_gemm_bf16(qkv, qp::GEMM_QKV_ROPE, ws + c.gemm, kGemmSplitBytes, s));
   if (st != QP_OK) return st;
   // Scoring, top-k and compaction need the group's K and V only, not its attention: they run on the library's side
   // stream beside the attention and the projections that follow, and are joined back before the call returns.
@@ -217,12 +224,12 @@ qp_status qp_layer_group(const qp_layout* layout, const qp_layer_shape* shape, c
   st = qp_topk_compact(layout, (const float*)(ws + c.scores), ws + c.k, ws + c.v, n_g, keep, group_token_base, cache,
                        kept_idx_or_null, score_ws, score_bytes, fork.stream());
   if (st != QP_OK) return st;
-  st = finish(qp::launch_gemm_bf16(oproj, qp::GEMM_PLAIN, s));
+  st = finish(qp::launch_gemm_bf16(oproj, qp::GEMM_PLAIN, ws + c.gemm, kGemmSplitBytes, s));
   if (st != QP_OK) return st;
   qp::launch_rms_norm(ws + c.x1, weights->ln2_w, ws + c.h, n_g, dm, shape->rms_eps, s);
-  st = finish(qp::launch_gemm_bf16(gate_up, qp::GEMM_SWIGLU, s));
+  st = finish(qp::launch_gemm_bf16(gate_up, qp::GEMM_SWIGLU, nullptr, 0, s));
   if (st != QP_OK) return st;
-  return finish(qp::launch_gemm_bf16(down, qp::GEMM_PLAIN, s));
+  return finish(qp::launch_gemm_bf16(down, qp::GEMM_PLAIN, ws + c.gemm, kGemmSplitBytes, s));
 }
 
 qp_status qp_layer_window_queries(const qp_layout* layout, const qp_layer_shape* shape,
@@ -251,7 +258,7 @@ qp_status qp_layer_window_queries(const qp_layout* layout, const qp_layer_shape*
   qp::launch_rms_norm(x_win, weights->ln1_w, ws + c.h, n_window, shape->d_model, shape->rms_eps, s);
   qp::launch_rope_table(pos, (long)axis_stride, n_window, shape->rope_theta, shape->mrope_section[0],
                         shape->mrope_section[1], (float*)(ws + c.cs), s);
-  return finish(qp::launch_gemm_bf16(qkv, qp::GEMM_QKV_ROPE, s));
+  return finish(qp::launch_gemm_bf16(qkv, qp::GEMM_QKV_ROPE, ws + c.gemm, kGemmSplitBytes, s));
 }
 
 }  // extern "C"

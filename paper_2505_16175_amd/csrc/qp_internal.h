@@ -185,9 +185,17 @@ struct GemmArgs {
   int m, n, k;
   int h_q, h_kv;
   int tiles_m, tiles_n, m_block, n_quads;  // filled by the launcher (tile counts and the XCD block mapping)
+  int split_k, steps_per_split;            // filled by the launcher: k chunks (1 = none) and 64-wide k-steps per chunk
+  float* partial;                          // [split_k][m][n] f32 partial sums when split_k > 1
 };
 bool gemm_supported(const GemmArgs& a, int mode);
-hipError_t launch_gemm_bf16(const GemmArgs& a, int mode, hipStream_t s);
+// scratch: optional (256-byte aligned) room for the partial sums of a split contraction; without it nothing is split
+hipError_t launch_gemm_bf16(const GemmArgs& a, int mode, void* scratch, size_t scratch_bytes, hipStream_t s);
+struct GemmSplit {
+  int split_k, steps_per_split;
+  size_t scratch_bytes;
+};
+GemmSplit gemm_plan_split(const GemmArgs& a, int mode, size_t scratch_bytes);  // host arithmetic only
 int gemm_tile_rows(const GemmArgs& a);    // token rows per workgroup tile the launcher would use: 128 or 256
 void gemm_force_tile_rows(int rows);      // 0 = choose per launch (default), 128 or 256
 void launch_rms_norm(const void* x, const void* w, void* out, int n_tokens, int d_model, float eps, hipStream_t s);

@@ -142,6 +142,60 @@ def test_swiglu_gate_up(n, d_model, d_ff, tile):
     assert_stored_close(to_f64(act), LO.bf16_round(want), "swiglu")
 
 
+@pytest.mark.parametrize("m,n,k,bias,res", [(1, 3584, 18944, False, True), (7, 512, 1024, True, True), (64, 3584, 3584, False, True),
+                                            (130, 264, 640, True, False), (300, 1024, 4096, False, False)])
+def test_linear_split_contraction(m, n, k, bias, res):
+    """Few tokens against long rows with scratch offered: the contraction is dealt to k chunks and a second launch
+    adds the partial sums. Same tolerance as the unsplit call, and bit-identical between two runs."""
+    print(f"case m={m} n={n} k={k}", flush=True)
+    g = torch.Generator().manual_seed(m + 3 * n + 5 * k)
+    x, w = _bf(m, k, gen=g), _bf(n, k, gen=g, scale=k ** -0.5)
+    b = _bf(n, gen=g, scale=0.5) if bias else None
+    r = _bf(m, n, gen=g) if res else None
+    want = LO.linear(to_f64(x), to_f64(w), None if b is None else to_f64(b))
+    if r is not None:
+        want = want + to_f64(r)
+    dv = lambda t: None if t is None else t.to(DEV)
+    scratch = torch.empty(32 << 20, dtype=torch.uint8, device=DEV)
+    outs = []
+    for _ in range(2):
+        out = torch.full((m, n), float("nan"), dtype=torch.bfloat16, device=DEV)
+        scratch.fill_(0xff)                                       # NaN patterns: every partial read must have been written
+        B.linear(dv(x), dv(w), dv(b), dv(r), out, scratch)
+        torch.cuda.synchronize()
+        outs.append(out)
+    assert_stored_close(to_f64(outs[0]), LO.bf16_round(want), "split linear")
+    assert torch.equal(outs[0], outs[1])
+    plain = torch.empty_like(outs[0])
+    B.linear(dv(x), dv(w), dv(b), dv(r), plain)                   # unsplit: differs at most by rounding flips
+    torch.cuda.synchronize()
+    assert_stored_close(to_f64(plain), LO.bf16_round(want), "unsplit linear")
+
+
+@pytest.mark.parametrize("n,d_model,h_q,h_kv", [(1, 3584, 28, 4), (9, 1024, 4, 2), (64, 3584, 28, 4)])
+def test_qkv_rope_split_contraction(n, d_model, h_q, h_kv):
+    print(f"case n={n} d_model={d_model} heads={h_q}/{h_kv}", flush=True)
+    g = torch.Generator().manual_seed(7 * n + d_model + h_q)
+    theta, sections = 1e6, (16, 24, 24)
+    h = _bf(n, d_model, gen=g)
+    nq = (h_q + 2 * h_kv) * 128
+    w, b = _bf(nq, d_model, gen=g, scale=d_model ** -0.5), _bf(nq, gen=g, scale=0.5)
+    pos = W.text_positions(n, 4000)
+    want = _oracle_qkv(to_f64(h), to_f64(w), to_f64(b), pos.numpy(), h_q, h_kv, theta, sections)
+    layout = B.make_layout(h_q, h_kv, 128, "bf16")
+    cs = torch.empty(n, 64, 2, dtype=torch.float32, device=DEV)
+    B.rope_table(pos.to(DEV), 0, n, theta, sections, cs)
+    scratch = torch.empty(32 << 20, dtype=torch.uint8, device=DEV)
+    scratch.fill_(0xff)
+    q = torch.full((n, h_q, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    k = torch.full((n, h_kv, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    v = torch.full((n, h_kv, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    B.qkv_rope(layout, h.to(DEV), w.to(DEV), b.to(DEV), cs, q, k, v, scratch)
+    torch.cuda.synchronize()
+    for name, got, ref in zip("qkv", (q, k, v), want):
+        assert_stored_close(to_f64(got), ref, name)
+
+
 def test_unsupported_shapes_are_refused_before_launch():
     x = torch.zeros(4, 72, dtype=torch.bfloat16, device=DEV)
     w = torch.zeros(8, 72, dtype=torch.bfloat16, device=DEV)
