@@ -86,6 +86,18 @@ qp_status qp_swiglu_gate_up(const void* h, const void* w_gate_up, void* act, int
  * cover both): 0 = choose per call, 128 or 256. INVALID_ARG for any other value. */
 qp_status qp_select_linear_tile(int32_t token_rows);
 
+/* How qp_linear would lay out a call (host arithmetic only, nothing is launched): token rows per workgroup tile,
+ * workgroups per k chunk (including idle padding workgroups of the XCD mapping), k chunks (1 = not split) with
+ * their 64-wide k-steps, and how much of the offered scratch the partial sums would take. */
+typedef struct {
+  int32_t token_rows_per_tile; /* 128 or 256 */
+  int32_t workgroups;
+  int32_t k_chunks;
+  int32_t k_steps_per_chunk;   /* the last chunk may have fewer */
+  size_t scratch_bytes;
+} qp_linear_plan_info;
+qp_status qp_linear_plan(int32_t m, int32_t n, int32_t k, size_t workspace_bytes, qp_linear_plan_info* out);
+
 /* ---- the layer ------------------------------------------------------------------------------------------- */
 
 /* Workspace of qp_layer_group / qp_layer_window_queries for groups of at most max_group_tokens tokens and a

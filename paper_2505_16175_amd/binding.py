@@ -62,6 +62,11 @@ GROUP_FN = ctypes.CFUNCTYPE(ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, cty
 QP_FEED_PAGEABLE, QP_FEED_END, QP_FEED_TIMEOUT = 1, 100, 101
 
 
+class qp_linear_plan_info(ctypes.Structure):
+    _fields_ = [("token_rows_per_tile", ctypes.c_int32), ("workgroups", ctypes.c_int32), ("k_chunks", ctypes.c_int32),
+                ("k_steps_per_chunk", ctypes.c_int32), ("scratch_bytes", ctypes.c_size_t)]
+
+
 class QPError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
@@ -93,6 +98,7 @@ SIGNATURES = {
     "qp_qkv_rope": (_i32, [_LP, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
     "qp_swiglu_gate_up": (_i32, [_vp, _vp, _vp, _i32, _i32, _i32, _vp]),
     "qp_select_linear_tile": (_i32, [_i32]),
+    "qp_linear_plan": (_i32, [_i32, _i32, _i32, _sz, ctypes.POINTER(qp_linear_plan_info)]),
     "qp_layer_workspace_bytes": (_sz, [_LP, _SP, _i32, _i32]),
     "qp_layer_group": (_i32, [_LP, _SP, _WP, _vp, _vp, _i64, _i32, _i32, _vp, _i32, _i32, _i32, _CP, _vp, _vp, _vp,
                               _sz, _vp]),
@@ -297,6 +303,12 @@ def qkv_rope(layout, h, w_qkv, b_qkv, cos_sin, q, k, v, workspace=None):
 def swiglu_gate_up(h, w_gate_up, act):
     _check(lib().qp_swiglu_gate_up(_ptr(h), _ptr(w_gate_up), _ptr(act), h.shape[0], h.shape[1],
                                    w_gate_up.shape[0] // 2, _stream()), "qp_swiglu_gate_up")
+
+
+def linear_plan(m, n, k, workspace_bytes=0) -> dict:
+    info = qp_linear_plan_info()
+    _check(lib().qp_linear_plan(m, n, k, workspace_bytes, ctypes.byref(info)), "qp_linear_plan")
+    return {name: getattr(info, name) for name, _ in qp_linear_plan_info._fields_}
 
 
 def select_linear_tile(token_rows: int):

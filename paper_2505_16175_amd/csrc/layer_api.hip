@@ -131,6 +131,23 @@ qp_status qp_swiglu_gate_up(const void* h, const void* w_gate_up, void* act, int
   return finish(qp::launch_gemm_bf16(a, qp::GEMM_SWIGLU, nullptr, 0, (hipStream_t)hip_stream));
 }
 
+qp_status qp_linear_plan(int32_t m, int32_t n, int32_t k, size_t workspace_bytes, qp_linear_plan_info* out) {
+  if (out == nullptr || m <= 0 || n <= 0 || k <= 0) return QP_ERR_INVALID_ARG;
+  qp::GemmArgs a{};
+  a.m = m, a.n = n, a.k = k;
+  if (!qp::gemm_supported(a, qp::GEMM_PLAIN)) return QP_ERR_UNSUPPORTED;
+  const qp::GemmSplit sp = qp::gemm_plan_split(a, qp::GEMM_PLAIN, workspace_bytes);
+  const int rows = qp::gemm_tile_rows(a);
+  const int tiles_m = (m + rows - 1) / rows, tiles_n = (n + 255) / 256;
+  const int m_block = tiles_m < 8 ? tiles_m : 8;
+  out->token_rows_per_tile = rows;
+  out->workgroups = 8 * ((tiles_m + m_block - 1) / m_block) * m_block * (((tiles_n + 7) / 8 + 3) / 4) * 4;
+  out->k_chunks = sp.split_k;
+  out->k_steps_per_chunk = sp.steps_per_split;
+  out->scratch_bytes = sp.scratch_bytes;
+  return QP_OK;
+}
+
 qp_status qp_select_linear_tile(int32_t token_rows) {
   if (token_rows != 0 && token_rows != 128 && token_rows != 256) return QP_ERR_INVALID_ARG;
   qp::gemm_force_tile_rows(token_rows);

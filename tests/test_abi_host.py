@@ -25,6 +25,34 @@ def test_library_exports_every_declared_symbol():
     assert B.version().startswith("quickprefill")
 
 
+def test_linear_plan_chunks_cover_the_contraction():
+    """Host arithmetic of the projection launch: k chunks are non-empty and cover all 64-wide k-steps, the partial
+    sums fit the scratch offered, launches that fill the GPU are never split, and without scratch nothing is."""
+    offered = 32 << 20
+    for m in (1, 7, 64, 128, 129, 300, 2048, 8192):
+        for n, k in ((3584, 3584), (4608, 3584), (3584, 18944), (512, 1024), (8, 64), (8192, 29568), (264, 640)):
+            p = B.linear_plan(m, n, k, offered)
+            rows, steps = p["token_rows_per_tile"], k // 64
+            assert rows in (128, 256)
+            tiles = -(-m // rows) * -(-n // 256)
+            assert p["workgroups"] >= tiles and p["workgroups"] % 8 == 0
+            c, per = p["k_chunks"], p["k_steps_per_chunk"]
+            assert c >= 1 and (c - 1) * per < steps <= c * per
+            if c > 1:
+                assert tiles * 4 <= 256 and per >= 4 and c * tiles <= 256 + tiles
+                assert p["scratch_bytes"] == c * m * n * 4 <= offered
+            else:
+                assert p["scratch_bytes"] == 0
+            if tiles * 4 > 256:
+                assert c == 1
+            assert B.linear_plan(m, n, k, 0)["k_chunks"] == 1
+    # the layer's decode-shaped calls do split
+    assert B.linear_plan(1, 3584, 18944, offered)["k_chunks"] > 8
+    assert B.linear_plan(1, 4608, 3584, offered)["k_chunks"] > 8
+    with pytest.raises(B.QPError):
+        B.linear_plan(4, 8, 72)                                   # k not a multiple of 64
+
+
 def test_layer_workspace_and_shape_errors():
     L = B.make_layout(28, 4, 128, "bf16")
     S = B.make_layer_shape(3584, 18944)
