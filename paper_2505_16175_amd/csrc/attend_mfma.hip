@@ -425,6 +425,56 @@ __global__ __launch_bounds__(MG_WAVES * 64) void attend_merge_kernel(AttendArgs 
     a.lse[(size_t)(h * r_heads + j) * a.n_g + t] = (big + log2f(dsum)) * 0.6931471805599453f;
 }
 
+// The same merge for launches of many rows and few chunks (small groups against a long cache: thousands of rows,
+// a handful of chunks): one wavefront per row, four rows per workgroup, no exchange through LDS. Same arithmetic
+// order per row as a single wavefront of attend_merge_kernel would use: chunks in batches of 8 around a running max.
+constexpr int MR_WAVES = 4;
+__global__ __launch_bounds__(MR_WAVES * 64) void attend_merge_rows_kernel(AttendArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int r_heads = a.h_q / a.h_kv;
+  const int n_rows = a.n_g * r_heads;
+  const long total = (long)a.h_kv * n_rows;
+  const long grow = (long)blockIdx.x * MR_WAVES + (threadIdx.x >> 6);
+  if (grow >= total) return;
+  const int h = (int)(grow / n_rows), row = (int)(grow - (long)h * n_rows);
+  const int t = row / r_heads, j = row - t * r_heads;
+  float m = -INFINITY, den = 0.f, acc0 = 0.f, acc1 = 0.f;
+  for (int c0 = 0; c0 < a.n_split; c0 += 8) {
+    float ls[8];
+    float2 po[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int c = min(c0 + u, a.n_split - 1);
+      ls[u] = c0 + u < a.n_split ? a.part_lse[(size_t)c * total + grow] : -INFINITY;
+      po[u] = *(const float2*)(a.part_o + ((size_t)c * total + grow) * MF_D + 2 * lane);
+    }
+    float mb = ls[0];  // finite: chunk c0 exists
+#pragma unroll
+    for (int u = 1; u < 8; ++u) mb = fmaxf(mb, ls[u]);
+    const float m_new = fmaxf(m, mb);
+    const float keep = exp2f(m - m_new);  // 0 the first time
+    den *= keep;
+    acc0 *= keep;
+    acc1 *= keep;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const float w = exp2f(ls[u] - m_new);
+      den += w;
+      acc0 = fmaf(w, po[u].x, acc0);
+      acc1 = fmaf(w, po[u].y, acc1);
+    }
+    m = m_new;
+  }
+  const float inv = 1.f / den;
+  bf16x2 pk;
+  pk[0] = (__bf16)(acc0 * inv);
+  pk[1] = (__bf16)(acc1 * inv);
+  bf16_t* orow = (bf16_t*)a.out + ((size_t)t * a.h_q + (size_t)h * r_heads + j) * MF_D;
+  *(uint32_t*)(orow + 2 * lane) = __builtin_bit_cast(uint32_t, pk);
+  if (a.lse != nullptr && lane == 0)
+    a.lse[(size_t)(h * r_heads + j) * a.n_g + t] = (m + log2f(den)) * 0.6931471805599453f;
+}
+
 bool attend_mfma_supported(const AttendArgs& a, int dtype) {
   // 24-bit row and 32-bit byte offsets inside one head's cache / the group's K, V
   return dtype == QP_BF16 && a.d == MF_D && a.h_kv <= 65535 && (long long)a.cap * (MF_D * 2) < (1ll << 31) &&
@@ -438,14 +488,14 @@ AttendPlan plan_attend_mfma(const AttendArgs& a, size_t split_ws_bytes) {
   const int n_wg = n_rb * a.h_kv;
   p.mirrored = n_wg <= device_cu_count();  // all workgroups resident at once: balance them; otherwise longest first
   // Few rows against a long cache (text prefill, decode, small groups): split the cache over chunks so that the
-  // launch still covers the chip, about one workgroup per CU, at least two tiles per chunk.
+  // launch still covers the chip, at most one workgroup per CU, at least two tiles per chunk.
   p.n_split = 1;
   p.split_tiles = 0;
   p.scratch_bytes = 0;
   const int n_ct = (a.c + MF_BN - 1) / MF_BN;
   const size_t per_split = (size_t)a.h_kv * n_rows * (MF_D + 1) * sizeof(float);
   if (split_ws_bytes > 0 && n_wg < MF_SPLIT_BELOW && n_ct >= 4) {
-    long want = (256 + n_wg - 1) / n_wg;
+    long want = device_cu_count() / n_wg;  // rounded down: all chunks' workgroups resident at once, one round
     want = std::min<long>(want, n_ct / 2);
     want = std::min<long>(want, MF_MAX_SPLIT);
     want = std::min<long>(want, (long)(split_ws_bytes / per_split));
@@ -489,7 +539,12 @@ void launch_attend_mfma(const AttendArgs& a_in, void* split_ws, size_t split_ws_
 
 void launch_attend_merge(const AttendArgs& a, hipStream_t s) {
   const long total = (long)a.h_kv * a.n_g * (a.h_q / a.h_kv);
-  hipLaunchKernelGGL(attend_merge_kernel, dim3((unsigned)total), dim3(MG_WAVES * 64), 0, s, a);
+  // few rows, many chunks (decode, text chunks): a workgroup of 8 wavefronts per row; many rows, few chunks (small
+  // video groups): a wavefront per row
+  if (total > 1024 && a.n_split <= 16)
+    hipLaunchKernelGGL(attend_merge_rows_kernel, dim3((unsigned)((total + MR_WAVES - 1) / MR_WAVES)), dim3(MR_WAVES * 64), 0, s, a);
+  else
+    hipLaunchKernelGGL(attend_merge_kernel, dim3((unsigned)total), dim3(MG_WAVES * 64), 0, s, a);
 }
 
 }  // namespace qp
