@@ -500,7 +500,13 @@ AttendPlan plan_attend_mfma(const AttendArgs& a, size_t split_ws_bytes) {
     want = std::min<long>(want, MF_MAX_SPLIT);
     want = std::min<long>(want, (long)(split_ws_bytes / per_split));
     if (want >= 2) {
-      p.split_tiles = (n_ct + (int)want - 1) / (int)want;
+      // The last chunk also walks the group's own tiles (up to n_gt of them for the latest rows). Chunks are made
+      // just long enough that its cache tiles plus those do not exceed the others' length by more than one tile, so
+      // that all chunks end together.
+      const int n_gt = (a.n_g + MF_BN - 1) / MF_BN;
+      int st = (n_ct + (int)want - 1) / (int)want;
+      while (st < n_ct - 1 && n_ct - ((n_ct + st - 1) / st - 1) * st + n_gt > st + 1) ++st;
+      p.split_tiles = st;
       p.n_split = (n_ct + p.split_tiles - 1) / p.split_tiles;  // every chunk starts on a cache tile
       p.scratch_bytes = (size_t)p.n_split * per_split;
     }
