@@ -548,6 +548,38 @@ def test_runs_are_deterministic_and_stream_ordered():
             assert torch.equal(a, b)
 
 
+def test_prefill_can_be_resumed_from_the_cache():
+    """The pruned cache and its length are the whole state between groups (Sec. 3.2: the kept KV is what is stored):
+    a layer prefilled for the first groups by qp_prefill_video and continued group by group with the three step calls
+    (the cache's len carrying on, positions offset by the tokens already seen) ends bit-identical to one
+    qp_prefill_video over the whole video."""
+    w = scaled(CONFIGS["cfg2_7b_32k"], n_frames=23, tokens_per_frame=64, group_frames=4)   # 5 groups + a short one
+    q, k, v, qw = make_layer(w, device=DEV, sharp=True)
+    want_out, want_cache = _run_prefill(w, q, k, v, qw, "window_attn")
+    layout = B.make_layout(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
+    cache = B.Cache(layout, B.cache_capacity(w.n_frames, w.tokens_per_frame, w.group_frames, w.retention))
+    ws = B.make_workspace(layout, w.group_tokens, w.n_window)
+    out = torch.full_like(q, float("nan"))
+    head_frames = 3 * w.group_frames
+    n_head = head_frames * w.tokens_per_frame
+    B.prefill_video(layout, head_frames, w.tokens_per_frame, w.group_frames, w.retention, "window_attn",
+                    q[:n_head], k[:n_head], v[:n_head], qw, cache, out[:n_head], ws)
+    torch.cuda.synchronize()
+    assert cache.len == 3 * B.keep_count(w.group_tokens, w.retention)
+    for base, n_g in w.group_bounds()[3:]:              # two full groups and the short last one
+        sl = slice(base, base + n_g)
+        scores = torch.empty(w.n_kv_heads, n_g, dtype=torch.float32, device=DEV)
+        B.group_attend(layout, q[sl], k[sl], v[sl], cache, out[sl], None, ws)
+        B.score_kv(layout, "window_attn", k[sl], v[sl], qw, scores, ws)
+        B.topk_compact(layout, scores, k[sl], v[sl], B.keep_count(n_g, w.retention), base, cache, None, ws)
+    torch.cuda.synchronize()
+    assert cache.len == want_cache.len
+    assert torch.equal(out, want_out)
+    n = cache.len
+    assert torch.equal(cache.k[:, :n], want_cache.k[:, :n]) and torch.equal(cache.v[:, :n], want_cache.v[:, :n])
+    assert torch.equal(cache.pos[:, :n], want_cache.pos[:, :n])
+
+
 @pytest.mark.parametrize("group_frames", [5, 1])
 def test_prefill_video_replays_from_a_hip_graph(group_frames):
     """A caller may capture qp_prefill_video (its forked library streams included) into a HIP graph: every replay,
