@@ -46,7 +46,10 @@ typedef enum {
   QP_ERR_INVALID_ARG = 1, /* NULL / misaligned pointer, non-positive size, bad enum          */
   QP_ERR_UNSUPPORTED = 2, /* dtype / head_dim / group size this build has no kernel for      */
   QP_ERR_CAPACITY = 3,    /* cache capacity or workspace too small                           */
-  QP_ERR_HIP = 4          /* a launch failed; qp_last_hip_error() holds the hipError_t value */
+  QP_ERR_HIP = 4,         /* a launch failed; qp_last_hip_error() holds the hipError_t value */
+  /* not errors: returned by the consumer-side calls of qp_feed.h only */
+  QP_FEED_END = 100,      /* the feed is closed and every published group has been taken     */
+  QP_FEED_TIMEOUT = 101   /* nothing was published within the time-out                       */
 } qp_status;
 
 typedef enum { QP_F32 = 0, QP_BF16 = 1 } qp_dtype;

@@ -37,10 +37,8 @@ enum {
                           (everything except qp_feed_consume) be used on a machine without a GPU */
 };
 
-/* Returned by the consumer-side calls when the feed is closed and every published group has been taken. */
-#define QP_FEED_END 100
-/* Returned by qp_feed_next when nothing was published within the timeout. */
-#define QP_FEED_TIMEOUT 101
+/* The consumer-side calls also return QP_FEED_END (the feed is closed and every published group has been taken) and
+ * qp_feed_next QP_FEED_TIMEOUT (nothing was published within the time-out); both are qp_status values of qp.h. */
 
 /* n_slots >= 2 host slots of slot_bytes each. INVALID_ARG on bad sizes, QP_ERR_HIP if an allocation fails. */
 qp_status qp_feed_create(int32_t n_slots, size_t slot_bytes, int32_t flags, qp_feed** out);

@@ -159,8 +159,8 @@ qp_status qp_feed_next(qp_feed* feed, int32_t timeout_ms, const void** host_slot
   std::unique_lock<std::mutex> lk(feed->mu);
   auto ready = [&] { return feed->taken < feed->written || feed->closed; };
   if (timeout_ms < 0) feed->cv.wait(lk, ready);
-  else if (!feed->cv.wait_for(lk, std::chrono::milliseconds(timeout_ms), ready)) return (qp_status)QP_FEED_TIMEOUT;
-  if (feed->taken >= feed->written) return (qp_status)QP_FEED_END;  // closed and drained
+  else if (!feed->cv.wait_for(lk, std::chrono::milliseconds(timeout_ms), ready)) return QP_FEED_TIMEOUT;
+  if (feed->taken >= feed->written) return QP_FEED_END;  // closed and drained
   const int slot = (int)(feed->taken % feed->n_slots);
   *host_slot = feed->slots[slot];
   *bytes = feed->bytes[slot];
@@ -221,7 +221,7 @@ qp_status qp_feed_consume(qp_feed* feed, void* device_buf0, void* device_buf1, s
     // back finished slots (waiting for the oldest copy if need be) before blocking on the producer.
     for (;;) {
       st = qp_feed_next(feed, 0, &slot, &bytes, &g);
-      if (st != (qp_status)QP_FEED_TIMEOUT) break;
+      if (st != QP_FEED_TIMEOUT) break;
       if (!copying.empty()) {
         st = recycle(true);
         if (st != QP_OK) break;
@@ -233,7 +233,7 @@ qp_status qp_feed_consume(qp_feed* feed, void* device_buf0, void* device_buf1, s
     const double w = ms_since(tw);
     waited += w;
     if (n_done == 0) first_wait = w;
-    if (st == (qp_status)QP_FEED_END) break;
+    if (st == QP_FEED_END) break;
     if (st != QP_OK) {
       result = st;
       break;

@@ -474,12 +474,14 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
 }
 
 const char* qp_status_string(qp_status s) {
-  switch (s) {
+  switch ((int)s) {  // callers across the C ABI may pass any int
     case QP_OK: return "ok";
     case QP_ERR_INVALID_ARG: return "invalid argument";
     case QP_ERR_UNSUPPORTED: return "unsupported dtype, head_dim or size";
     case QP_ERR_CAPACITY: return "cache capacity or workspace too small";
     case QP_ERR_HIP: return "HIP launch failed";
+    case QP_FEED_END: return "feed closed and drained";
+    case QP_FEED_TIMEOUT: return "nothing published within the time-out";
   }
   return "unknown status";
 }
