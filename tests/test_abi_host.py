@@ -61,6 +61,12 @@ def test_layer_workspace_and_shape_errors():
     split = 32 << 20                                                             # scratch of split contractions
     assert n >= acts + split + B.workspace_bytes(L, 2048, 64)
     assert n < acts + split + B.workspace_bytes(L, 2048, 64) + (4 << 20)
+    # Appendix D.1 prices a group's activations at Q, K, V (query head count) + one score block per head for the
+    # attention block and (2 d_model + 4 d_ff) per token for the MLP block; what the layer call keeps is below that
+    # (one d_ff-wide tensor instead of four, K and V at the KV head count), and 1/G of the whole video's
+    model_group = O.attn_activation_bytes(1, 2048, 28, 128, 1024, 1024) + O.mlp_activation_bytes(1, 2048, 3584, 18944)
+    model_video = O.attn_activation_bytes(1, 32768, 28, 128, 1024, 1024) + O.mlp_activation_bytes(1, 32768, 3584, 18944)
+    assert acts < model_group < model_video / 10
     assert B.layer_workspace_bytes(L, S, 0, 0) == 0
     assert B.layer_workspace_bytes(B.make_layout(28, 4, 64, "bf16"), S, 128, 0) == 0       # head_dim 128 only
     assert B.layer_workspace_bytes(L, B.make_layer_shape(3584, 18944, mrope_section=(16, 24, 20)), 128, 0) == 0
