@@ -50,7 +50,7 @@ def test_producer_blocks_while_the_ring_is_full_and_resumes_on_release():
 
         t = threading.Thread(target=producer)
         t.start()
-        time.sleep(0.2)
+        time.sleep(0.3)
         assert produced == [0, 1]                              # the third write waits for a free slot
         got = []
         while True:
@@ -102,8 +102,9 @@ def test_stub_producer_paces_the_groups():
             assert _read(p, n) == bytes(range(8 * g, 8 * g + 8))
             feed.release(g)
         ms = feed.stub_join()
-        assert len(due) == 3 and 0.09 < due[0] < 0.14 and 0.14 < due[1] < 0.19 and 0.19 < due[2] < 0.25
-        assert 195 < ms < 260
+        # never early; the upper bounds leave room for a busy host
+        assert len(due) == 3 and 0.099 < due[0] < 0.4 and 0.149 < due[1] < 0.45 and 0.199 < due[2] < 0.5
+        assert 199 < ms < 500
     finally:
         feed.destroy()
 
