@@ -417,3 +417,52 @@ def test_layer_text_chunk_and_decode_steps_after_video():
         assert cache.len == n_tok
         np.testing.assert_array_equal(cache.pos.cpu().numpy()[:, :n_tok], cp)
         assert_layer_close(to_f64(cache.k)[:, :n_tok], ck, f"layer {l} cached K", layers=l + 1)
+
+
+def test_layer_stack_replays_from_a_hip_graph():
+    """A caller may capture the layer calls (side-stream fork/join, split projections and their second launches
+    included) into a HIP graph: every replay, with eager work and synchronisations in between, reproduces the eager
+    run bit for bit. Two layers, a video group, a short text chunk and a single token."""
+    dims = SMALL
+    layers_t = [W.make_decoder_layer(dims, l, seed=7) for l in range(2)]
+    steps = [(0, 300), (300, 9), (309, 1)]
+    x = W.make_hidden(20, 16, dims.d_model, seed=3)[:310].contiguous().to(DEV)
+    pos = torch.cat([W.video_positions(20, 15)[:, :300], W.text_positions(10, 50)], dim=1).contiguous().to(DEV)
+    layout = B.make_layout(dims.n_q_heads, dims.n_kv_heads, 128, "bf16")
+    shape = B.make_layer_shape(dims.d_model, dims.d_ff, dims.rms_eps, dims.rope_theta, dims.mrope_section)
+    weights = [B.LayerWeights(**{k: v.to(DEV) for k, v in w_.items()}) for w_ in layers_t]
+    ws = B.make_layer_workspace(layout, shape, 300, 0)
+    keeps = [B.keep_count(300, 0.5), 9, 1]
+    caches = [B.Cache(layout, sum(keeps)) for _ in weights]
+    out = torch.zeros_like(x)
+    tmp = torch.empty(300, dims.d_model, dtype=torch.bfloat16, device=DEV)
+
+    def run():
+        for c in caches:
+            c.reset()
+        for (base, n), keep in zip(steps, keeps):
+            B.layer_group(layout, shape, weights[0], x[base:base + n], pos, base, base, None, "key_norm_small", keep,
+                          caches[0], tmp[:n], None, ws)
+            B.layer_group(layout, shape, weights[1], tmp[:n], pos, base, base, None, "key_norm_small", keep,
+                          caches[1], out[base:base + n], None, ws)
+
+    run()
+    torch.cuda.synchronize()
+    want = [out.clone()] + [t.clone() for c in caches for t in (c.k, c.v, c.pos)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for replay in range(3):
+        out.zero_()
+        for c in caches:
+            c.k.zero_(), c.v.zero_(), c.pos.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [out] + [t for c in caches for t in (c.k, c.v, c.pos)]
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), f"replay {replay}"
+        run()                                                    # eager work between the replays
+        torch.cuda.synchronize()
+        for a, b in zip([out] + [t for c in caches for t in (c.k, c.v, c.pos)], want):
+            assert torch.equal(a, b), f"eager after replay {replay}"
