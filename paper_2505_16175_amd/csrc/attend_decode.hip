@@ -6,7 +6,8 @@
 // matrix pipe: no workgroup-shared tiles and no barrier in the loop. Keys are cut into blocks of 32; a workgroup
 // takes a run of blocks and deals them to its 4 wavefronts, each of which works alone on its own 32 KB of LDS:
 //   K, V block  global -> LDS with direct loads (XOR-swizzled 16-byte chunks, as in the large kernel), two buffers
-//               each: the next block is requested before the current one is computed. All loads of the loop are
+//               each, refilled half by half: K two blocks ahead as soon as the QK product has its fragments, V two
+//               blocks ahead after the PV product. All loads of the loop are
 //               issued from inline assembly and waited for by count (the compiler tracks none of them, so it
 //               neither drains the prefetch before an LDS read nor touches a register whose load is in flight);
 //   S^T = K . Q^T with v_mfma_f32_32x32x16_bf16 (the <= 32 rows are the columns), online softmax per wavefront as
@@ -45,19 +46,15 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
-// QK^T, online softmax and PV of one 32-key block for this wavefront's rows (a lane holds row lane % 32 and half of
-// the block's keys). is_group: the block is the group's own keys (causal); n_valid: keys that exist in the block.
-__device__ __forceinline__ void decode_block(const unsigned char* kt, const int (&k_addr)[8], const bf16x8 (&qf)[8],
-                                             bool is_group, int n_valid, int t_lane, int g, float c2, float lazy,
-                                             bool has_next, const int (&v_addr)[4], float& m_run, float& l_run,
-                                             f32x16 (&o)[4]) {
-  // in flight, oldest first: K(b) x8, V(b) x8, then K(next) x8, V(next) x8 if requested
-  if (has_next) wait_vmcnt<24>();
-  else wait_vmcnt<8>();
+// QK^T and online softmax of one 32-key block for this wavefront's rows (a lane holds row lane % 32 and half of the
+// block's keys); leaves P^T (bf16) in pf. is_group: the block is the group's own keys (causal); n_valid: keys that
+// exist in the block. The caller has waited for the block's K.
+__device__ __forceinline__ void decode_qk_softmax(const unsigned char* kt, const int (&k_addr)[8], const bf16x8 (&qf)[8],
+                                                  bool is_group, int n_valid, int t_lane, int g, float c2, float lazy,
+                                                  float& m_run, float& l_run, f32x16 (&o)[4], bf16x8 (&pf)[2]) {
   u32x4 kf[8];
 #pragma unroll
   for (int s = 0; s < 8; ++s) kf[s] = *(const u32x4*)(kt + k_addr[s]);
-  const unsigned char* vt = kt + DC_TILE;
   f32x16 st;
 #pragma unroll
   for (int r = 0; r < 16; ++r) st[r] = 0.f;
@@ -80,7 +77,6 @@ __device__ __forceinline__ void decode_block(const unsigned char* kt, const int 
   ones[0] = (__bf16)1.0f;
   ones[1] = (__bf16)1.0f;
   float psum = 0.f;
-  bf16x8 pf[2];
 #pragma unroll
   for (int r = 0; r < 16; r += 2) {
     bf16x2 pr;
@@ -100,9 +96,11 @@ __device__ __forceinline__ void decode_block(const unsigned char* kt, const int 
     m_run = m_new;
   }
   l_run += psum;
-  // this block's V has landed in LDS (the next block's 16 requests, issued after it, may still be in flight)
-  if (has_next) wait_vmcnt<16>();
-  else wait_vmcnt<0>();
+}
+
+// O^T += V^T . P^T for the block whose V sits at vt. The caller has waited for the block's V.
+__device__ __forceinline__ void decode_pv(const unsigned char* vt, const int (&v_addr)[4], const bf16x8 (&pf)[2],
+                                          f32x16 (&o)[4]) {
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -165,41 +163,56 @@ __global__ __launch_bounds__(DC_NW * 64) void attend_decode_kernel(AttendArgs a)
   const float c2 = a.scale_log2;
   const float lazy = DC_RESCALE_LOG2 / c2;
 
-  // request block b_ into buffer buf_: 8 direct loads of K, then 8 of V (each moves 4 keys x 256 bytes)
-#define QP_DC_REQUEST(b_, buf_)                                                                          \
+  // request the K (V) half of block b_ into buffer buf_: 8 direct loads, each moving 4 keys x 256 bytes
+#define QP_DC_REQUEST(b_, buf_, is_v_)                                                                   \
   {                                                                                                      \
     const bool grp_ = (b_) == n_cb;                                                                      \
     const int key0_ = grp_ ? 0 : (b_)*DC_BK;                                                             \
     const int last_ = grp_ ? a.n_g - 1 : a.c - 1; /* keys past the end are clamped: masked below */      \
     const unsigned stride_ = grp_ ? gstride_b : (unsigned)(DC_D * 2);                                    \
-    const unsigned char* ksrc_ = grp_ ? gk : ck;                                                         \
-    const unsigned char* vsrc_ = grp_ ? gv : cv;                                                         \
-    unsigned char* kdst_ = vbuf + (buf_)*DC_BUF;                                                         \
+    const unsigned char* src_ = (is_v_) ? (grp_ ? gv : cv) : (grp_ ? gk : ck);                           \
+    unsigned char* dst_ = vbuf + (buf_)*DC_BUF + ((is_v_) ? DC_TILE : 0);                                \
     _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                      \
       const int kl_ = 4 * i + st_sub;                                                                    \
       const unsigned row_ = (unsigned)min(key0_ + kl_, last_) * stride_;                                 \
-      lds_dma16(ksrc_, row_ + (unsigned)((st_pos ^ (kl_ & 15)) << 4), kdst_ + i * 1024);                 \
-    }                                                                                                    \
-    _Pragma("unroll") for (int i = 0; i < 8; ++i) {                                                      \
-      const int kl_ = 4 * i + st_sub;                                                                    \
-      const unsigned row_ = (unsigned)min(key0_ + kl_, last_) * stride_;                                 \
-      lds_dma16(vsrc_, row_ + (unsigned)((st_pos ^ ((kl_ & 7) << 1)) << 4), kdst_ + DC_TILE + i * 1024); \
+      const int swz_ = (is_v_) ? ((kl_ & 7) << 1) : (kl_ & 15);                                          \
+      lds_dma16(src_, row_ + (unsigned)((st_pos ^ swz_) << 4), dst_ + i * 1024);                         \
     }                                                                                                    \
   }
 
   // The Q fragments (ordinary loads) must have arrived before the first request: from here on only untracked
   // operations are in flight, and the counts in the waits are exact.
   wait_vmcnt<0>();
+  // Each half of a buffer is refilled as soon as its block has been consumed: K(i+2) right after the QK product of
+  // block i, V(i+2) after its PV product, so that up to three halves beyond the current block are in flight.
+  // Requests in issue order: K(i) V(i) K(i+1) V(i+1) | K(i+2) after QK(i) | V(i+2) after PV(i) ...
   int b = chunk * a.split_tiles + wave;
   int cur = 0;
-  if (b < b_end) QP_DC_REQUEST(b, 0)
+  if (b < b_end) {
+    QP_DC_REQUEST(b, 0, false)
+    QP_DC_REQUEST(b, 0, true)
+    if (b + DC_NW < b_end) {
+      QP_DC_REQUEST(b + DC_NW, 1, false)
+      QP_DC_REQUEST(b + DC_NW, 1, true)
+    }
+  }
   while (b < b_end) {
-    const int b_next = b + DC_NW;
-    const bool has_next = b_next < b_end;
-    if (has_next) QP_DC_REQUEST(b_next, cur ^ 1)
-    decode_block(vbuf + cur * DC_BUF, k_addr, qf, b == n_cb, b == n_cb ? a.n_g : min(DC_BK, a.c - b * DC_BK), t_lane, g,
-                 c2, lazy, has_next, v_addr, m_run, l_run, o);
-    b = b_next;
+    const bool has1 = b + DC_NW < b_end, has2 = b + 2 * DC_NW < b_end;
+    unsigned char* buf = vbuf + cur * DC_BUF;
+    // K(i) has landed: V(i) and block i+1 (16 requests) may still be in flight
+    if (has1) wait_vmcnt<24>();
+    else wait_vmcnt<8>();
+    bf16x8 pf[2];
+    decode_qk_softmax(buf, k_addr, qf, b == n_cb, b == n_cb ? a.n_g : min(DC_BK, a.c - b * DC_BK), t_lane, g, c2, lazy,
+                      m_run, l_run, o, pf);
+    if (has2) QP_DC_REQUEST(b + 2 * DC_NW, cur, false)  // the K fragments of block i are in registers
+    // V(i) has landed: block i+1 and K(i+2) may still be in flight
+    if (has2) wait_vmcnt<24>();
+    else if (has1) wait_vmcnt<16>();
+    else wait_vmcnt<0>();
+    decode_pv(buf + DC_TILE, v_addr, pf, o);
+    if (has2) QP_DC_REQUEST(b + 2 * DC_NW, cur, true)
+    b += DC_NW;
     cur ^= 1;
   }
 #undef QP_DC_REQUEST
