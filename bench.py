@@ -332,7 +332,7 @@ def run_stack(torch, B, w, rule, n_layers, steps, warmup, feed_ms=None):
             q_wins[l] = torch.empty(n_win, hq, 128, dtype=torch.bfloat16, device="cuda")
             B.layer_window_queries(layout, shape, weights[l], W.make_hidden(1, n_win, dm, device="cuda", seed=900 + l),
                                    pw, q_wins[l], ws)
-    bounds = w.group_bounds()
+    bounds = B.group_bounds(w.n_frames, w.tokens_per_frame, w.group_frames)
     bufs = [torch.empty(w.group_tokens, dm, dtype=torch.bfloat16, device="cuda") for _ in range(2)]
     out = torch.empty_like(x)
 
@@ -421,6 +421,7 @@ def cpu_baseline(w, q, k, v, qw, rule):
     """The oracle on the host: all groups scored and selected, a sample of groups attended in full."""
     import numpy as np  # noqa: F401
     from oracle import qp_oracle as O
+    from paper_2505_16175_amd import binding as B
     from paper_2505_16175_amd.workload import to_f64
     try:
         from threadpoolctl import threadpool_info
@@ -432,7 +433,7 @@ def cpu_baseline(w, q, k, v, qw, rule):
     t0 = time.perf_counter()
     sel = O.select_all_groups(k64, v64, qw64, w.n_frames, w.tokens_per_frame, w.group_frames, w.retention, rule)
     t_sel = time.perf_counter() - t0
-    bounds = w.group_bounds()
+    bounds = B.group_bounds(w.n_frames, w.tokens_per_frame, w.group_frames)
     g = len(bounds)
     # attention cost is linear in the group index; this sample's mean index equals the full run's
     sample = sorted({0, g - 1} | ({(g - 1) // 3, g - 1 - (g - 1) // 3} if g >= 4 else set())) if g > 1 else [0]
@@ -552,7 +553,7 @@ def main():
     resident_cache_bytes = sum(c.nbytes() for c in caches)
 
     # ---- instrumented replay of the same steps: HIP events around every launch group of the path
-    bounds = w.group_bounds()
+    bounds = B.group_bounds(w.n_frames, w.tokens_per_frame, w.group_frames)
     score_bufs = {n: torch.empty(w.n_kv_heads, n, dtype=torch.float32, device="cuda") for _, n in set(bounds)}
     ev = []
     for _ in range(args.steps):

@@ -109,6 +109,13 @@ int64_t qp_keep_count(int64_t n_group_tokens, double retention);
  * (groups of group_frames frames, the last one possibly shorter). -1 on bad arguments. */
 int64_t qp_cache_capacity(int32_t n_frames, int32_t tokens_per_frame, int32_t group_frames, double retention);
 
+/* The frame-aligned groups of a video (Sec. 3.2, "Group-Based Prefill": groups of about N_g tokens; Tables 1-2 give
+ * the size in frames): group i covers tokens [first_token[i], first_token[i] + n_tokens[i]); every group has
+ * group_frames frames except possibly the last. Returns the number of groups G; writes the first
+ * min(G, max_groups) entries of each HOST array that is not NULL. -1 on bad arguments. */
+int32_t qp_group_bounds(int32_t n_frames, int32_t tokens_per_frame, int32_t group_frames, int32_t* first_token,
+                        int32_t* n_tokens, int32_t max_groups);
+
 /* Bytes of workspace that every entry point accepts for groups of at most max_group_tokens
  * tokens and a query window of n_window rows (includes 2 x 32 MiB of key-split scratch for the
  * attention launches of qp_prefill_video). 0 on bad arguments. */
@@ -182,7 +189,10 @@ qp_status qp_topk_compact(const qp_layout* layout, const float* scores, const vo
  * other group's attention. They are forked from hip_stream at entry and joined back into it before
  * the call returns: work the caller enqueues on hip_stream afterwards is ordered after all of this
  * call's work. The call only enqueues (it never waits for the GPU); calls from several host threads
- * are serialised while they enqueue, because they share those streams. */
+ * are serialised while they enqueue, because they share those streams.
+ * Failure after the first launch (QP_ERR_HIP from a launch or a stream call): nothing further is enqueued, the
+ * library's streams are still joined back into hip_stream, the groups already enqueued run to completion, and
+ * cache->len is restored to its value at entry (rows beyond it, and `out`, then hold unspecified data). */
 qp_status qp_prefill_video(const qp_layout* layout, int32_t n_frames, int32_t tokens_per_frame,
                            int32_t group_frames, double retention, qp_score_rule rule, const void* q,
                            const void* k, const void* v, const void* q_win, int32_t n_window, qp_cache* cache,
@@ -211,6 +221,11 @@ qp_status qp_attend_plan(const qp_layout* layout, int32_t n_group_tokens, int32_
 /* Choose the attention kernel for later qp_group_attend / qp_prefill_video calls of this
  * process (tests use it to cover both). Returns INVALID_ARG for an unknown value. */
 qp_status qp_select_attend_kernel(int32_t which);
+
+/* Test seam for the error paths: the n_checks-th launch check from now on (every entry point of this header checks
+ * once after it has enqueued its launches; qp_prefill_video checks three times per group) reports QP_ERR_HIP with
+ * hipErrorLaunchFailure although the GPU work was enqueued and runs normally. 0 switches it off. Process-wide. */
+qp_status qp_debug_fail_after(int32_t n_checks);
 
 const char* qp_status_string(qp_status s); /* static string, never NULL */
 int qp_last_hip_error(void);               /* hipError_t of the last failed launch on this thread, 0 if none */

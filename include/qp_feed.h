@@ -42,11 +42,18 @@ enum {
 
 /* n_slots >= 2 host slots of slot_bytes each. INVALID_ARG on bad sizes, QP_ERR_HIP if an allocation fails. */
 qp_status qp_feed_create(int32_t n_slots, size_t slot_bytes, int32_t flags, qp_feed** out);
-void qp_feed_destroy(qp_feed* feed); /* the producer must have finished; NULL is ignored */
+/* Stops the feed (as qp_feed_stop), joins the stand-in producer's thread if one was started, releases everything.
+ * A producer thread of the caller's own must have returned from its last call before this. NULL is ignored. */
+void qp_feed_destroy(qp_feed* feed);
+/* The consumer gives up: from now on qp_feed_begin_write and qp_feed_publish return QP_FEED_END instead of blocking
+ * or publishing, and a producer blocked on a full ring wakes up with that status. qp_feed_consume calls it when it
+ * ends with an error (group function failed, group larger than the device buffer, HIP error). Never undone. */
+qp_status qp_feed_stop(qp_feed* feed);
 
 /* ---- producer side ------------------------------------------------------------------------------------- */
 /* The next slot to fill (host pointer, slot_bytes long). Blocks while all slots are in use (published but not yet
- * copied to the device). INVALID_ARG after qp_feed_close or if the previous slot was not published. */
+ * copied to the device) and the feed has not been stopped. INVALID_ARG after qp_feed_close or if the previous slot
+ * was not published; QP_FEED_END once the feed is stopped (nobody will take the group). */
 qp_status qp_feed_begin_write(qp_feed* feed, void** host_slot);
 /* The slot obtained last holds `bytes` bytes of the next group (groups are numbered in publication order). */
 qp_status qp_feed_publish(qp_feed* feed, size_t bytes);

@@ -81,6 +81,8 @@ _SP, _WP, _f32 = ctypes.POINTER(qp_layer_shape), ctypes.POINTER(qp_layer_weights
 SIGNATURES = {
     "qp_keep_count": (_i64, [_i64, _f64]),
     "qp_cache_capacity": (_i64, [_i32, _i32, _i32, _f64]),
+    "qp_debug_fail_after": (_i32, [_i32]),
+    "qp_group_bounds": (_i32, [_i32, _i32, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32), _i32]),
     "qp_workspace_bytes": (_sz, [_LP, _i32, _i32]),
     "qp_group_attend": (_i32, [_LP, _vp, _vp, _vp, _i32, _CP, _vp, _vp, _vp, _sz, _vp]),
     "qp_score_kv": (_i32, [_LP, _i32, _vp, _vp, _i32, _vp, _i32, _vp, _vp, _sz, _vp]),
@@ -106,6 +108,7 @@ SIGNATURES = {
     # include/qp_feed.h
     "qp_feed_create": (_i32, [_i32, _sz, _i32, ctypes.POINTER(_vp)]),
     "qp_feed_destroy": (None, [_vp]),
+    "qp_feed_stop": (_i32, [_vp]),
     "qp_feed_begin_write": (_i32, [_vp, ctypes.POINTER(_vp)]),
     "qp_feed_publish": (_i32, [_vp, _sz]),
     "qp_feed_close": (_i32, [_vp]),
@@ -190,6 +193,16 @@ def version() -> str:
 
 def keep_count(n_group_tokens, retention) -> int:
     return lib().qp_keep_count(n_group_tokens, retention)
+
+
+def group_bounds(n_frames, tokens_per_frame, group_frames):
+    """[(first_token, n_tokens)] of every frame-aligned group, from qp_group_bounds."""
+    n = lib().qp_group_bounds(n_frames, tokens_per_frame, group_frames, None, None, 0)
+    if n < 0:
+        raise QPError(QP_ERR_INVALID_ARG, "qp_group_bounds")
+    first, count = (ctypes.c_int32 * n)(), (ctypes.c_int32 * n)()
+    lib().qp_group_bounds(n_frames, tokens_per_frame, group_frames, first, count, n)
+    return [(int(f), int(c)) for f, c in zip(first, count)]
 
 
 def cache_capacity(n_frames, tokens_per_frame, group_frames, retention) -> int:
@@ -371,6 +384,9 @@ class Feed:
 
     def close(self):
         _check(lib().qp_feed_close(self.h), "qp_feed_close")
+
+    def stop(self):
+        _check(lib().qp_feed_stop(self.h), "qp_feed_stop")
 
     def next(self, timeout_ms=-1):
         """(status, host_pointer, bytes, group); status is QP_OK, QP_FEED_END or QP_FEED_TIMEOUT."""

@@ -28,6 +28,7 @@ struct qp_feed {
   long written = 0;  // groups published; group g lives in slot g % n_slots
   long taken = 0;    // groups handed to the consumer
   bool writing = false, closed = false;
+  bool stopped = false;  // the consumer has given up (error exit of qp_feed_consume, qp_feed_stop, destroy): producers must not block
   // device side (absent with QP_FEED_PAGEABLE on a machine without a GPU)
   hipStream_t copy = nullptr;
   hipEvent_t copied[2] = {nullptr, nullptr}, computed[2] = {nullptr, nullptr};
@@ -114,8 +115,18 @@ qp_status qp_feed_create(int32_t n_slots, size_t slot_bytes, int32_t flags, qp_f
   return QP_OK;
 }
 
+qp_status qp_feed_stop(qp_feed* feed) {
+  if (feed == nullptr) return QP_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lk(feed->mu);
+  feed->stopped = true;
+  feed->cv.notify_all();
+  return QP_OK;
+}
+
 void qp_feed_destroy(qp_feed* feed) {
   if (feed == nullptr) return;
+  // a producer blocked on a full ring (its consumer stopped early) must wake up before its thread is joined
+  (void)qp_feed_stop(feed);
   if (feed->stub_started && feed->stub.joinable()) feed->stub.join();
   free_feed(feed);
 }
@@ -125,7 +136,8 @@ qp_status qp_feed_begin_write(qp_feed* feed, void** host_slot) {
   std::unique_lock<std::mutex> lk(feed->mu);
   if (feed->closed || feed->writing) return QP_ERR_INVALID_ARG;
   const int slot = (int)(feed->written % feed->n_slots);
-  feed->cv.wait(lk, [&] { return !feed->busy[slot]; });
+  feed->cv.wait(lk, [&] { return !feed->busy[slot] || feed->stopped; });
+  if (feed->stopped) return QP_FEED_END;  // nobody will take this group
   feed->writing = true;
   *host_slot = feed->slots[slot];
   return QP_OK;
@@ -135,6 +147,10 @@ qp_status qp_feed_publish(qp_feed* feed, size_t bytes) {
   if (feed == nullptr) return QP_ERR_INVALID_ARG;
   std::lock_guard<std::mutex> lk(feed->mu);
   if (!feed->writing || feed->closed) return QP_ERR_INVALID_ARG;
+  if (feed->stopped) {
+    feed->writing = false;
+    return QP_FEED_END;
+  }
   if (bytes > feed->slot_bytes) return QP_ERR_CAPACITY;
   const int slot = (int)(feed->written % feed->n_slots);
   feed->bytes[slot] = bytes;
@@ -281,6 +297,8 @@ qp_status qp_feed_consume(qp_feed* feed, void* device_buf0, void* device_buf1, s
     (void)qp_feed_release(feed, copying.front());
     copying.pop_front();
   }
+  // an early exit leaves groups nobody will take: a producer waiting for a free slot must not wait for ever
+  if (result != QP_OK) (void)qp_feed_stop(feed);
   if (stats_or_null != nullptr) {
     stats_or_null->groups = n_done;
     stats_or_null->total_ms = ms_since(t0);

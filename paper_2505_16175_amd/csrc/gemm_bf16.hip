@@ -23,6 +23,8 @@
 //   * SWIGLU: block 0 holds gate columns [n0/2 + 32 wn, +32), block 1 the up columns of the same outputs.
 // Workgroup ids are dealt round-robin over the 8 XCDs; the workgroups an XCD runs side by side cover a block of
 // token tiles x weight tiles, which bounds what its L2 has to fetch per k-step.
+#include <atomic>
+
 #include "qp_internal.h"
 
 namespace qp {
@@ -58,7 +60,10 @@ struct Tile {
   __device__ static constexpr int swizzle(int r) { return (r / RPL) & (CPR - 1); }
 };
 
-// 64 lanes x 16 bytes global -> LDS at the wave-uniform LDS byte address lds_addr (lane L lands at lds_addr + 16 L)
+// 64 lanes x 16 bytes global -> LDS at the wave-uniform LDS byte address lds_addr (lane L lands at lds_addr + 16 L);
+// m0 is clobbered on purpose (see lds_dma16)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void gm_dma16(const unsigned char* base, unsigned byte_off, unsigned lds_addr) {
   asm volatile(
       "s_mov_b32 m0, %2\n\t"
@@ -66,8 +71,9 @@ __device__ __forceinline__ void gm_dma16(const unsigned char* base, unsigned byt
       "global_load_lds_dwordx4 %0, %1"
       :
       : "v"(byte_off), "s"(base), "s"(lds_addr)
-      : "memory");
+      : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 template <int N>
 __device__ __forceinline__ void gm_wait_vmcnt() {
@@ -460,13 +466,14 @@ bool gemm_supported(const GemmArgs& a, int mode) {
   return false;
 }
 
-static int g_forced_tile_rows = 0;  // 0: choose per launch; 128 / 256: tests cover both tilings
-void gemm_force_tile_rows(int rows) { g_forced_tile_rows = rows; }
+static std::atomic<int> g_forced_tile_rows{0};  // 0: choose per launch; 128 / 256: tests cover both tilings
+void gemm_force_tile_rows(int rows) { g_forced_tile_rows.store(rows, std::memory_order_relaxed); }
 
 // 256-row tiles unless 128-row tiles finish sooner: a launch lasts ceil(tiles / CUs) rounds of one tile each, and a
 // 128-row tile costs about 0.6 of a 256-row one (half the products, less reuse of the weight fragments).
 int gemm_tile_rows(const GemmArgs& a) {
-  if (g_forced_tile_rows != 0) return g_forced_tile_rows;
+  const int forced = g_forced_tile_rows.load(std::memory_order_relaxed);
+  if (forced != 0) return forced;
   const int cus = device_cu_count();
   const long tiles_n = (a.n + GM_BN - 1) / GM_BN;
   const long t256 = (long)((a.m + 255) / 256) * tiles_n, t128 = (long)((a.m + 127) / 128) * tiles_n;

@@ -4,6 +4,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 
 #include "qp_internal.h"
@@ -11,7 +12,7 @@
 namespace {
 
 thread_local int g_last_hip_error = 0;
-int g_attend_kernel = QP_ATTEND_AUTO;
+std::atomic<int> g_attend_kernel{QP_ATTEND_AUTO};  // read once per call; set by qp_select_attend_kernel from any thread
 
 inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 inline size_t round256(size_t x) { return (x + 255) / 256 * 256; }
@@ -48,8 +49,15 @@ float scale_log2_of(const qp_layout* L) {
   return scale * 1.4426950408889634f;
 }
 
+// Fault injection for the tests of the error paths (qp_debug_fail_after): the n-th status check from now reports a
+// launch failure although nothing failed on the GPU. 0 = off.
+std::atomic<int> g_fail_countdown{0};
+
 qp_status finish(hipError_t launch_err) {
   hipError_t e = launch_err != hipSuccess ? launch_err : hipGetLastError();
+  if (e == hipSuccess && g_fail_countdown.load(std::memory_order_relaxed) > 0 &&
+      g_fail_countdown.fetch_sub(1, std::memory_order_relaxed) == 1)
+    e = hipErrorLaunchFailure;
   if (e != hipSuccess) {
     g_last_hip_error = (int)e;
     return QP_ERR_HIP;
@@ -184,6 +192,22 @@ int64_t qp_cache_capacity(int32_t n_frames, int32_t tokens_per_frame, int32_t gr
   return total;
 }
 
+int32_t qp_group_bounds(int32_t n_frames, int32_t tokens_per_frame, int32_t group_frames, int32_t* first_token,
+                        int32_t* n_tokens, int32_t max_groups) {
+  if (n_frames <= 0 || tokens_per_frame <= 0 || group_frames <= 0 || max_groups < 0) return -1;
+  if ((int64_t)n_frames * tokens_per_frame > INT32_MAX) return -1;
+  int32_t gi = 0;
+  for (int32_t f = 0; f < n_frames; ++gi) {
+    const int32_t g = (n_frames - f) < group_frames ? (n_frames - f) : group_frames;
+    if (gi < max_groups) {
+      if (first_token != nullptr) first_token[gi] = f * tokens_per_frame;
+      if (n_tokens != nullptr) n_tokens[gi] = g * tokens_per_frame;
+    }
+    f += g;
+  }
+  return gi;
+}
+
 size_t qp_workspace_bytes(const qp_layout* L, int32_t max_group_tokens, int32_t n_window) {
   if (check_layout(L) != QP_OK || check_group(max_group_tokens) != QP_OK || n_window < 0) return 0;
   size_t b = scores_bytes(L, max_group_tokens);
@@ -209,10 +233,11 @@ qp_status qp_attend_plan(const qp_layout* L, int32_t n_g, int32_t cache_len, siz
   a.d = L->head_dim;
   a.c = a.cap = cache_len;
   const bool mfma_ok = qp::attend_mfma_supported(a, L->dtype);
-  if (g_attend_kernel == QP_ATTEND_MFMA && !mfma_ok) return QP_ERR_UNSUPPORTED;
+  const int which = g_attend_kernel.load(std::memory_order_relaxed);
+  if (which == QP_ATTEND_MFMA && !mfma_ok) return QP_ERR_UNSUPPORTED;
   memset(out, 0, sizeof(*out));
-  if (mfma_ok && g_attend_kernel != QP_ATTEND_SCALAR) {
-    const bool decode = g_attend_kernel == QP_ATTEND_AUTO && qp::attend_decode_applies(a, L->dtype);
+  if (mfma_ok && which != QP_ATTEND_SCALAR) {
+    const bool decode = which == QP_ATTEND_AUTO && qp::attend_decode_applies(a, L->dtype);
     const qp::AttendPlan p = decode ? qp::plan_attend_decode(a, workspace_bytes) : qp::plan_attend_mfma(a, workspace_bytes);
     out->kernel = decode ? QP_ATTEND_MFMA_DECODE : QP_ATTEND_MFMA;
     out->workgroups = p.workgroups;
@@ -229,7 +254,7 @@ qp_status qp_attend_plan(const qp_layout* L, int32_t n_g, int32_t cache_len, siz
 
 qp_status qp_select_attend_kernel(int32_t which) {
   if (which != QP_ATTEND_AUTO && which != QP_ATTEND_SCALAR && which != QP_ATTEND_MFMA) return QP_ERR_INVALID_ARG;
-  g_attend_kernel = which;
+  g_attend_kernel.store(which, std::memory_order_relaxed);
   return QP_OK;
 }
 
@@ -263,11 +288,12 @@ qp_status qp_group_attend(const qp_layout* L, const void* q_g, const void* k_g, 
 
   hipStream_t s = (hipStream_t)hip_stream;
   const bool mfma_ok = qp::attend_mfma_supported(a, L->dtype);
-  if (g_attend_kernel == QP_ATTEND_MFMA && !mfma_ok) return QP_ERR_UNSUPPORTED;
+  const int which = g_attend_kernel.load(std::memory_order_relaxed);
+  if (which == QP_ATTEND_MFMA && !mfma_ok) return QP_ERR_UNSUPPORTED;
   const size_t ws_bytes = workspace ? workspace_bytes : 0;
-  if (mfma_ok && g_attend_kernel == QP_ATTEND_AUTO && qp::attend_decode_applies(a, L->dtype))
+  if (mfma_ok && which == QP_ATTEND_AUTO && qp::attend_decode_applies(a, L->dtype))
     qp::launch_attend_decode(a, workspace, ws_bytes, s);
-  else if (mfma_ok && g_attend_kernel != QP_ATTEND_SCALAR) qp::launch_attend_mfma(a, workspace, ws_bytes, s);
+  else if (mfma_ok && which != QP_ATTEND_SCALAR) qp::launch_attend_mfma(a, workspace, ws_bytes, s);
   else qp::launch_attend_scalar(a, L->dtype, s);
   return finish(hipSuccess);
 }
@@ -401,7 +427,7 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
     return QP_ERR_CAPACITY;
   if ((int64_t)cache->len + qp_cache_capacity(n_frames, tokens_per_frame, group_frames, retention) > cache->capacity)
     return QP_ERR_CAPACITY;
-  if (g_attend_kernel == QP_ATTEND_MFMA) {
+  if (g_attend_kernel.load(std::memory_order_relaxed) == QP_ATTEND_MFMA) {
     qp::AttendArgs probe;
     memset(&probe, 0, sizeof(probe));
     probe.h_q = L->n_q_heads;
@@ -429,15 +455,17 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
   SideStreams none;
   SideStreams& g_side = overlap ? *side : none;
   void* score_stream = overlap ? (void*)g_side.score : hip_stream;
+  // A failed stream call or launch stops the loop (nothing further is enqueued) but never skips the join below.
+  const int32_t len_at_entry = cache->len;
 #define QP_HIP_OK(call_) \
-  if ((call_) != hipSuccess) return finish(hipGetLastError())
+  if (st == QP_OK && (call_) != hipSuccess) st = finish(hipGetLastError())
   if (overlap) {
     QP_HIP_OK(hipEventRecord(g_side.fork, main_stream));
     QP_HIP_OK(hipStreamWaitEvent(g_side.score, g_side.fork, 0));
     for (int i = 1; i < g_side.n_att; ++i) QP_HIP_OK(hipStreamWaitEvent(g_side.attend[i], g_side.fork, 0));
   }
   int gi = 0;
-  for (int32_t f = 0; f < n_frames; f += group_frames, ++gi) {
+  for (int32_t f = 0; f < n_frames && st == QP_OK; f += group_frames, ++gi) {
     const int32_t g = (n_frames - f) < group_frames ? (n_frames - f) : group_frames;
     const int32_t base = f * tokens_per_frame, n_g = g * tokens_per_frame;
     const char* qg = (const char*)q + (size_t)base * q_tok;
@@ -448,6 +476,7 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
     const int ai = overlap ? gi % g_side.n_att : 0;
     hipStream_t att_stream = ai ? g_side.attend[ai] : main_stream;
     if (overlap && gi > 0) QP_HIP_OK(hipStreamWaitEvent(att_stream, g_side.compacted[(gi - 1) & 1], 0));
+    if (st != QP_OK) break;
     st = qp_group_attend(L, qg, kg, vg, n_g, cache, og, nullptr, split_ws + ai * kAttendSplitBytes, kAttendSplitBytes,
                          (void*)att_stream);
     if (st != QP_OK) break;
@@ -460,17 +489,32 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
     if (st != QP_OK) break;
     if (overlap) QP_HIP_OK(hipEventRecord(g_side.compacted[gi & 1], g_side.score));
   }
-  // everything enqueued on the library's streams is ordered before whatever the caller enqueues next
+#undef QP_HIP_OK
+  // Join, on success and on failure alike: everything enqueued on the library's streams is ordered before whatever
+  // the caller enqueues next on hip_stream. A join call that fails is reported unless an earlier error already is.
   if (overlap) {
-    QP_HIP_OK(hipEventRecord(g_side.compacted[0], g_side.score));
-    QP_HIP_OK(hipStreamWaitEvent(main_stream, g_side.compacted[0], 0));
+    hipError_t je = hipEventRecord(g_side.compacted[0], g_side.score);
+    if (je == hipSuccess) je = hipStreamWaitEvent(main_stream, g_side.compacted[0], 0);
     for (int i = 1; i < g_side.n_att; ++i) {
-      QP_HIP_OK(hipEventRecord(g_side.attend_done[i], g_side.attend[i]));
-      QP_HIP_OK(hipStreamWaitEvent(main_stream, g_side.attend_done[i], 0));
+      hipError_t e = hipEventRecord(g_side.attend_done[i], g_side.attend[i]);
+      if (e == hipSuccess) e = hipStreamWaitEvent(main_stream, g_side.attend_done[i], 0);
+      if (je == hipSuccess) je = e;
+    }
+    if (je != hipSuccess) {
+      const qp_status js = finish(je);
+      if (st == QP_OK) st = js;
     }
   }
-#undef QP_HIP_OK
+  // After a failure the groups already enqueued still run, but the cache is handed back at its length at entry:
+  // rows beyond it are scratch.
+  if (st != QP_OK) cache->len = len_at_entry;
   return st;
+}
+
+qp_status qp_debug_fail_after(int32_t n_checks) {
+  if (n_checks < 0) return QP_ERR_INVALID_ARG;
+  g_fail_countdown.store(n_checks, std::memory_order_relaxed);
+  return QP_OK;
 }
 
 const char* qp_status_string(qp_status s) {

@@ -74,7 +74,11 @@ __device__ __forceinline__ float wave_sum(float v) {
 // 64 lanes x 16 bytes global -> LDS without passing through registers: lane L's chunk lands at
 // lds_dst + 16 L (lds_dst is wave-uniform). Written as inline assembly so that the compiler does not
 // treat it as an LDS store it must drain (vmcnt(0)) before every later LDS read; the kernel waits for
-// these loads itself (s_waitcnt vmcnt) before the barrier that publishes a tile.
+// these loads itself (s_waitcnt vmcnt) before the barrier that publishes a tile. m0 is on the clobber list so that
+// the compiler orders its own uses of m0 around the statement (it warns that m0 is reserved: nothing is to be
+// preserved here, the statement sets m0 itself each time).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void lds_dma16(const unsigned char* base, unsigned byte_off, unsigned char* lds_dst) {
   const unsigned lds_addr =
       __builtin_amdgcn_readfirstlane((unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds_dst);
@@ -84,8 +88,9 @@ __device__ __forceinline__ void lds_dma16(const unsigned char* base, unsigned by
       "global_load_lds_dwordx4 %0, %1"
       :
       : "v"(byte_off), "s"(base), "s"(lds_addr)
-      : "memory");
+      : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 // Arguments common to the attention kernels. All pointers are device pointers.
 struct AttendArgs {

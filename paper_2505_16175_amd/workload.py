@@ -61,22 +61,8 @@ class Workload:
         return self.group_frames * self.tokens_per_frame
 
     @property
-    def n_groups(self) -> int:
-        return -(-self.n_frames // self.group_frames)
-
-    @property
     def gqa_ratio(self) -> int:
         return self.n_q_heads // self.n_kv_heads
-
-    def group_bounds(self):
-        """[(first_token, n_tokens)] of each frame-aligned group; the last may be short."""
-        out = []
-        f = 0
-        while f < self.n_frames:
-            g = min(self.group_frames, self.n_frames - f)
-            out.append((f * self.tokens_per_frame, g * self.tokens_per_frame))
-            f += g
-        return out
 
     def torch_dtype(self):
         return torch.float32 if self.dtype == "f32" else torch.bfloat16

@@ -25,6 +25,39 @@ def test_library_exports_every_declared_symbol():
     assert B.version().startswith("quickprefill")
 
 
+def test_group_bounds_match_the_oracle_and_a_hand_case():
+    # hour-long config: 56 groups of 64 frames and one of 16 (3600 = 56 * 64 + 16)
+    w = CONFIGS["cfg5_7b_hour_stack"]
+    b = B.group_bounds(w.n_frames, w.tokens_per_frame, w.group_frames)
+    assert len(b) == 57 and b[0] == (0, 8192) and b[-1] == (56 * 8192, 2048) and sum(n for _, n in b) == w.n_tokens
+    for f, t, g in ((1, 1, 1), (7, 6, 3), (8, 16, 2), (5, 3, 9), (256, 128, 16), (3600, 128, 64)):
+        assert B.group_bounds(f, t, g) == [tuple(x) for x in O.group_bounds(f, t, g)]
+    lib = B.lib()
+    assert lib.qp_group_bounds(0, 1, 1, None, None, 0) == -1
+    assert lib.qp_group_bounds(4, 0, 1, None, None, 0) == -1
+    assert lib.qp_group_bounds(4, 4, 0, None, None, 0) == -1
+    assert lib.qp_group_bounds(1 << 20, 1 << 12, 1, None, None, 0) == -1      # token indices beyond int32
+    first = (ctypes.c_int32 * 2)(-7, -7)                                       # fewer slots than groups: only those are written
+    assert lib.qp_group_bounds(7, 6, 3, first, None, 1) == 3 and list(first) == [0, -7]
+
+
+@pytest.mark.skipif(__import__("torch").cuda.is_available(), reason="needs a machine WITHOUT a GPU: there every launch fails")
+def test_prefill_video_reports_a_failed_launch_and_leaves_the_cache_length():
+    # Host code never dereferences the data pointers, so made-up aligned addresses do; without a device the first
+    # launch fails, the call must say so and hand the cache back as it got it.
+    L = B.make_layout(4, 2, 64, "f32")
+    fake = 1 << 20
+    c = B.qp_cache(fake, fake, fake, B.cache_capacity(8, 16, 2, 0.5) + 5, 5)
+    st = B.lib().qp_prefill_video(ctypes.byref(L), 8, 16, 2, 0.5, 0, fake, fake, fake, None, 0, ctypes.byref(c), fake,
+                                  fake, B.workspace_bytes(L, 32, 0), None)
+    assert st == B.QP_ERR_HIP and c.len == 5 and B.last_hip_error() != 0
+
+
+def test_debug_fail_after_arguments():
+    assert B.lib().qp_debug_fail_after(-1) == B.QP_ERR_INVALID_ARG
+    assert B.lib().qp_debug_fail_after(0) == B.QP_OK
+
+
 def test_linear_plan_chunks_cover_the_contraction():
     """Host arithmetic of the projection launch: k chunks are non-empty and cover all 64-wide k-steps, the partial
     sums fit the scratch offered, launches that fill the GPU are never split, and without scratch nothing is."""

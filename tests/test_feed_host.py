@@ -86,6 +86,58 @@ def test_consumer_blocks_until_published_and_ends_after_close():
         feed.destroy()
 
 
+def _returns_within(fn, seconds):
+    t = threading.Thread(target=fn, daemon=True)
+    t.start()
+    t.join(seconds)
+    return not t.is_alive()
+
+
+def test_destroy_returns_when_the_consumer_stopped_early_with_the_ring_full():
+    # the consumer gives up at group 1 of 8 with 2 slots: the stand-in producer is blocked on the full ring and
+    # destroy must wake it before joining its thread
+    import torch
+    src = torch.arange(8 * 16, dtype=torch.uint8)
+    feed = B.Feed(2, 16, B.QP_FEED_PAGEABLE)
+    feed.stub_producer(src, [16] * 8, 0, 0)
+    st, _, _, g = feed.next(-1)
+    assert (st, g) == (B.QP_OK, 0)
+    feed.release(0)
+    st, _, _, g = feed.next(-1)
+    assert (st, g) == (B.QP_OK, 1)                             # never released: the consumer "fails" here
+    time.sleep(0.2)                                            # the producer has filled the ring and is waiting
+    assert _returns_within(feed.destroy, 5.0)
+
+
+def test_stop_wakes_a_blocked_producer_and_refuses_later_writes():
+    feed = B.Feed(2, 16, B.QP_FEED_PAGEABLE)
+    try:
+        _write(feed, b"a")
+        _write(feed, b"b")
+        seen = []
+
+        def third():
+            try:
+                _write(feed, b"c")
+                seen.append("written")
+            except B.QPError as e:
+                seen.append(e.status)
+
+        t = threading.Thread(target=third, daemon=True)
+        t.start()
+        time.sleep(0.2)
+        assert seen == []                                      # blocked: both slots are published and unreleased
+        feed.stop()
+        t.join(5)
+        assert seen == [B.QP_FEED_END]
+        with pytest.raises(B.QPError) as e:
+            feed.begin_write()
+        assert e.value.status == B.QP_FEED_END
+        assert feed.next(0)[0] == B.QP_OK                      # what was published can still be taken
+    finally:
+        feed.destroy()
+
+
 def test_stub_producer_paces_the_groups():
     import torch
     feed = B.Feed(2, 8, B.QP_FEED_PAGEABLE)

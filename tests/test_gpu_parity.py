@@ -463,7 +463,7 @@ def _full_size_check(w, rule, sharp, n_rows, layer=0):
     out, cache = _run_prefill(w, q, k, v, qw, rule)
     sel, pos, near, sel_valid = _check_cache_against_oracle(w, k, v, qw, rule, cache)
     rng = np.random.default_rng(5)
-    bounds = w.group_bounds()
+    bounds = B.group_bounds(w.n_frames, w.tokens_per_frame, w.group_frames)
     groups = sorted({0, 1, len(bounds) // 2, len(bounds) - 1})
     k64, v64 = _f64(k), _f64(v)
     stats = []
@@ -566,7 +566,7 @@ def test_prefill_can_be_resumed_from_the_cache():
                     q[:n_head], k[:n_head], v[:n_head], qw, cache, out[:n_head], ws)
     torch.cuda.synchronize()
     assert cache.len == 3 * B.keep_count(w.group_tokens, w.retention)
-    for base, n_g in w.group_bounds()[3:]:              # two full groups and the short last one
+    for base, n_g in B.group_bounds(w.n_frames, w.tokens_per_frame, w.group_frames)[3:]:              # two full groups and the short last one
         sl = slice(base, base + n_g)
         scores = torch.empty(w.n_kv_heads, n_g, dtype=torch.float32, device=DEV)
         B.group_attend(layout, q[sl], k[sl], v[sl], cache, out[sl], None, ws)
@@ -675,3 +675,42 @@ def test_group_attend_largest_group():
     rows = sample_rows(n_g, 20, np.random.default_rng(1))
     want = O.attend_group(_f64(q), _f64(k), _f64(v), _f64(cache.k), _f64(cache.v), rows=rows)
     assert_attn_close(_f64(out[rows]), want, "bf16", "largest group")
+
+
+def test_prefill_video_failure_mid_loop_joins_streams_and_restores_the_cache_length():
+    """A launch check that fails in the third group (forced from the host; every kernel still runs normally): the call
+    reports QP_ERR_HIP, hands the cache back at its length at entry, and has joined its streams, so that the very next
+    call on the same stream reproduces an undisturbed run bit for bit."""
+    w = scaled(CONFIGS["cfg2_7b_32k"], n_frames=24, tokens_per_frame=64, group_frames=4)
+    q, k, v, qw = make_layer(w, device=DEV, sharp=True)
+    layout = B.make_layout(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
+    cap = B.cache_capacity(w.n_frames, w.tokens_per_frame, w.group_frames, w.retention)
+    ws = B.make_workspace(layout, w.group_tokens, w.n_window)
+    cache = B.Cache(layout, cap)
+    out = torch.empty_like(q)
+
+    def run():
+        cache.reset()
+        B.prefill_video(layout, w.n_frames, w.tokens_per_frame, w.group_frames, w.retention, "window_attn", q, k, v,
+                        qw, cache, out, ws)
+
+    run()
+    torch.cuda.synchronize()
+    want = (out.clone(), cache.k.clone(), cache.v.clone(), cache.pos.clone())
+    final_len = cache.len
+    for nth in (1, 5, 8, 9):                                  # group 0's attention; group 1's scores; group 2's scores, top-k
+        cache.reset()
+        assert B.lib().qp_debug_fail_after(nth) == B.QP_OK
+        try:
+            with pytest.raises(B.QPError) as e:
+                B.prefill_video(layout, w.n_frames, w.tokens_per_frame, w.group_frames, w.retention, "window_attn", q,
+                                k, v, qw, cache, out, ws)
+        finally:
+            B.lib().qp_debug_fail_after(0)
+        assert e.value.status == B.QP_ERR_HIP
+        assert cache.len == 0                                 # restored, although earlier groups were appended
+        run()                                                 # no synchronisation in between: ordered by the join
+        torch.cuda.synchronize()
+        assert cache.len == final_len
+        for a, b in zip(want, (out, cache.k, cache.v, cache.pos)):
+            assert torch.equal(a, b), f"after a failure at check {nth}"

@@ -35,9 +35,3 @@ def test_recipe_statistics():
     assert np.corrcoef(kn[:, 0], kn[:, 1])[0, 1] > 0.9
     # bf16 values widen exactly
     assert np.array_equal(to_f64(q).astype(np.float32), q.float().numpy())
-
-
-def test_group_bounds_ragged():
-    w = CONFIGS["cfg5_7b_hour_stack"]
-    b = w.group_bounds()
-    assert len(b) == 57 and b[-1] == (56 * 8192, 2048) and sum(n for _, n in b) == w.n_tokens
