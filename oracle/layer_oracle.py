@@ -35,10 +35,14 @@ Readings (the paper does not describe the layer beyond Appendix D.1; these are s
 
 Parity status: rms_norm, mrope_cos_sin / apply_rotary, silu / swiglu_mlp and linear are pinned by the CPU
 tests (closed forms, the relative-position invariance of rotary embeddings, norm preservation, reduction to
-the one-dimensional embedding, hand-computed small cases, library silu). layer_group as a whole against
-numbers printed in the paper: parity unpinned -- the paper prints no activation of any layer; it is pinned
-structurally (it equals its parts composed by hand in the test, and with zero attention/MLP weights it is the
-identity).
+the one-dimensional embedding, hand-computed small cases, library silu). window_queries / project_queries: a
+one-token case worked by hand (tests/golden/hand_window_queries.txt), scale invariance (the norm is there), which
+parameters they depend on, bias-before-rotation, and equality with layer_group's own q for the same tokens.
+layer_group's wiring: the same block built from library routines only (torch rms_norm / linear / silu / scaled-dot-
+product attention, rotation as a complex product), its composition from the pinned parts, perturbation pins on
+every edge of the residual stream, identity with zero output projections. layer_stack: rho = 1 equals one group;
+with rho < 1 every layer's kept set is the top-k of that layer's own keys under that layer's own window queries.
+layer_group against numbers printed in the paper: parity unpinned -- the paper prints no activation of any layer.
 """
 from __future__ import annotations
 

@@ -243,3 +243,196 @@ def test_store_hook_rounds_every_kept_tensor():
         np.testing.assert_array_equal(mid[name], lo.bf16_round(mid[name]), err_msg=name)
     np.testing.assert_array_equal(y, lo.bf16_round(y))
     np.testing.assert_array_equal(nk, lo.bf16_round(nk))
+
+
+# ----------------------------------------------------------------------------- the scoring window's queries
+def test_window_queries_hand_case():
+    """tests/golden/hand_window_queries.txt: one token through RMSNorm, W_q + b_q and the rotary embedding, every
+    number worked by hand. Dropping the norm, the norm weight, the bias or the rotation, pairing neighbours instead of
+    halves, or taking the wrong position axis for a frequency all change the numbers."""
+    from conftest import read_golden
+    rows = read_golden("hand_window_queries.txt")
+    want_q = np.array([float(r[1]) for r in rows])
+    want_rot = np.array([float(r[2]) for r in rows])
+    shape = dict(n_q_heads=1, n_kv_heads=1, head_dim=4, d_model=4, rms_eps=0.0, rope_theta=100.0, mrope_section=(1, 1, 0))
+    w = dict(ln1=np.array([1.0, 1.0, 2.0, 1.0]),
+             w_q=np.array([[1.0, 0, 0, 0], [0, 1.0, 0, 0], [0, 0, 1.0, 0], [1.0, 1.0, 0, 0]]),
+             b_q=np.array([0.0, 0.5, 0.0, -1.0]))
+    x = np.array([[1.0, -1.0, 2.0, 0.0]])
+    at_origin = lo.window_queries(x, np.array([[0], [0], [0]]), w, shape)      # angle 0: the projection itself
+    np.testing.assert_allclose(at_origin[0, 0], want_q, atol=2e-15)
+    got = lo.window_queries(x, np.array([[3], [5], [7]]), w, shape)
+    assert got.shape == (1, 1, 4)
+    np.testing.assert_allclose(got[0, 0], want_rot, atol=3e-15)
+    # project_queries is the part after the norm
+    h = np.array([[1.0, -1.0, 4.0, 0.0]]) / math.sqrt(1.5)
+    np.testing.assert_allclose(lo.project_queries(h, w["w_q"], w["b_q"], np.array([[3], [5], [7]]), shape)[0, 0],
+                               want_rot, atol=3e-15)
+
+
+def test_window_queries_invariants():
+    shape = small_shape()
+    w = random_layer(shape)
+    n = 5
+    x = RNG.standard_normal((n, shape["d_model"]))
+    pos = np.stack([np.arange(n) + 9, np.arange(n) + 2, np.arange(n)])
+    q = lo.window_queries(x, pos, w, shape)
+    assert q.shape == (n, shape["n_q_heads"], shape["head_dim"])
+    # the hidden states are normalised first: scaling them changes nothing (fails if RMSNorm is dropped)
+    no_eps = dict(shape, rms_eps=0.0)
+    np.testing.assert_allclose(lo.window_queries(3.7 * x, pos, w, no_eps), lo.window_queries(x, pos, w, no_eps),
+                               rtol=1e-12, atol=1e-13)
+    # it is the FIRST norm's weight, and only the query projection's parameters
+    w2 = dict(w, ln2=w["ln2"] * 3.0, w_k=w["w_k"] * 2.0, b_k=w["b_k"] + 1.0, w_v=w["w_v"] * 2.0, w_o=w["w_o"] * 2.0)
+    np.testing.assert_array_equal(lo.window_queries(x, pos, w2, shape), q)
+    assert np.abs(lo.window_queries(x, pos, dict(w, ln1=w["ln1"] * 1.5), shape) - q).max() > 1e-3
+    # the bias is added before the rotation: with a zero matrix the queries are the rotated bias, at the origin the bias itself
+    wz = dict(w, w_q=np.zeros_like(w["w_q"]))
+    at0 = lo.window_queries(x, np.zeros((3, n), dtype=np.int64), wz, shape)
+    np.testing.assert_allclose(at0, np.broadcast_to(w["b_q"].reshape(1, shape["n_q_heads"], -1), at0.shape), atol=1e-15)
+    rot = lo.window_queries(x, pos, wz, shape)
+    np.testing.assert_allclose(np.linalg.norm(rot, axis=-1), np.linalg.norm(at0, axis=-1), rtol=1e-12)
+    assert np.abs(rot - at0).max() > 1e-3
+    # rotation is per token: the queries of token i do not depend on the other tokens
+    np.testing.assert_allclose(lo.window_queries(x[2:3], pos[:, 2:3], w, shape), q[2:3], atol=1e-14)
+
+
+def test_window_queries_equal_the_layers_own_queries_for_the_same_tokens():
+    # the window's tokens run as a group through the same layer produce the same q (same norm, projection, rotation)
+    shape = small_shape()
+    w = random_layer(shape)
+    n = 6
+    x = RNG.standard_normal((n, shape["d_model"]))
+    pos = np.stack([np.arange(n) + 40, np.arange(n) + 40, np.arange(n) + 40])
+    empty = np.zeros((shape["n_kv_heads"], 0, shape["head_dim"]))
+    _, _, _, _, mid = lo.layer_group(x, pos, w, shape, empty, empty, None, "key_norm_small", 1.0)
+    np.testing.assert_allclose(lo.window_queries(x, pos, w, shape), mid["q"], atol=1e-14)
+    # and with the storage hook both round at the same places
+    _, _, _, _, mid_r = lo.layer_group(lo.bf16_round(x), pos, w, shape, empty, empty, None, "key_norm_small", 1.0,
+                                       store=lo.bf16_round)
+    np.testing.assert_array_equal(lo.window_queries(lo.bf16_round(x), pos, w, shape, store=lo.bf16_round), mid_r["q"])
+
+
+# ----------------------------------------------------------------------------- the block's wiring
+def _torch_block(x, pos1d, w, shape):
+    """The same pre-norm block out of library routines only (torch.nn.functional rms_norm / linear / silu /
+    scaled_dot_product_attention, rotation as a complex multiplication), one group, empty cache, equal position
+    indices on the three axes."""
+    F = torch.nn.functional
+    t = lambda a: torch.tensor(np.asarray(a), dtype=torch.float64)
+    n, dm = x.shape
+    h_q, h_kv, d = shape["n_q_heads"], shape["n_kv_heads"], shape["head_dim"]
+    half = d // 2
+    rot = torch.polar(torch.ones(n, half, dtype=torch.float64),
+                      t(pos1d)[:, None] * shape["rope_theta"] ** (-2.0 * torch.arange(half, dtype=torch.float64) / d))
+
+    def rotate(z):                                              # [n, H, d]; component i pairs with i + d/2
+        zc = torch.complex(z[..., :half], z[..., half:]) * rot[:, None, :]
+        return torch.cat([zc.real, zc.imag], dim=-1)
+
+    xt = t(x)
+    h = F.rms_norm(xt, (dm,), t(w["ln1"]), shape["rms_eps"])
+    q = rotate(F.linear(h, t(w["w_q"]), t(w["b_q"])).view(n, h_q, d))
+    k = rotate(F.linear(h, t(w["w_k"]), t(w["b_k"])).view(n, h_kv, d))
+    v = F.linear(h, t(w["w_v"]), t(w["b_v"])).view(n, h_kv, d)
+    r = h_q // h_kv
+    a = F.scaled_dot_product_attention(q.permute(1, 0, 2)[None], k.permute(1, 0, 2)[None].repeat_interleave(r, dim=1),
+                                       v.permute(1, 0, 2)[None].repeat_interleave(r, dim=1), is_causal=True)
+    a = a[0].permute(1, 0, 2).reshape(n, h_q * d)
+    x1 = xt + F.linear(a, t(w["w_o"]))
+    h2 = F.rms_norm(x1, (dm,), t(w["ln2"]), shape["rms_eps"])
+    x2 = x1 + F.linear(F.silu(F.linear(h2, t(w["w_gate"]))) * F.linear(h2, t(w["w_up"])), t(w["w_down"]))
+    return x1.numpy(), h2.numpy(), x2.numpy()
+
+
+def test_layer_block_equals_the_same_block_built_from_library_routines():
+    """Catches any mis-wiring of the residual stream: the second norm or the MLP fed from x instead of x1, a
+    residual dropped or doubled, the two norm weights swapped, gate and up exchanged."""
+    shape = small_shape()
+    w = random_layer(shape)
+    n = 9
+    x = RNG.standard_normal((n, shape["d_model"]))
+    p = np.arange(n) + 3
+    empty = np.zeros((shape["n_kv_heads"], 0, shape["head_dim"]))
+    y, _, _, _, mid = lo.layer_group(x, np.stack([p, p, p]), w, shape, empty, empty, None, "key_norm_small", 1.0)
+    x1, h2, x2 = _torch_block(x, p, w, shape)
+    np.testing.assert_allclose(mid["x1"], x1, atol=1e-12)
+    np.testing.assert_allclose(mid["h2"], h2, atol=1e-12)
+    np.testing.assert_allclose(y, x2, atol=1e-12)
+
+
+def test_layer_block_composed_from_its_parts_and_perturbations():
+    shape = small_shape()
+    w = random_layer(shape)
+    n = 7
+    x = RNG.standard_normal((n, shape["d_model"]))
+    pos = np.stack([np.arange(n), np.arange(n) % 2, np.arange(n) % 3])
+    ck = RNG.standard_normal((shape["n_kv_heads"], 5, shape["head_dim"]))      # a non-empty cache this time
+    cv = RNG.standard_normal((shape["n_kv_heads"], 5, shape["head_dim"]))
+    run = lambda wt: lo.layer_group(x, pos, wt, shape, ck, cv, None, "value_norm", 0.5)
+    y, _, _, _, mid = run(w)
+    # composition by hand from the pinned parts
+    x1 = x + lo.linear(mid["attn"].reshape(n, -1), w["w_o"])
+    h2 = lo.rms_norm(x1, w["ln2"], shape["rms_eps"])
+    x2 = x1 + lo.swiglu_mlp(h2, w["w_gate"], w["w_up"], w["w_down"])
+    np.testing.assert_allclose(mid["x1"], x1, atol=1e-14)
+    np.testing.assert_allclose(mid["h2"], h2, atol=1e-14)
+    np.testing.assert_allclose(y, x2, atol=1e-14)
+    # the second norm and the MLP see the attention's contribution; the first residual does not see the second norm
+    _, _, _, _, m_o = run(dict(w, w_o=w["w_o"] * 1.5))
+    assert np.abs(m_o["h2"] - mid["h2"]).max() > 1e-3 and np.abs(m_o["x1"] - mid["x1"]).max() > 1e-3
+    y_ln2, _, _, _, m_ln2 = run(dict(w, ln2=w["ln2"] * 1.5))
+    np.testing.assert_array_equal(m_ln2["x1"], mid["x1"])
+    assert np.abs(y_ln2 - y).max() > 1e-3
+    # the MLP's output is added to x1 (not to x): with w_down = 0 the layer returns x1
+    y0, _, _, _, m0 = run(dict(w, w_down=np.zeros_like(w["w_down"])))
+    np.testing.assert_array_equal(y0, m0["x1"])
+    assert np.abs(m0["x1"] - x).max() > 1e-3
+    # and with w_o = 0 it is x + MLP(RMSNorm(x; ln2))
+    yo, _, _, _, _ = run(dict(w, w_o=np.zeros_like(w["w_o"])))
+    np.testing.assert_allclose(yo, x + lo.swiglu_mlp(lo.rms_norm(x, w["ln2"], shape["rms_eps"]), w["w_gate"], w["w_up"],
+                                                     w["w_down"]), atol=1e-14)
+    # the cache is read by the attention: other cached values change the output, the kept rows come from this group's k, v
+    y_c, idx, nk, nv, m_c = lo.layer_group(x, pos, w, shape, ck, cv * 2.0, None, "value_norm", 0.5)
+    assert np.abs(y_c - y).max() > 1e-3
+    for j in range(shape["n_kv_heads"]):
+        np.testing.assert_array_equal(nk[j], m_c["k"][idx[j], j])
+        np.testing.assert_array_equal(nv[j], m_c["v"][idx[j], j])
+
+
+@pytest.mark.parametrize("rule", ["window_attn", "window_logit"])
+def test_stack_window_rule_selects_on_this_layers_own_window_queries(rule):
+    """With rho < 1 the window rule decides what is kept: the kept indices of every layer must be the top-k of
+    score_kv over that layer's own keys and that layer's own window queries (not another layer's, not unrotated)."""
+    shape = small_shape()
+    layers = [random_layer(shape), random_layer(shape)]
+    tpf, frames = 4, 4
+    n = tpf * frames
+    x = RNG.standard_normal((n, shape["d_model"]))
+    pos3 = np.stack([np.repeat(np.arange(frames), tpf), np.tile(np.arange(tpf), frames), np.zeros(n, dtype=np.int64)])
+    x_win = RNG.standard_normal((2, 3, shape["d_model"]))
+    pos_win = np.stack([np.arange(3) + frames] * 3)
+    gb = qo.group_bounds(frames, tpf, 2)
+    _, caches = lo.layer_stack(x, pos3, layers, shape, gb, x_win, pos_win, rule, 0.5)
+    # replay by hand, group-major: every group goes through layer 0 then layer 1; layer l scores its own keys with its
+    # own window queries (its own text hidden states through its own norm and W_q)
+    empty = np.zeros((2, 0, 8))
+    state = [[empty, empty, []] for _ in layers]
+    for base, n_g in gb:
+        cur = x[base:base + n_g]
+        for l, wts in enumerate(layers):
+            qw = lo.window_queries(x_win[l], pos_win, wts, shape)
+            ck, cv, kept_l = state[l]
+            cur, idx, nk, nv, mid = lo.layer_group(cur, pos3[:, base:base + n_g], wts, shape, ck, cv, qw, rule, 0.5)
+            want = qo.topk_select(qo.score_kv(rule, mid["k"], mid["v"], qw), qo.keep_count(n_g, 0.5))
+            np.testing.assert_array_equal(idx, want)
+            kept_l.append(base + idx)
+            state[l][0], state[l][1] = np.concatenate([ck, nk], axis=1), np.concatenate([cv, nv], axis=1)
+    for l in range(len(layers)):
+        np.testing.assert_array_equal(caches[l][2], np.concatenate(state[l][2], axis=1))
+        np.testing.assert_array_equal(caches[l][0], state[l][0])
+    kept = state[0][2]
+    # another layer's window queries would have kept something else somewhere
+    qw_other = lo.window_queries(x_win[1], pos_win, layers[0], shape)
+    _, idx_other, _, _, _ = lo.layer_group(x[:8], pos3[:, :8], layers[0], shape, empty, empty, qw_other, rule, 0.5)
+    assert not np.array_equal(idx_other, kept[0])
