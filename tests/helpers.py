@@ -1,6 +1,8 @@
 """Comparison helpers shared by the GPU parity tests (no method arithmetic of their own)."""
 import numpy as np
 
+from paper_2505_16175_amd.workload import to_f64
+
 # Tolerances of the benchmark definition: bf16 outputs within 2e-2 absolute / 1e-2 relative of the
 # fp64 oracle, f32 within 1e-5. |O| is small under the literal 1/sqrt(d) input scaling, so a
 # normalised-error gate is applied as well (a wrong kernel must not pass on the absolute term).
@@ -57,3 +59,36 @@ def sample_rows(n_g, n_samples, rng, tile=32):
     while len(rows) < min(n_g, n_samples):
         rows.add(int(rng.integers(0, n_g)))
     return sorted(rows)
+
+
+# ---- the decoder layer around the path: the product's fused weight tensors split into the layer oracle's names ----
+def oracle_weights(w, dims):
+    hq, hkv = dims.n_q_heads * 128, dims.n_kv_heads * 128
+    f = {k: to_f64(v) for k, v in w.items()}
+    return dict(ln1=f["ln1_w"], ln2=f["ln2_w"], w_q=f["w_qkv"][:hq], b_q=f["b_qkv"][:hq],
+                w_k=f["w_qkv"][hq:hq + hkv], b_k=f["b_qkv"][hq:hq + hkv], w_v=f["w_qkv"][hq + hkv:],
+                b_v=f["b_qkv"][hq + hkv:], w_o=f["w_o"], w_gate=f["w_gate_up"][:dims.d_ff],
+                w_up=f["w_gate_up"][dims.d_ff:], w_down=f["w_down"])
+
+
+def oracle_shape(dims):
+    return dict(n_q_heads=dims.n_q_heads, n_kv_heads=dims.n_kv_heads, head_dim=128, d_model=dims.d_model,
+                rms_eps=dims.rms_eps, rope_theta=dims.rope_theta, mrope_section=dims.mrope_section)
+
+
+# Through a whole layer the attention kernel's own tolerance applies (it rounds the softmax numerators to bf16:
+# up to 2e-2 absolute / 1e-2 relative on the attention output), carried through W_o and the MLP; everything else
+# is one-ulp rounding flips. Layers add their errors, so the absolute floor grows with the depth of the stack;
+# the normalised error stays under the attention kernel's 1e-2. A wrong operand, index or epilogue gives errors
+# of the size of the RMS itself.
+def assert_layer_close(got, want, what, layers=1):
+    got, want = np.asarray(got, dtype=np.float64), np.asarray(want, dtype=np.float64)
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    rms = np.sqrt(np.mean(want * want))
+    err = np.abs(got - want)
+    rel = np.linalg.norm(got - want) / np.linalg.norm(want)
+    print(f"{what}: normalised error {rel:.2e}, max abs error {err.max():.2e}, rms {rms:.2e}", flush=True)
+    bad = err > 2e-2 * np.abs(want) + 2e-2 * layers * rms
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} out of tolerance, max err {err.max():.3e} (rms {rms:.3e})"
+    assert rel <= 1e-2, f"{what}: normalised error {rel:.3e}"
+    return rel

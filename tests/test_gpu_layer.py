@@ -8,6 +8,7 @@ from oracle import qp_oracle as O
 from paper_2505_16175_amd import binding as B
 from paper_2505_16175_amd import workload as W
 from paper_2505_16175_amd.workload import to_f64
+from helpers import assert_layer_close, compare_kept, oracle_shape, oracle_weights
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -211,38 +212,6 @@ def test_unsupported_shapes_are_refused_before_launch():
 
 
 # ------------------------------------------------------------------------------------------------ the layer
-def _oracle_weights(w, dims):
-    hq, hkv = dims.n_q_heads * 128, dims.n_kv_heads * 128
-    f = {k: to_f64(v) for k, v in w.items()}
-    return dict(ln1=f["ln1_w"], ln2=f["ln2_w"], w_q=f["w_qkv"][:hq], b_q=f["b_qkv"][:hq],
-                w_k=f["w_qkv"][hq:hq + hkv], b_k=f["b_qkv"][hq:hq + hkv], w_v=f["w_qkv"][hq + hkv:],
-                b_v=f["b_qkv"][hq + hkv:], w_o=f["w_o"], w_gate=f["w_gate_up"][:dims.d_ff],
-                w_up=f["w_gate_up"][dims.d_ff:], w_down=f["w_down"])
-
-
-def _oracle_shape(dims):
-    return dict(n_q_heads=dims.n_q_heads, n_kv_heads=dims.n_kv_heads, head_dim=128, d_model=dims.d_model,
-                rms_eps=dims.rms_eps, rope_theta=dims.rope_theta, mrope_section=dims.mrope_section)
-
-
-# Through a whole layer the attention kernel's own tolerance applies (it rounds the softmax numerators to bf16:
-# up to 2e-2 absolute / 1e-2 relative on the attention output), carried through W_o and the MLP; everything else
-# is one-ulp rounding flips. Layers add their errors, so the absolute floor grows with the depth of the stack;
-# the normalised error stays under the attention kernel's 1e-2. A wrong operand, index or epilogue gives errors
-# of the size of the RMS itself.
-def assert_layer_close(got, want, what, layers=1):
-    got, want = np.asarray(got, dtype=np.float64), np.asarray(want, dtype=np.float64)
-    assert np.isfinite(got).all(), f"{what}: non-finite output"
-    rms = np.sqrt(np.mean(want * want))
-    err = np.abs(got - want)
-    rel = np.linalg.norm(got - want) / np.linalg.norm(want)
-    print(f"{what}: normalised error {rel:.2e}, max abs error {err.max():.2e}, rms {rms:.2e}", flush=True)
-    bad = err > 2e-2 * np.abs(want) + 2e-2 * layers * rms
-    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} out of tolerance, max err {err.max():.3e} (rms {rms:.3e})"
-    assert rel <= 1e-2, f"{what}: normalised error {rel:.3e}"
-    return rel
-
-
 def _gpu_stack(dims, layers_t, x, pos, bounds, x_win, pos_win, rule, retention):
     """The group-major schedule of Sec. 3.2 driven through the C ABI: every group runs through all layers."""
     layout = B.make_layout(dims.n_q_heads, dims.n_kv_heads, 128, "bf16")
@@ -276,6 +245,23 @@ def _gpu_stack(dims, layers_t, x, pos, bounds, x_win, pos_win, rule, retention):
     return out, caches, kept
 
 
+def _gpu_group_qkv(dims, wt_dev, x_dev, pos_dev, first, n_g):
+    """The group's rotated q, k and its v as the layer computes them on the GPU (same calls, same kernels: RMSNorm,
+    rotary table, fused QKV projection with the contraction-split scratch the layer offers), returned widened."""
+    layout = B.make_layout(dims.n_q_heads, dims.n_kv_heads, 128, "bf16")
+    h = torch.empty_like(x_dev)
+    cs = torch.empty(n_g, 64, 2, dtype=torch.float32, device=DEV)
+    q = torch.empty(n_g, dims.n_q_heads, 128, dtype=torch.bfloat16, device=DEV)
+    k = torch.empty(n_g, dims.n_kv_heads, 128, dtype=torch.bfloat16, device=DEV)
+    v = torch.empty_like(k)
+    scratch = torch.empty(32 << 20, dtype=torch.uint8, device=DEV)
+    B.rms_norm(x_dev, wt_dev["ln1_w"], h, dims.rms_eps)
+    B.rope_table(pos_dev, first, n_g, dims.rope_theta, dims.mrope_section, cs)
+    B.qkv_rope(layout, h, wt_dev["w_qkv"], wt_dev["b_qkv"], cs, q, k, v, scratch)
+    torch.cuda.synchronize()
+    return to_f64(q), to_f64(k), to_f64(v)
+
+
 SMALL = W.LayerDims(256, 384, 4, 2)
 
 
@@ -292,8 +278,8 @@ def test_layer_stack_full_retention_matches_oracle(rule, tile):
     bounds = O.group_bounds(frames, tpf, gf)
     use_win = rule.startswith("window")
     got, caches, _ = _gpu_stack(dims, layers_t, x, pos, bounds, x_win if use_win else None, pos_win, rule, 1.0)
-    want, want_caches = LO.layer_stack(to_f64(x), pos.numpy(), [_oracle_weights(w, dims) for w in layers_t],
-                                       _oracle_shape(dims), bounds, to_f64(x_win) if use_win else None, pos_win.numpy(),
+    want, want_caches = LO.layer_stack(to_f64(x), pos.numpy(), [oracle_weights(w, dims) for w in layers_t],
+                                       oracle_shape(dims), bounds, to_f64(x_win) if use_win else None, pos_win.numpy(),
                                        rule, 1.0, store=LO.bf16_round)
     assert_layer_close(to_f64(got), want, "stack output", layers=3)
     for l, (cache, (ck, cv, cp)) in enumerate(zip(caches, want_caches)):
@@ -311,25 +297,61 @@ def test_layer_group_pruned_first_group_and_parts():
     x = W.make_hidden(3, 100, dims.d_model)
     pos = W.video_positions(3, 100)
     got, caches, kept = _gpu_stack(dims, [wt], x, pos, [(0, n_g)], None, None, "key_norm_small", 0.3)
-    shape = _oracle_shape(dims)
+    shape = oracle_shape(dims)
     empty = np.zeros((dims.n_kv_heads, 0, 128))
-    want, idx, nk, nv, mid = LO.layer_group(to_f64(x), pos.numpy(), _oracle_weights(wt, dims), shape, empty, empty, None,
+    want, idx, nk, nv, mid = LO.layer_group(to_f64(x), pos.numpy(), oracle_weights(wt, dims), shape, empty, empty, None,
                                             "key_norm_small", 0.3, store=LO.bf16_round)
     assert_layer_close(to_f64(got), want, "layer output")
-    # the kept set is decided on each side's own bf16 keys, which differ by one-ulp flips in a few elements:
-    # a disagreement is accepted only between keys whose oracle scores are within 2e-3 (relative) of the k-th
+    # The selection is a function of the stored keys. The oracle's own keys differ from the GPU's by one-ulp flips in
+    # a few elements, so the rule of the path applies to the keys the GPU stored: the oracle scores THOSE (widened
+    # exactly) and its top-k must be the GPU's kept set, except between scores within 1e-5 (relative) of the k-th.
     got_idx = kept[0][2].cpu().numpy()
+    wt_dev = {k_: v_.to(DEV) for k_, v_ in wt.items()}
+    _, k_gpu, v_gpu = _gpu_group_qkv(dims, wt_dev, x.to(DEV), pos.to(DEV), 0, n_g)
+    assert_layer_close(k_gpu, mid["k"], "rotated keys")
+    scores_gpu_keys = O.score_kv("key_norm_small", k_gpu, v_gpu)
+    excused = compare_kept(got_idx, O.topk_select(scores_gpu_keys, idx.shape[1]), scores_gpu_keys)
+    print(f"kept sets on the GPU's stored keys: {excused} near-tie heads of {dims.n_kv_heads}", flush=True)
     for h in range(dims.n_kv_heads):
-        diff = np.setxor1d(got_idx[h], idx[h])
-        assert (np.diff(got_idx[h]) > 0).all()
-        if diff.size:
-            s_k = np.sort(mid["scores"][h])[::-1][idx.shape[1] - 1]
-            assert (np.abs(mid["scores"][h][diff] - s_k) < 2e-3 * abs(s_k)).all(), (h, diff)
+        # the appended rows are the GPU's own k, v at the kept tokens, bit for bit
+        np.testing.assert_array_equal(to_f64(caches[0].k)[h, :90], k_gpu[got_idx[h], h])
+        np.testing.assert_array_equal(to_f64(caches[0].v)[h, :90], v_gpu[got_idx[h], h])
         same = np.isin(got_idx[h], idx[h])
+        assert same.mean() > 0.9                                 # against the oracle's own keys: nearly the same set
         rows = np.searchsorted(idx[h], got_idx[h][same])
         assert_layer_close(to_f64(caches[0].k)[h, :90][same], nk[h][rows], f"head {h} cached K")
         assert_layer_close(to_f64(caches[0].v)[h, :90][same], nv[h][rows], f"head {h} cached V")
     assert caches[0].len == 90
+
+
+def test_layer_group_against_the_unrounded_definition():
+    """The layer against the fp64 definition with NO rounding anywhere (store = identity). The kernels round to bf16
+    where they store (h, q, k, v, attention output, x1, h2, the SwiGLU product, the output: 9 tensors on the way to
+    an output element, each a relative error of at most 2^-9, independent in sign) and the attention rounds its
+    softmax numerators (another 2^-9 per term): carried through the projections these add in quadrature to about
+    sqrt(10) * 2^-9 / sqrt(3) = 3.6e-3 of the RMS. Gates: normalised error <= 1e-2 and every element within
+    3e-2 |y| + 3e-2 rms (eight standard deviations). Nothing pruned, so no selection enters."""
+    dims = SMALL
+    n_g = 150
+    wt = W.make_decoder_layer(dims, 2)
+    x = W.make_hidden(6, 25, dims.d_model, seed=5)
+    pos = W.video_positions(6, 25)
+    got, caches, _ = _gpu_stack(dims, [wt], x, pos, [(0, n_g)], None, None, "value_norm", 1.0)
+    empty = np.zeros((dims.n_kv_heads, 0, 128))
+    want, _, nk, nv, _ = LO.layer_group(to_f64(x), pos.numpy(), oracle_weights(wt, dims), oracle_shape(dims), empty, empty,
+                                        None, "value_norm", 1.0)
+    got = to_f64(got)
+    rms = np.sqrt(np.mean(want * want))
+    err = np.abs(got - want)
+    rel = np.linalg.norm(got - want) / np.linalg.norm(want)
+    print(f"layer against the unrounded definition: normalised error {rel:.2e}, max abs {err.max():.2e}, rms {rms:.2e}",
+          flush=True)
+    assert np.isfinite(got).all() and rel <= 1e-2
+    assert (err <= 3e-2 * np.abs(want) + 3e-2 * rms).all()
+    for name, g_, w_ in (("K", to_f64(caches[0].k)[:, :n_g], nk), ("V", to_f64(caches[0].v)[:, :n_g], nv)):
+        r = np.linalg.norm(g_ - w_) / np.linalg.norm(w_)
+        print(f"cached {name} against the unrounded definition: normalised error {r:.2e}", flush=True)
+        assert r <= 4e-3                                         # two roundings (h, then the projection's store)
 
 
 def test_layer_group_full_size_sampled_rows():
@@ -368,7 +390,7 @@ def test_layer_group_full_size_sampled_rows():
     assert cache.len == c + keep
 
     rb = LO.bf16_round
-    ow, oshape = _oracle_weights(wt, dims), _oracle_shape(dims)
+    ow, oshape = oracle_weights(wt, dims), oracle_shape(dims)
     x64 = to_f64(x)
     h = rb(LO.rms_norm(x64, ow["ln1"], dims.rms_eps))
     cos, sin = LO.mrope_cos_sin(pos.numpy(), 128, dims.rope_theta, dims.mrope_section)
@@ -377,19 +399,21 @@ def test_layer_group_full_size_sampled_rows():
     v = rb(LO.linear(h, ow["w_v"], ow["b_v"]).reshape(n_g, hkv, 128))
     qw = LO.window_queries(to_f64(x_win), pos_win.numpy(), ow, oshape, store=rb)
     np.testing.assert_allclose(to_f64(q_win), qw, atol=2.0 ** -7 * np.abs(qw).max())     # one ulp at the largest value
-    scores = O.score_kv("window_attn", k, v, qw)
-    idx = O.topk_select(scores, keep)
+    # selection: the oracle scores the keys and window queries the GPU stored (widened exactly); 1e-5 near-tie rule
+    wt_dev = {k_: v_.to(DEV) for k_, v_ in wt.items()}
+    _, k_gpu, v_gpu = _gpu_group_qkv(dims, wt_dev, x.to(DEV), pos.to(DEV), 0, n_g)
+    assert_layer_close(k_gpu, k, "rotated keys")
+    assert_layer_close(v_gpu, v, "values")
+    scores = O.score_kv("window_attn", k_gpu, v_gpu, to_f64(q_win))
     got_idx = kept.cpu().numpy()
+    excused = compare_kept(got_idx, O.topk_select(scores, keep), scores)
+    print(f"kept sets on the GPU's stored keys: {excused} near-tie heads of {hkv}", flush=True)
+    idx = O.topk_select(O.score_kv("window_attn", k, v, qw), keep)               # on the oracle's own keys
     for hh in range(hkv):
-        diff = np.setxor1d(got_idx[hh], idx[hh])
-        assert (np.diff(got_idx[hh]) > 0).all()
-        if diff.size:        # each side scores its own bf16 keys and window queries: see the one-layer test above
-            s_k = np.sort(scores[hh])[::-1][keep - 1]
-            assert (np.abs(scores[hh][diff] - s_k) < 2e-3 * abs(s_k)).all(), (hh, diff)
         np.testing.assert_array_equal(cache.pos.cpu().numpy()[hh, c:c + keep], 5000 + got_idx[hh])
-        same = np.isin(got_idx[hh], idx[hh])
-        assert_layer_close(to_f64(cache.k)[hh, c:c + keep][same], k[got_idx[hh][same], hh], f"head {hh} appended K")
-        assert_layer_close(to_f64(cache.v)[hh, c:c + keep][same], v[got_idx[hh][same], hh], f"head {hh} appended V")
+        np.testing.assert_array_equal(to_f64(cache.k)[hh, c:c + keep], k_gpu[got_idx[hh], hh])
+        np.testing.assert_array_equal(to_f64(cache.v)[hh, c:c + keep], v_gpu[got_idx[hh], hh])
+        assert np.isin(got_idx[hh], idx[hh]).mean() > 0.9
     rows = sorted({0, 1, 127, 128, 255, 256, 1023, 1024, n_g - 129, n_g - 1} | set(np.random.default_rng(5).integers(0, n_g, 54).tolist()))
     a = rb(O.attend_group(q, k, v, to_f64(ck), to_f64(cv), rows=rows))                      # [len(rows), H_q, d]
     x1 = rb(x64[rows] + LO.linear(a.reshape(len(rows), hq * 128), ow["w_o"]))
@@ -409,8 +433,8 @@ def test_layer_text_chunk_and_decode_steps_after_video():
     x = W.make_hidden(10, 16, dims.d_model, seed=5)
     pos = torch.cat([W.video_positions(10, 15)[:, :150], W.text_positions(10, 40)], dim=1).contiguous()
     got, caches, _ = _gpu_stack(dims, layers_t, x, pos, steps, None, None, "value_norm", 1.0)
-    want, want_caches = LO.layer_stack(to_f64(x), pos.numpy(), [_oracle_weights(w_, dims) for w_ in layers_t],
-                                       _oracle_shape(dims), steps, None, None, "value_norm", 1.0, store=LO.bf16_round)
+    want, want_caches = LO.layer_stack(to_f64(x), pos.numpy(), [oracle_weights(w_, dims) for w_ in layers_t],
+                                       oracle_shape(dims), steps, None, None, "value_norm", 1.0, store=LO.bf16_round)
     for base, n in steps:
         assert_layer_close(to_f64(got)[base:base + n], want[base:base + n], f"tokens {base}..{base + n - 1}", layers=2)
     for l, (cache, (ck, cv, cp)) in enumerate(zip(caches, want_caches)):

@@ -1,14 +1,19 @@
-"""GPU tests of the feed (include/qp_feed.h): a stack fed group by group from the host equals the same stack run
-directly, and the run time follows the overlap equation of Sec. 3.3."""
+"""GPU tests of the feed (include/qp_feed.h): a stack fed group by group from the host equals the layer oracle's
+stack and, bit for bit, the same stack driven directly; the run time follows the oracle's pipeline model and the
+equation of Sec. 3.3."""
 import time
 
 import numpy as np
 import pytest
 import torch
 
+from helpers import assert_layer_close, oracle_shape, oracle_weights
+from oracle import layer_oracle as LO
+from oracle import overlap_oracle as OO
 from oracle import qp_oracle as O
 from paper_2505_16175_amd import binding as B
 from paper_2505_16175_amd import workload as W
+from paper_2505_16175_amd.workload import to_f64
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -87,6 +92,56 @@ def test_fed_stack_equals_direct_stack():
             assert c.len == n and torch.equal(c.k, k) and torch.equal(c.v, v) and torch.equal(c.pos, p)
 
 
+def test_fed_stack_matches_the_layer_oracle():
+    """The fed run against the fp64 layer oracle (not against another GPU run): two layers, four groups with a
+    ragged last one, nothing pruned, so that no selection decision enters; outputs, cache rows and positions."""
+    dims = W.LayerDims(256, 384, 4, 2)
+    frames, tpf, gf = 11, 36, 3
+    bounds = O.group_bounds(frames, tpf, gf)
+    x = W.make_hidden(frames, tpf, dims.d_model)
+    stack = Stack(dims, 2, bounds, 1.0)
+    feed = B.Feed(2, stack.n_max * dims.d_model * 2)
+    try:
+        feed.stub_producer(x, [n * dims.d_model * 2 for _, n in bounds], 1000, 300)
+        stats = _consume(stack, feed, dims.d_model)
+        feed.stub_join()
+    finally:
+        feed.destroy()
+    assert stats["groups"] == len(bounds)
+    layers = [oracle_weights(wt.tensors, dims) for wt in stack.weights]          # generated on the GPU: read them back
+    want, want_caches = LO.layer_stack(to_f64(x), stack.pos.cpu().numpy(), layers, oracle_shape(dims), bounds, None, None,
+                                       "key_norm_small", 1.0, store=LO.bf16_round)
+    assert_layer_close(to_f64(stack.out), want, "fed stack output", layers=2)
+    for l, (cache, (ck, cv, cp)) in enumerate(zip(stack.caches, want_caches)):
+        assert cache.len == frames * tpf
+        np.testing.assert_array_equal(cache.pos.cpu().numpy()[:, :cache.len], cp)
+        assert_layer_close(to_f64(cache.k)[:, :cache.len], ck, f"layer {l} cached K", layers=l + 1)
+        assert_layer_close(to_f64(cache.v)[:, :cache.len], cv, f"layer {l} cached V", layers=l + 1)
+
+
+def test_consumer_that_fails_early_leaves_no_blocked_producer():
+    """The group function fails at group 1 of 8 with a ring of 2 slots: qp_feed_consume reports the failure, and the
+    stand-in loader, which was waiting for a free slot, ends instead of blocking destroy for ever."""
+    n_groups, nbytes = 8, 4096
+    src = torch.zeros(n_groups * nbytes, dtype=torch.uint8).pin_memory()
+    feed = B.Feed(2, nbytes)
+    bufs = [torch.empty(nbytes, dtype=torch.uint8, device=DEV) for _ in range(2)]
+
+    def fn(group, dev_ptr, n):
+        if group == 1:
+            raise B.QPError(B.QP_ERR_INVALID_ARG, "group function of the test")
+
+    t0 = time.perf_counter()
+    try:
+        feed.stub_producer(src, [nbytes] * n_groups, 0, 0)
+        with pytest.raises(B.QPError):
+            feed.consume(bufs[0], bufs[1], fn)
+        feed.stub_join()
+    finally:
+        feed.destroy()
+    assert time.perf_counter() - t0 < 10.0
+
+
 def test_group_larger_than_the_device_buffer_is_refused():
     feed = B.Feed(2, 1024)
     try:
@@ -129,7 +184,12 @@ def test_run_time_follows_the_overlap_equation(first_ms, group_ms):
     direct()
     t_prefill, t_last_group = direct()
     t_dec = first_ms + (n_groups - 1) * group_ms
-    expect = max(t_dec + t_last_group, t_prefill + first_ms)
+    expect = OO.overlap_total(t_dec, t_prefill, first_ms, t_last_group)
+    # the pipeline stepped group by group with the loader's schedule and equal shares of the measured prefill time
+    # (the last group measured on its own): the closed form is its lower bound and, for this steady loader, close to it
+    per_group = [(t_prefill - t_last_group) / (n_groups - 1)] * (n_groups - 1) + [t_last_group]
+    stepped = OO.pipeline_finish([first_ms + g * group_ms for g in range(n_groups)], per_group)
+    assert expect - 1e-9 <= stepped <= OO.sequential_total(t_dec, t_prefill)
     stack.reset()
     torch.cuda.synchronize()
     feed = B.Feed(3, n_g * dims.d_model * 2)
@@ -140,12 +200,13 @@ def test_run_time_follows_the_overlap_equation(first_ms, group_ms):
     finally:
         feed.destroy()
     print(f"t_prefill {t_prefill:.2f} ms, last group {t_last_group:.2f} ms, t_dec {t_dec:.2f} ms (producer took "
-          f"{producer_ms:.2f}); expected {expect:.2f} + delta, measured {stats['total_ms']:.2f} ms, waited "
+          f"{producer_ms:.2f}); equation {expect:.2f} + delta, stepped pipeline {stepped:.2f}, measured {stats['total_ms']:.2f} ms, waited "
           f"{stats['waited_ms']:.2f} ms (first group {stats['first_group_wait_ms']:.2f})", flush=True)
     assert stats["groups"] == n_groups
     # delta: one group's host->device copy (15 MB, 0.3 ms), launch and timer slack (observed 0.7-1.5 ms; the bound
     # leaves room for a noisy host). In the loader-bound case running the two sides one after the other adds 30 ms.
     assert expect - 2.0 <= stats["total_ms"] <= expect + 12.0
-    if t_dec + t_prefill - expect > 20.0:                       # where overlap has something to win, it is won
-        assert stats["total_ms"] < t_dec + t_prefill - 15.0
+    assert stepped - 2.0 <= stats["total_ms"] <= stepped + 12.0
+    if OO.sequential_total(t_dec, t_prefill) - expect > 20.0:   # where overlap has something to win, it is won
+        assert stats["total_ms"] < OO.sequential_total(t_dec, t_prefill) - 15.0
     assert abs(stats["first_group_wait_ms"] - first_ms) < 5.0
