@@ -167,10 +167,9 @@ qp_status qp_score_kv(const qp_layout* layout, qp_score_rule rule, const void* k
  *   group_token_base: video-token index of the group's first token (recorded in cache->pos)
  *   cache: rows K_g[I], V_g[I] are appended at [len, len+keep) of every head in ascending
  *     token order, pos gets group_token_base + I, then cache->len += keep (host side)
- *   kept_idx_or_null [H_kv][keep] int32: group-local kept indices, ascending (written if not NULL;
- *     if NULL the workspace holds them between the selection and the copy: H_kv*keep*4 bytes)
- * Errors: INVALID_ARG, UNSUPPORTED, CAPACITY (len + keep > capacity, or workspace too small);
- * on any error the cache is untouched. */
+ *   kept_idx_or_null [H_kv][keep] int32: group-local kept indices, ascending (written if not NULL)
+ *   workspace, workspace_bytes: not used (selection and copy are one launch); may be NULL / 0
+ * Errors: INVALID_ARG, UNSUPPORTED, CAPACITY (len + keep > capacity); on any error the cache is untouched. */
 qp_status qp_topk_compact(const qp_layout* layout, const float* scores, const void* k_g, const void* v_g,
                           int32_t n_group_tokens, int32_t keep, int32_t group_token_base, qp_cache* cache,
                           int32_t* kept_idx_or_null, void* workspace, size_t workspace_bytes, void* hip_stream);

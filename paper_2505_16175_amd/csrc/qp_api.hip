@@ -375,13 +375,8 @@ qp_status qp_topk_compact(const qp_layout* L, const float* scores, const void* k
   if (kept_idx && (((uintptr_t)kept_idx) & 3u)) return QP_ERR_INVALID_ARG;
   if (keep < 1 || keep > n_g || group_token_base < 0) return QP_ERR_INVALID_ARG;
   if ((int64_t)cache->len + keep > cache->capacity) return QP_ERR_CAPACITY;
-  // the kept indices pass from the selection to the copy through the caller's buffer or the workspace
-  int32_t* kept_ws = kept_idx;
-  if (kept_ws == nullptr) {
-    if (!workspace || (((uintptr_t)workspace) & 255u)) return QP_ERR_INVALID_ARG;
-    if (workspace_bytes < qp::topk_workspace_bytes(L->n_kv_heads, keep)) return QP_ERR_CAPACITY;
-    kept_ws = (int32_t*)workspace;
-  }
+  (void)workspace;  // selection and copy are one launch: the kept indices never leave the kernel unless asked for
+  (void)workspace_bytes;
 
   qp::TopkArgs a;
   a.scores = scores;
@@ -397,7 +392,7 @@ qp_status qp_topk_compact(const qp_layout* L, const float* scores, const void* k
   a.base = group_token_base;
   a.cap = cache->capacity;
   a.len = cache->len;
-  st = finish(qp::launch_topk_compact(a, L->dtype, kept_ws, (hipStream_t)hip_stream));
+  st = finish(qp::launch_topk_compact(a, L->dtype, kept_idx, (hipStream_t)hip_stream));
   if (st == QP_OK) cache->len += keep;
   return st;
 }
@@ -442,7 +437,6 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
   const size_t kv_tok = (size_t)L->n_kv_heads * L->head_dim * esz;
   float* scores = (float*)workspace;
   const size_t sb = scores_bytes(L, (int32_t)max_group);
-  int32_t* kept_ws = (int32_t*)((char*)workspace + sb);
   const size_t kb = qp::topk_workspace_bytes(L->n_kv_heads, (int32_t)max_group);
   void* ws2 = (char*)workspace + sb + kb;  // window scratch, then the two key-split areas of the attention streams
   const size_t ws2_bytes = workspace_bytes - sb - kb - MAX_ATT_STREAMS * kAttendSplitBytes;
@@ -484,7 +478,7 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
     //    The appended rows [len, len+k) are disjoint from the rows [0, len) any attention kernel in flight reads.
     st = qp_score_kv(L, rule, kg, vg, n_g, q_win, n_window, scores, ws2, ws2_bytes, score_stream);
     if (st != QP_OK) break;
-    st = qp_topk_compact(L, scores, kg, vg, n_g, (int32_t)qp_keep_count(n_g, retention), base, cache, kept_ws, ws2,
+    st = qp_topk_compact(L, scores, kg, vg, n_g, (int32_t)qp_keep_count(n_g, retention), base, cache, nullptr, ws2,
                          ws2_bytes, score_stream);
     if (st != QP_OK) break;
     if (overlap) QP_HIP_OK(hipEventRecord(g_side.compacted[gi & 1], g_side.score));

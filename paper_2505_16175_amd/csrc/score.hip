@@ -292,7 +292,8 @@ static void launch_window_t(const WindowArgs& a, hipStream_t s) {
 }
 
 void launch_score_window(const WindowArgs& a, int dtype, hipStream_t s) {
-  if (window_mfma_supported(dtype, a.h_q, a.h_kv, a.d, a.w)) {
+  // the MFMA kernels form 32-bit byte offsets into the group's K
+  if (window_mfma_supported(dtype, a.h_q, a.h_kv, a.d, a.w) && (long long)a.n_g * a.h_kv * (a.d * 2) < (1ll << 31)) {
     launch_score_window_mfma(a, s);
     return;
   }

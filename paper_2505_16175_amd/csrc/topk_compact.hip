@@ -1,10 +1,11 @@
-// TopK of Eq. 2 (Sec. 3.2) per KV head, and compaction K~ = K_g[I], V~ = V_g[I] into the cache.
+// TopK of Eq. 2 (Sec. 3.2) per KV head, and compaction K~ = K_g[I], V~ = V_g[I] into the cache, in ONE launch.
 //
-// Two launches on the same stream:
-//   topk_select_kernel     one workgroup per KV head; exact selection on order-preserving 32-bit keys
-//                          held in LDS; writes the kept indices (ascending) and the cache positions.
-//   compact_gather_kernel  pure copy: 16-byte vector loads/stores, one row (d elements) per
-//                          d*sizeof/16 lanes, four rows per lane group in flight, 64 rows per workgroup.
+// topk_compact_kernel: grid (slices, KV heads). Every workgroup of a head finds the head's selection threshold
+// itself, on order-preserving 32-bit keys held in LDS (the head's scores are a few tens of KB and come from L2, so
+// repeating the search costs less than a second launch or a wait between workgroups), and then handles only its own
+// slice of the group's tokens: it ranks the slice's survivors, writes their indices and cache positions, and copies
+// their K and V rows (16-byte vector loads/stores, d*sizeof/16 lanes per row, all loads of a batch in flight before
+// the first store). Copies of early workgroups overlap the searches of later ones.
 //
 // Selection = find the k-th largest key T and how many keys equal to T survive (`need`), then emit.
 //   * While loading, the workgroup takes the minimum and maximum key. A round spreads the current key
@@ -18,11 +19,11 @@
 //   * As soon as the bucket holds at most 256 keys they are copied to a list and ranked directly
 //     (every candidate counts the candidates above and equal to it). Otherwise another round runs on the
 //     bucket; a bucket of width one is exact. The width shrinks by 2^11 per round: at most 3 rounds.
-//   * Emit: wavefront w owns a contiguous run of tokens and walks it 64 at a time; ballots give every
-//     survivor its rank inside the batch, running counts its slot. A token survives iff key > T, or
-//     key == T and fewer than `need` equal keys precede it: ties go to the lower index and the kept
-//     list comes out in ascending token order. A first sweep counts (greater, equal) per wavefront so
-//     that each one knows where its output starts.
+//   * Emit: a token survives iff key > T, or key == T and fewer than `need` equal keys precede it: ties go to
+//     the lower index and the kept list comes out in ascending token order. The workgroup counts the
+//     (greater, equal) keys before its slice, which fixes where the slice's survivors start; inside the slice
+//     wavefront w owns a contiguous run of tokens and walks it 64 at a time, ballots give every survivor its rank
+//     inside the batch, running counts its slot.
 #include "qp_internal.h"
 
 namespace qp {
@@ -34,8 +35,10 @@ constexpr int SEL_NB = 1 << SEL_BITS;  // buckets per round, two per thread
 constexpr int SEL_LIST = 256;          // a bucket of at most this many keys is ranked directly
 constexpr int SEL_UNROLL = 2;          // independent loads per thread and loop trip
 constexpr int SEL_MAX_ROUNDS = 4;      // 3 suffice for 32-bit keys; the bound makes termination explicit
-constexpr int GATHER_THREADS = 256;
-constexpr int GATHER_UNROLL = 4;
+constexpr int GATHER_UNROLL = 4;       // rows per lane group in flight in the copy
+constexpr int SLICE_MAX = 4096;        // tokens per slice at most (their survivors' indices sit in LDS)
+constexpr int SLICE_WANT_KEEP = 128;   // survivors per slice aimed for
+constexpr int SLICES_MAX = 16;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 static_assert(SEL_NB == 2 * TOPK_THREADS, "two buckets per thread");
 
@@ -45,15 +48,17 @@ __device__ __forceinline__ uint32_t order_key(float s) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // ascending in s
 }
 
-__global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(TopkArgs a, int32_t* __restrict__ kept_out) {
-  extern __shared__ uint32_t keys[];  // [n_g]
+template <typename T, int D>
+__global__ __launch_bounds__(TOPK_THREADS) void topk_compact_kernel(TopkArgs a, int32_t* __restrict__ kept_out, int slice_tokens) {
+  extern __shared__ uint32_t keys[];  // [n_g] keys, then [slice_tokens] kept token indices of this slice
   __shared__ __attribute__((aligned(8))) uint32_t hist[SEL_NB];
   __shared__ uint32_t list[SEL_LIST];
   __shared__ uint32_t wave_a[TOPK_WAVES], wave_b[TOPK_WAVES], wave_min[TOPK_WAVES], wave_max[TOPK_WAVES];
   __shared__ uint32_t sel_bucket, sel_need, sel_count, sel_key, list_n;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int h = blockIdx.x, n = a.n_g;
+  const int h = blockIdx.y, n = a.n_g;
+  uint32_t* sl_idx = keys + n;
   const float* s = a.scores + (size_t)h * n;
   uint32_t kmin = 0xffffffffu, kmax = 0u;
   for (int j0 = tid; j0 < n; j0 += SEL_UNROLL * TOPK_THREADS) {
@@ -185,9 +190,22 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(TopkArgs a, i
   }
   // thr: the k-th largest key; need: how many keys equal to it survive (>= 1)
 
-  // emit, wavefront by wavefront over contiguous runs of tokens
-  const int run = ((n + TOPK_WAVES - 1) / TOPK_WAVES + 63) / 64 * 64;
-  const int j_begin = min(wave * run, n), j_end = min(j_begin + run, n);
+  // this workgroup's slice of the tokens, and the (greater, equal) keys before it
+  const int s_begin = min((int)blockIdx.x * slice_tokens, n), s_end = min(s_begin + slice_tokens, n);
+  uint32_t gt_c = 0, eq_c = 0;
+  for (int j = tid; j < s_begin; j += TOPK_THREADS) {
+    const uint32_t key = keys[j];
+    gt_c += key > thr;
+    eq_c += key == thr;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    gt_c += (uint32_t)__shfl_xor((int)gt_c, o, 64);
+    eq_c += (uint32_t)__shfl_xor((int)eq_c, o, 64);
+  }
+  // emit, wavefront by wavefront over contiguous runs of the slice's tokens
+  const int run = ((s_end - s_begin + TOPK_WAVES - 1) / TOPK_WAVES + 63) / 64 * 64;
+  const int j_begin = min(s_begin + wave * run, s_end), j_end = min(j_begin + run, s_end);
   uint32_t gt_w = 0, eq_w = 0;
   for (int j0 = j_begin; j0 < j_end; j0 += 64 * SEL_UNROLL) {
     uint32_t kk[SEL_UNROLL];
@@ -200,19 +218,28 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(TopkArgs a, i
       eq_w += (uint32_t)__popcll(__ballot(in && kk[u] == thr));
     }
   }
+  __syncthreads();  // wave_a / wave_b of the threshold search are free again
   if (lane == 0) {
     wave_a[wave] = gt_w;
     wave_b[wave] = eq_w;
+    wave_min[wave] = gt_c;  // the counts before the slice, per wavefront
+    wave_max[wave] = eq_c;
   }
   __syncthreads();
-  uint32_t gt_before = 0, eq_run = 0;
+  uint32_t gt_before = 0, eq_before = 0, gt_run = 0, eq_run = 0, gt_slice = 0, eq_slice = 0;
 #pragma unroll
-  for (int w = 0; w < TOPK_WAVES - 1; ++w) {
-    gt_before += w < wave ? wave_a[w] : 0u;
+  for (int w = 0; w < TOPK_WAVES; ++w) {
+    gt_before += wave_min[w];
+    eq_before += wave_max[w];
+    gt_run += w < wave ? wave_a[w] : 0u;
     eq_run += w < wave ? wave_b[w] : 0u;
+    gt_slice += wave_a[w];
+    eq_slice += wave_b[w];
   }
-  uint32_t out_run = gt_before + min(eq_run, need);
-  int32_t* kept = kept_out + (size_t)h * a.keep;
+  const uint32_t out_base = gt_before + min(eq_before, need);  // slot of the slice's first survivor
+  const uint32_t n_slice = gt_slice + (min(eq_before + eq_slice, need) - min(eq_before, need));
+  eq_run += eq_before;
+  uint32_t out_run = gt_before + gt_run + min(eq_run, need);
   int32_t* pos = a.pos + (size_t)h * a.cap + a.len;
   const unsigned long long below = (1ull << lane) - 1ull;  // lanes before this one
   for (int j0 = j_begin; j0 < j_end; j0 += 64 * SEL_UNROLL) {
@@ -227,80 +254,86 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(TopkArgs a, i
       const bool keep_it = (j < j_end && kk[u] > thr) || (is_eq && eq_run + (uint32_t)__popcll(be & below) < need);
       const unsigned long long bs = __ballot(keep_it);
       const uint32_t slot = out_run + (uint32_t)__popcll(bs & below);
-      if (keep_it && slot < (uint32_t)a.keep) {  // slot < keep always holds; the check keeps the stores in bounds
-        kept[slot] = j;
+      // out_base <= slot < out_base + n_slice <= keep always holds; the checks keep the stores in bounds
+      if (keep_it && slot < (uint32_t)a.keep && slot - out_base < (uint32_t)slice_tokens) {
+        sl_idx[slot - out_base] = (uint32_t)j;
+        if (kept_out != nullptr) kept_out[(size_t)h * a.keep + slot] = j;
         pos[slot] = a.base + j;
       }
       out_run += (uint32_t)__popcll(bs);
       eq_run += (uint32_t)__popcll(be);
     }
   }
-}
+  __syncthreads();
 
-template <typename T, int D>
-__global__ __launch_bounds__(GATHER_THREADS) void compact_gather_kernel(TopkArgs a, const int32_t* __restrict__ kept_in) {
+  // copy the slice's survivors: row r of the slice goes to cache row len + out_base + r
   constexpr int PER = Elem<T>::kPer16B;
   constexpr int LPR = D / PER;  // lanes per row
-  constexpr int ROWS_PER_ITER = GATHER_THREADS / LPR;
-  const int tid = threadIdx.x, sub = tid % LPR;
-  const int h = blockIdx.y;
-  const int32_t* kept = kept_in + (size_t)h * a.keep;
+  constexpr int ROWS_PER_ITER = TOPK_THREADS / LPR;
+  const int sub = tid % LPR;
+  const int n_copy = (int)min(n_slice, (uint32_t)min(slice_tokens, a.keep - (int)min(out_base, (uint32_t)a.keep)));
   const T* gk = (const T*)a.k;
   const T* gv = (const T*)a.v;
-  T* ck = (T*)a.ck + ((size_t)h * a.cap + a.len) * D;
-  T* cv = (T*)a.cv + ((size_t)h * a.cap + a.len) * D;
-  const int rbase = blockIdx.x * (ROWS_PER_ITER * GATHER_UNROLL) + tid / LPR;
-  // four rows per lane group in flight: all loads are issued before the first store
-  u32x4 kk[GATHER_UNROLL], vv[GATHER_UNROLL];
+  T* ck = (T*)a.ck + ((size_t)h * a.cap + a.len + out_base) * D;
+  T* cv = (T*)a.cv + ((size_t)h * a.cap + a.len + out_base) * D;
+  for (int r0 = tid / LPR; r0 < n_copy; r0 += ROWS_PER_ITER * GATHER_UNROLL) {
+    u32x4 kk[GATHER_UNROLL], vv[GATHER_UNROLL];
 #pragma unroll
-  for (int u = 0; u < GATHER_UNROLL; ++u) {
-    const int r = rbase + u * ROWS_PER_ITER;
-    if (r < a.keep) {
-      const size_t src = ((size_t)kept[r] * a.h_kv + h) * D + sub * PER;
-      kk[u] = *(const u32x4*)(gk + src);
-      vv[u] = *(const u32x4*)(gv + src);
+    for (int u = 0; u < GATHER_UNROLL; ++u) {
+      const int r = r0 + u * ROWS_PER_ITER;
+      if (r < n_copy) {
+        const size_t src = ((size_t)sl_idx[r] * a.h_kv + h) * D + sub * PER;
+        kk[u] = *(const u32x4*)(gk + src);
+        vv[u] = *(const u32x4*)(gv + src);
+      }
     }
-  }
 #pragma unroll
-  for (int u = 0; u < GATHER_UNROLL; ++u) {
-    const int r = rbase + u * ROWS_PER_ITER;
-    if (r < a.keep) {
-      const size_t dst = (size_t)r * D + sub * PER;
-      *(u32x4*)(ck + dst) = kk[u];
-      *(u32x4*)(cv + dst) = vv[u];
+    for (int u = 0; u < GATHER_UNROLL; ++u) {
+      const int r = r0 + u * ROWS_PER_ITER;
+      if (r < n_copy) {
+        const size_t dst = (size_t)r * D + sub * PER;
+        *(u32x4*)(ck + dst) = kk[u];
+        *(u32x4*)(cv + dst) = vv[u];
+      }
     }
   }
 }
 
 size_t topk_workspace_bytes(int h_kv, int keep) { return ((size_t)h_kv * keep * sizeof(int32_t) + 255) / 256 * 256; }
 
-template <typename T, int D>
-static void launch_gather(const TopkArgs& a, const int32_t* kept, hipStream_t s) {
-  constexpr int ROWS_PER_WG = GATHER_THREADS / (D / Elem<T>::kPer16B) * GATHER_UNROLL;
-  hipLaunchKernelGGL((compact_gather_kernel<T, D>), dim3((a.keep + ROWS_PER_WG - 1) / ROWS_PER_WG, a.h_kv),
-                     dim3(GATHER_THREADS), 0, s, a, kept);
+// Tokens per slice: about SLICE_WANT_KEEP survivors each, at most SLICES_MAX slices, at most SLICE_MAX tokens, whole
+// batches of 64.
+static int slice_tokens_for(int n_g, int keep) {
+  int slices = (keep + SLICE_WANT_KEEP - 1) / SLICE_WANT_KEEP;
+  if (slices > SLICES_MAX) slices = SLICES_MAX;
+  const int at_least = (n_g + SLICE_MAX - 1) / SLICE_MAX;
+  if (slices < at_least) slices = at_least;
+  if (slices < 1) slices = 1;
+  return ((n_g + slices - 1) / slices + 63) / 64 * 64;  // <= SLICE_MAX: SLICE_MAX is a multiple of 64
 }
 
-// kept_ws: [h_kv][keep] int32 scratch for the kept indices (the caller's kept buffer or the workspace)
-hipError_t launch_topk_compact(const TopkArgs& a, int dtype, int32_t* kept_ws, hipStream_t s) {
-  const size_t lds_bytes = (size_t)a.n_g * sizeof(uint32_t);
+template <typename T, int D>
+static hipError_t launch_fused(const TopkArgs& a, int32_t* kept_out, hipStream_t s) {
+  const int slice_tokens = slice_tokens_for(a.n_g, a.keep);
+  const int slices = (a.n_g + slice_tokens - 1) / slice_tokens;
+  const size_t lds_bytes = ((size_t)a.n_g + slice_tokens) * sizeof(uint32_t);
   static bool attr_set[QP_MAX_DEVICES] = {};
   const int dev = current_device();
   if (dev < 0 || !attr_set[dev]) {
-    hipError_t e = hipFuncSetAttribute((const void*)topk_select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       QP_MAX_GROUP_TOKENS * (int)sizeof(uint32_t));
+    hipError_t e = hipFuncSetAttribute((const void*)topk_compact_kernel<T, D>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (QP_MAX_GROUP_TOKENS + SLICE_MAX) * (int)sizeof(uint32_t));
     if (e != hipSuccess) return e;
     if (dev >= 0) attr_set[dev] = true;
   }
-  hipLaunchKernelGGL(topk_select_kernel, dim3(a.h_kv), dim3(TOPK_THREADS), lds_bytes, s, a, kept_ws);
-  if (dtype == QP_F32) {
-    if (a.d == 64) launch_gather<float, 64>(a, kept_ws, s);
-    else launch_gather<float, 128>(a, kept_ws, s);
-  } else {
-    if (a.d == 64) launch_gather<bf16_t, 64>(a, kept_ws, s);
-    else launch_gather<bf16_t, 128>(a, kept_ws, s);
-  }
+  hipLaunchKernelGGL((topk_compact_kernel<T, D>), dim3(slices, a.h_kv), dim3(TOPK_THREADS), lds_bytes, s, a, kept_out,
+                     slice_tokens);
   return hipSuccess;
+}
+
+// kept_out: [h_kv][keep] int32 for the kept indices, or nullptr if the caller does not want them
+hipError_t launch_topk_compact(const TopkArgs& a, int dtype, int32_t* kept_out, hipStream_t s) {
+  if (dtype == QP_F32) return a.d == 64 ? launch_fused<float, 64>(a, kept_out, s) : launch_fused<float, 128>(a, kept_out, s);
+  return a.d == 64 ? launch_fused<bf16_t, 64>(a, kept_out, s) : launch_fused<bf16_t, 128>(a, kept_out, s);
 }
 
 }  // namespace qp

@@ -663,11 +663,17 @@ def test_capacity_and_unsupported_errors_leave_the_cache_alone():
     with pytest.raises(B.QPError) as e:
         B.topk_compact(layout, s, k, v, keep, n_g, cache, kept)          # 100 + 100 > 150
     assert e.value.status == B.QP_ERR_CAPACITY and cache.len == 100
-    with pytest.raises(B.QPError) as e:
-        B.topk_compact(layout, s, k, v, 20, n_g, cache, None, None)      # fits, but no kept buffer and no workspace
-    assert e.value.status == B.QP_ERR_INVALID_ARG and cache.len == 100
     torch.cuda.synchronize()
     assert torch.equal(cache.k, before[0]) and torch.equal(cache.pos, before[1])
+    # neither a kept-index buffer nor a workspace is needed: selection and copy are one launch
+    B.topk_compact(layout, s, k, v, 20, n_g, cache, None, None)
+    torch.cuda.synchronize()
+    assert cache.len == 120
+    want = O.topk_select(s.double().cpu().numpy(), 20)
+    np.testing.assert_array_equal(cache.pos.cpu().numpy()[:, 100:120], n_g + want)
+    for h in range(2):
+        assert torch.equal(cache.k[h, 100:120], k[torch.from_numpy(want[h]).to(DEV), h])
+        assert torch.equal(cache.k[h, :100], before[0][h, :100])
     # forcing the MFMA kernel on a layout it does not take is refused, the scalar kernel takes it
     l64 = B.make_layout(4, 2, 64, "bf16")
     q64 = torch.randn(16, 4, 64, device=DEV).bfloat16()
