@@ -149,6 +149,24 @@ qp_status qp_group_attend(const qp_layout* layout, const void* q_g, const void* 
                           int32_t n_group_tokens, const qp_cache* cache, void* out_g, float* lse_or_null,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* qp_group_attend for callers that cannot allocate or hand over scratch memory: code under HIP graph capture,
+ * tight serving loops (one decode step or one text chunk per call), harnesses that forbid hipMalloc. Same
+ * arguments and results as qp_group_attend without the workspace pair: the key split's partial results live in a
+ * device array of QP_NOALLOC_SCRATCH_BYTES that the library holds on every GPU it runs on until the process ends.
+ * The call allocates nothing and frees nothing. With a workspace of exactly QP_NOALLOC_SCRATCH_BYTES,
+ * qp_group_attend takes the same launch layout and returns the same bits.
+ *   Limit: n_group_tokens * H_q <= QP_NOALLOC_MAX_ROWS (decode steps and text chunks; a chunk of that many rows
+ *     leaves room for at least 8 key chunks), else QP_ERR_CAPACITY and nothing is launched.
+ *   The array keeps the previous call's contents; nothing in it needs clearing (every partial result is written
+ *     before the merge reads it). All calls on one GPU share the array: calls that may overlap on one GPU
+ *     (different streams, different host threads) race -- use qp_group_attend with distinct workspaces for those.
+ *   Other errors as qp_group_attend; QP_ERR_HIP if the array's device address cannot be obtained. */
+#define QP_NOALLOC_SCRATCH_BYTES (8u << 20)
+#define QP_NOALLOC_MAX_ROWS 2048
+qp_status qp_group_attend_noalloc(const qp_layout* layout, const void* q_g, const void* k_g, const void* v_g,
+                                  int32_t n_group_tokens, const qp_cache* cache, void* out_g, float* lse_or_null,
+                                  void* hip_stream);
+
 /* Importance scores of a group's new KV entries (the functions listed under Eq. 2).
  *   k_g, v_g as above (the norm rules read only the tensor they name; the other may be NULL)
  *   q_win [n_window][H_q][d]: the text-query window (the two WINDOW rules only, else ignored)

@@ -82,6 +82,7 @@ SIGNATURES = {
     "qp_keep_count": (_i64, [_i64, _f64]),
     "qp_cache_capacity": (_i64, [_i32, _i32, _i32, _f64]),
     "qp_debug_fail_after": (_i32, [_i32]),
+    "qp_group_attend_noalloc": (_i32, [_LP, _vp, _vp, _vp, _i32, _CP, _vp, _vp, _vp]),
     "qp_group_bounds": (_i32, [_i32, _i32, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32), _i32]),
     "qp_workspace_bytes": (_sz, [_LP, _i32, _i32]),
     "qp_group_attend": (_i32, [_LP, _vp, _vp, _vp, _i32, _CP, _vp, _vp, _vp, _sz, _vp]),
@@ -243,6 +244,17 @@ def group_attend(layout, q_g, k_g, v_g, cache: Optional[Cache], out_g, lse=None,
                                ctypes.byref(cache.c) if cache is not None else None, _ptr(out_g), _ptr(lse),
                                wp, wb, _stream())
     _check(st, "qp_group_attend")
+
+
+NOALLOC_SCRATCH_BYTES = 8 << 20
+NOALLOC_MAX_ROWS = 2048
+
+
+def group_attend_noalloc(layout, q_g, k_g, v_g, cache: Optional[Cache], out_g, lse=None):
+    st = lib().qp_group_attend_noalloc(ctypes.byref(layout), _ptr(q_g), _ptr(k_g), _ptr(v_g), q_g.shape[0],
+                                       ctypes.byref(cache.c) if cache is not None else None, _ptr(out_g), _ptr(lse),
+                                       _stream())
+    _check(st, "qp_group_attend_noalloc")
 
 
 def score_kv(layout, rule, k_g, v_g, q_win, scores, workspace=None):

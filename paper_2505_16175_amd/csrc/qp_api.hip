@@ -65,6 +65,33 @@ qp_status finish(hipError_t launch_err) {
   return QP_OK;
 }
 
+// Scratch of qp_group_attend_noalloc: one array per GPU that the library is loaded on, held until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress; the device address it yields (one per
+// device) is what launches and copies use.
+constexpr size_t kStaticScratchBytes = (size_t)QP_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+void* g_scratch_ptr[qp::QP_MAX_DEVICES] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of the current device's copy of `scratch` (looked up once per device), nullptr + status on failure.
+qp_status static_scratch(void** out) {
+  const int dev = qp::current_device();
+  if (dev < 0) return QP_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      g_last_hip_error = (int)(e != hipSuccess ? e : hipErrorInvalidSymbol);
+      return QP_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return QP_OK;
+}
+
 // Scratch that qp_group_attend's key split may use (partial outputs of the chunks); qp_prefill_video keeps one
 // area per attention stream, so that two groups' attention launches in flight never share one.
 constexpr size_t kAttendSplitBytes = (size_t)32 << 20;
@@ -256,6 +283,17 @@ qp_status qp_select_attend_kernel(int32_t which) {
   if (which != QP_ATTEND_AUTO && which != QP_ATTEND_SCALAR && which != QP_ATTEND_MFMA) return QP_ERR_INVALID_ARG;
   g_attend_kernel.store(which, std::memory_order_relaxed);
   return QP_OK;
+}
+
+qp_status qp_group_attend_noalloc(const qp_layout* L, const void* q_g, const void* k_g, const void* v_g, int32_t n_g,
+                                  const qp_cache* cache, void* out_g, float* lse, void* hip_stream) {
+  qp_status st = check_layout(L);
+  if (st != QP_OK) return st;
+  if ((st = check_group(n_g)) != QP_OK) return st;
+  if ((int64_t)n_g * L->n_q_heads > QP_NOALLOC_MAX_ROWS) return QP_ERR_CAPACITY;
+  void* ws = nullptr;
+  if ((st = static_scratch(&ws)) != QP_OK) return st;
+  return qp_group_attend(L, q_g, k_g, v_g, n_g, cache, out_g, lse, ws, kStaticScratchBytes, hip_stream);
 }
 
 qp_status qp_group_attend(const qp_layout* L, const void* q_g, const void* k_g, const void* v_g, int32_t n_g,
