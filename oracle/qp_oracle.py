@@ -188,6 +188,40 @@ def topk_select(scores, k):
 
 
 # --------------------------------------------------------------------------- #
+# Variant: the pruned cache kept in 8 bits per element
+# --------------------------------------------------------------------------- #
+def fp8_e4m3_round(x):
+    """Nearest value of the 8-bit E4M3 floating-point format, returned as float64.
+
+    The format (OCP 8-bit floating point, E4M3): 1 sign bit, 4 exponent bits with bias 7, 3 mantissa bits, no
+    infinities; normal values (1 + m/8) * 2^e for e in [-6, 8] (the largest, 1.75 * 2^8 = 448, because the code above
+    it is NaN), subnormal values (m/8) * 2^-6. Rounding is to nearest, ties to the even mantissa; magnitudes that
+    would round above 448 saturate to +-448 (a reading: the format also allows NaN there); NaN stays NaN.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    a = np.abs(x)
+    _, ex = np.frexp(a)                              # a = f * 2^ex, f in [0.5, 1): exponent of the leading bit is ex - 1
+    e = np.maximum(ex - 1, -6)                       # subnormals share the smallest normal exponent
+    quantum = np.ldexp(1.0, e - 3)                   # spacing of representable values in that binade
+    r = np.rint(a / quantum) * quantum               # np.rint rounds half to even; both operations are exact in float64
+    r = np.minimum(r, 448.0)
+    r = np.where(np.isnan(x), np.nan, r)
+    return np.copysign(r, x)
+
+
+CACHE_FORMATS = (None, "fp8_e4m3")
+
+
+def _store_cache_rows(rows, cache_format):
+    """Rows as the cache holds them: unchanged, or rounded to the cache's element format."""
+    if cache_format is None:
+        return rows
+    if cache_format == "fp8_e4m3":
+        return fp8_e4m3_round(rows)
+    raise ValueError(f"unknown cache format {cache_format!r}")
+
+
+# --------------------------------------------------------------------------- #
 # The whole path for one layer
 # --------------------------------------------------------------------------- #
 def select_all_groups(k, v, q_win, n_frames, tokens_per_frame, group_frames, retention, rule, scale=None):
@@ -204,23 +238,27 @@ def select_all_groups(k, v, q_win, n_frames, tokens_per_frame, group_frames, ret
     return out
 
 
-def gather_cache(k, v, selections, upto_group):
-    """Cache contents before group `upto_group`: K~ [H_kv, C, d], V~ [H_kv, C, d], pos [H_kv, C]."""
+def gather_cache(k, v, selections, upto_group, cache_format=None):
+    """Cache contents before group `upto_group`: K~ [H_kv, C, d], V~ [H_kv, C, d], pos [H_kv, C]. With a cache_format
+    the kept rows are rounded to it when they enter the cache (what later groups attend to)."""
     k = np.asarray(k)
     h_kv, d = k.shape[1], k.shape[2]
     ks, vs, ps = [], [], []
     for base, n_g, idx, _ in selections[:upto_group]:
         pos = base + idx                                                   # [H_kv, k_g] global token index
-        ks.append(np.stack([k[pos[h], h, :] for h in range(h_kv)]))
-        vs.append(np.stack([v[pos[h], h, :] for h in range(h_kv)]))
+        ks.append(_store_cache_rows(np.stack([k[pos[h], h, :] for h in range(h_kv)]), cache_format))
+        vs.append(_store_cache_rows(np.stack([v[pos[h], h, :] for h in range(h_kv)]), cache_format))
         ps.append(pos)
     if not ks:
         return (np.zeros((h_kv, 0, d)), np.zeros((h_kv, 0, d)), np.zeros((h_kv, 0), dtype=np.int64))
     return np.concatenate(ks, axis=1), np.concatenate(vs, axis=1), np.concatenate(ps, axis=1)
 
 
-def prefill_video(q, k, v, q_win, n_frames, tokens_per_frame, group_frames, retention, rule, scale=None):
-    """One layer of QuickPrefill, group by group, in the order the method states.
+def prefill_video(q, k, v, q_win, n_frames, tokens_per_frame, group_frames, retention, rule, scale=None,
+                  cache_format=None):
+    """One layer of QuickPrefill, group by group, in the order the method states. cache_format: element format of
+    the pruned cache (None: the inputs' own; "fp8_e4m3": kept rows are rounded to 8 bits when they are stored; the
+    group's own K, V, which it attends to before pruning, and the scores are not affected).
 
     Returns O [N, H_q, d], cache K~ [H_kv, C_G, d], V~ [H_kv, C_G, d], pos [H_kv, C_G],
     and the per-group selections.
@@ -245,8 +283,10 @@ def prefill_video(q, k, v, q_win, n_frames, tokens_per_frame, group_frames, rete
         idx = topk_select(s, keep_count(n_g, retention))
         # 4. K~_g = K_g[I_g], V~_g = V_g[I_g] appended to the cache
         pos = base + idx
-        cache_k = np.concatenate([cache_k, np.stack([k[pos[h], h, :] for h in range(h_kv)])], axis=1)
-        cache_v = np.concatenate([cache_v, np.stack([v[pos[h], h, :] for h in range(h_kv)])], axis=1)
+        cache_k = np.concatenate([cache_k, _store_cache_rows(np.stack([k[pos[h], h, :] for h in range(h_kv)]),
+                                                             cache_format)], axis=1)
+        cache_v = np.concatenate([cache_v, _store_cache_rows(np.stack([v[pos[h], h, :] for h in range(h_kv)]),
+                                                             cache_format)], axis=1)
         cache_pos = np.concatenate([cache_pos, pos], axis=1)
         selections.append((base, n_g, idx, s))
     return out, cache_k, cache_v, cache_pos, selections

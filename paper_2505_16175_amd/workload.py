@@ -13,7 +13,7 @@ available here.
 Recipe for one layer, independently for Q, K and V (frame f, token slot t, head h):
 
     x[0, t, h, :] = eps                                    eps ~ N(0, 1) i.i.d.
-    x[f, t, h, :] = a * x[f-1, t, h, :] + b * eps          inter-frame correlation
+    x[f, t, h, :] = a * x[f-1, t, h, :] + b * eps          inter-frame correlation (summed by doubling)
     K[n, :, :]   *= exp(sigma * z_n),  z_n ~ N(0, 1)       per-token log-normal key scale
     Q, K, V      /= sqrt(head_dim)
     Q_win[w, h, :] = N(0, 1) / sqrt(head_dim)              text-query window, uncorrelated
@@ -91,14 +91,18 @@ def scaled(w: Workload, **kw) -> Workload:
 
 
 def _ar1(gen, n_frames, tokens_per_frame, n_heads, head_dim, a, b, device):
-    out = torch.empty(n_frames, tokens_per_frame, n_heads, head_dim, dtype=torch.float32, device=device)
-    prev = torch.randn(tokens_per_frame, n_heads, head_dim, generator=gen, dtype=torch.float32, device=device)
-    out[0] = prev
-    for f in range(1, n_frames):
-        eps = torch.randn(tokens_per_frame, n_heads, head_dim, generator=gen, dtype=torch.float32, device=device)
-        prev = a * prev + b * eps
-        out[f] = prev
-    return out.view(n_frames * tokens_per_frame, n_heads, head_dim)
+    """x[0] = eps[0], x[f] = a x[f-1] + b eps[f], i.e. x[f] = sum_j a^j u[f-j] with u[0] = eps[0], u[f] = b eps[f].
+    Summed by doubling (after the pass with stride s every frame holds the terms j < 2s), so a video of F frames
+    takes log2(F) passes over the tensor instead of F small ones."""
+    x = torch.randn(n_frames, tokens_per_frame, n_heads, head_dim, generator=gen, dtype=torch.float32, device=device)
+    x[1:] *= b
+    stride = 1
+    while stride < n_frames:
+        nxt = x.clone()
+        torch.add(x[stride:], x[:-stride], alpha=a ** stride, out=nxt[stride:])
+        x = nxt
+        stride *= 2
+    return x.view(n_frames * tokens_per_frame, n_heads, head_dim)
 
 
 def make_layer(w: Workload, layer: int = 0, device: str = "cpu", sharp: bool = False,

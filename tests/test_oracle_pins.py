@@ -392,3 +392,76 @@ def test_memory_models_match_paper_figures():
         assert abs(gib - float(value)) <= float(tol), (name, gib)
     # pruning shrinks the cache by 1/rho (Sec. 3.2)
     assert O.kv_cache_bytes(28, 1000, 8, 128, 2, retention=0.25) * 4 == O.kv_cache_bytes(28, 1000, 8, 128, 2)
+
+
+# --------------------------------------------------------------------------- the 8-bit cache variant
+def _e4m3_values():
+    """Every finite value of the format, decoded from its bit patterns by the format's definition."""
+    vals = []
+    for code in range(128):
+        e, m = code >> 3, code & 7
+        if e == 15 and m == 7:
+            continue                                           # NaN
+        vals.append((m / 8.0) * 2.0 ** -6 if e == 0 else (1 + m / 8.0) * 2.0 ** (e - 7))
+    return np.array(sorted(vals))
+
+
+def test_fp8_rounding_hand_cases():
+    for x, want, why in read_golden("fp8_e4m3_hand_cases.txt"):
+        got = float(O.fp8_e4m3_round(float(x)))
+        assert got == float(want), (x, got, want, why)
+        assert float(O.fp8_e4m3_round(-float(x))) == -float(want)        # odd symmetry
+
+
+def test_fp8_rounding_is_the_nearest_representable_value_ties_to_even():
+    vals = _e4m3_values()
+    assert len(vals) == 127 and vals[0] == 0.0 and vals[1] == 2.0 ** -9 and vals[-1] == 448.0
+    rng = np.random.default_rng(8)
+    x = np.concatenate([rng.standard_normal(4000) * 10.0 ** rng.integers(-4, 3, 4000), rng.uniform(-460, 460, 2000),
+                        (vals[:-1] + vals[1:]) / 2, vals])     # random values, every halfway point, every value itself
+    got = O.fp8_e4m3_round(x)
+    assert np.isin(np.abs(got), vals).all()
+    # brute force: nearest value by distance; at exact halfway points the one with the even code
+    a = np.minimum(np.abs(x), 448.0)
+    d = np.abs(a[:, None] - vals[None, :])
+    best = d.min(axis=1)
+    for i in range(len(x)):
+        cand = np.flatnonzero(d[i] == best[i])
+        pick = cand[0] if len(cand) == 1 else [c for c in cand if c % 2 == 0][0]   # index in the sorted table = code
+        assert abs(got[i]) == vals[pick], (x[i], got[i], vals[pick])
+    np.testing.assert_array_equal(O.fp8_e4m3_round(got), got)                       # idempotent
+    xs = np.sort(x)
+    assert (np.diff(O.fp8_e4m3_round(xs)) >= 0).all()                               # monotone
+    assert np.isnan(O.fp8_e4m3_round(np.nan))
+
+
+def test_fp8_rounding_matches_the_library_cast_inside_the_range():
+    rng = np.random.default_rng(9)
+    x = np.concatenate([rng.standard_normal(20000) * 10.0 ** rng.integers(-4, 3, 20000), rng.uniform(-448, 448, 5000)])
+    x = x[np.abs(x) <= 448.0].astype(np.float32)                # the library cast does not saturate; inside the range they agree
+    want = torch.tensor(x).to(torch.float8_e4m3fn).to(torch.float64).numpy()
+    np.testing.assert_array_equal(O.fp8_e4m3_round(x.astype(np.float64)), want)
+
+
+def test_fp8_cache_rounds_stored_rows_only():
+    """With the 8-bit cache the kept sets, the first group's outputs and the group's own keys are untouched; the cache
+    holds the rounded rows, and later groups attend to exactly those."""
+    from paper_2505_16175_amd.workload import CONFIGS, make_layer, scaled, to_f64
+    w = scaled(CONFIGS["cfg1_tiny_f32"], n_frames=6)
+    q, k, v, qw = (to_f64(t) for t in make_layer(w, sharp=True))
+    args = (w.n_frames, w.tokens_per_frame, w.group_frames, w.retention, "key_norm_small")
+    out, ck, cv, pos, sel = O.prefill_video(q, k, v, qw, *args)
+    out8, ck8, cv8, pos8, sel8 = O.prefill_video(q, k, v, qw, *args, cache_format="fp8_e4m3")
+    np.testing.assert_array_equal(pos8, pos)
+    np.testing.assert_array_equal(ck8, O.fp8_e4m3_round(ck))
+    np.testing.assert_array_equal(cv8, O.fp8_e4m3_round(cv))
+    n0 = w.group_tokens
+    np.testing.assert_array_equal(out8[:n0], out[:n0])                        # the first group sees no cache
+    assert np.abs(out8[n0:] - out[n0:]).max() > 1e-4                          # later groups see rounded rows
+    # later groups attend to the rounded cache and their own exact K, V
+    g1 = slice(n0, 2 * n0)
+    gk, gv, _ = O.gather_cache(k, v, sel8, 1, cache_format="fp8_e4m3")
+    np.testing.assert_array_equal(gk, ck8[:, :gk.shape[1]])
+    np.testing.assert_allclose(out8[g1], O.attend_group(q[g1], k[g1], v[g1], gk, gv), atol=1e-15)
+    # bytes: one per element instead of the inputs' (the bytes factor of the cache-memory equation of App. D.2)
+    assert O.kv_cache_bytes(1, pos.shape[1], w.n_kv_heads, w.head_dim, 1) * 2 == O.kv_cache_bytes(1, pos.shape[1], w.n_kv_heads, w.head_dim, 2)

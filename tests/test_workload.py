@@ -35,3 +35,17 @@ def test_recipe_statistics():
     assert np.corrcoef(kn[:, 0], kn[:, 1])[0, 1] > 0.9
     # bf16 values widen exactly
     assert np.array_equal(to_f64(q).astype(np.float32), q.float().numpy())
+
+
+def test_frame_recursion_summed_by_doubling_equals_the_sequential_recursion():
+    # the generator sums x[f] = a x[f-1] + b eps[f] by doubling; same innovations, sequential recursion, same values
+    import torch
+    from paper_2505_16175_amd import workload as W
+    a, b, frames = 0.9, 0.44, 37                                  # not a power of two
+    x = W._ar1(torch.Generator().manual_seed(3), frames, 3, 2, 4, a, b, "cpu").view(frames, 3, 2, 4)
+    eps = torch.randn(frames, 3, 2, 4, generator=torch.Generator().manual_seed(3))
+    ref = torch.empty_like(eps)
+    ref[0] = eps[0]
+    for f in range(1, frames):
+        ref[f] = a * ref[f - 1] + b * eps[f]
+    assert (x - ref).abs().max() < 1e-5
