@@ -1,18 +1,24 @@
 #!/usr/bin/env python3
 """Benchmark of the QuickPrefill hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg2_7b_32k] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config NAME] [--no-cpu-baseline] [--grid] ...
 
-One step = one pass of the whole path (group attention + scoring + top-k/compaction for every
-group) over one layer of the named synthetic workload, through qp_prefill_video of the C ABI,
-inputs already resident in HBM. Prints ONE JSON line:
-  value      video tokens prefilled per second per layer over the K timed steps
-  roofline   the group-attention kernel (dominant): useful flops of a launch / its average
-             duration (HIP events around every qp_group_attend launch of an instrumented replay
-             of the same K steps, on the stream the kernels run on) against the bf16 MFMA peak
-  stages     per-stage times of the instrumented replay, and the HBM-side figures of the
-             score / top-k+compact kernels at their real per-group shapes
-  cpu_baseline  the fp64 oracle timed on the host on a bounded sample of the same workload
+One step = one pass of the whole path (group attention + scoring + top-k/compaction for every group of every layer)
+over the named synthetic workload, through qp_prefill_video of the C ABI, inputs already resident in HBM. Without
+--config the headline is the largest config, cfg5_7b_hour_stack (28 layers, every layer's inputs and pruned cache
+resident), and the line also carries a `configs` array with all five configs. Prints ONE JSON line:
+  value         video tokens prefilled per second per layer over the K timed steps
+  roofline      the group-attention kernel (dominant): useful flops of a launch / its average duration (HIP events
+                around every qp_group_attend launch of a serial replay of layer 0, on the stream the kernels run on)
+                against the bf16 MFMA peak; whole_step_frac = all layers' attention flops / ms_per_step; traffic =
+                HBM bytes per launch from the rocprofv3 counter summary under profiles/
+  stages        per-stage times of the replay, the HBM-side figures of the score / top-k+compact kernels at their
+                real per-group shapes and at a bandwidth-characterisation shape, the stages that consume the cache
+  cpu_baseline  the fp64 oracle timed on the host on a bounded sample of the same workload (projected layer time)
+  near_tie      kept sets of the GPU against the oracle's: identical / excused near-ties / mismatches
+  configs       per config: ms per step, tokens/s/layer, attention fraction of peak, score and top-k GB/s, near-tie
+                counts, final cache length, resident cache bytes, and the oracle's projected rate
+  table2_grid   the points of the paper's Table 2 ablation grid as throughput on config 2's video
 """
 import argparse
 import json
@@ -27,11 +33,8 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+PEAK_EXP_PER_S = 256 * 4 * 4 * 2.4e9   # v_exp_f32: a wavefront instruction takes 16 cycles on a 16-lane SIMD
 
-# HBM bytes per launch of the attention kernel (FETCH_SIZE + WRITE_SIZE of rocprofv3 --pmc, averaged over
-# the launches of this benchmark and scaled by the same counters' reading on the calibration copy below);
-# figures and commands are in profiles/.
-MEASURED_TRAFFIC = {"cfg2_7b_32k": 56.8e6, "cfg3_7b_128k_norm": 186.4e6, "cfg4_72b_128k": 435.9e6}
 CAL_COPY_BYTES = 256 << 20
 
 
@@ -127,10 +130,13 @@ def characterise_hbm(torch, B, reps=6):
     out["score_window_logit"] = {"shape": f"{h} KV heads x {r} query heads x {win} window rows x {n_g} tokens",
                                  "bytes": nbytes, "us": tl * 1e6, "GBps": nbytes / tl / 1e9,
                                  "frac_of_hbm_peak": nbytes / tl / 1e9 / PEAK_HBM_GBS}
-    flops = 2 * 2.0 * h * r * win * n_g * d
+    flops = 2.0 * h * r * win * n_g * d          # the method's one-pass minimum; the kernels do two passes
+    n_exp = 2.0 * h * r * win * n_g              # one exponential per (row, key) and pass
     out["score_window"] = {"shape": f"{h} KV heads x {r} query heads x {win} window rows x {n_g} tokens",
-                           "flops_two_pass": flops, "us": t * 1e6, "TFLOPs": flops / t / 1e12,
-                           "frac_of_mfma_peak": flops / t / 1e12 / PEAK_BF16_TFLOPS, "bytes": nbytes,
+                           "flops_one_pass": flops, "us": t * 1e6, "one_pass_TFLOPs": flops / t / 1e12,
+                           "frac_of_mfma_peak_one_pass": flops / t / 1e12 / PEAK_BF16_TFLOPS,
+                           "bound": "alu (exp2 at a quarter of the vector rate: 256 CUs x 4 SIMDs x 4 lanes x 2.4 GHz)",
+                           "exp_per_s": n_exp / t, "frac_of_exp_peak": n_exp / t / PEAK_EXP_PER_S, "bytes": nbytes,
                            "GBps": nbytes / t / 1e9, "frac_of_hbm_peak": nbytes / t / 1e9 / PEAK_HBM_GBS}
     return out
 
@@ -417,146 +423,164 @@ def run_stack(torch, B, w, rule, n_layers, steps, warmup, feed_ms=None):
     }))
 
 
-def cpu_baseline(w, q, k, v, qw, rule):
-    """The oracle on the host: all groups scored and selected, a sample of groups attended in full."""
-    import numpy as np  # noqa: F401
-    from oracle import qp_oracle as O
-    from paper_2505_16175_amd import binding as B
-    from paper_2505_16175_amd.workload import to_f64
+def _blas_threads():
     try:
         from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        return int(max([p.get("num_threads", 1) for p in threadpool_info()] or [1]))
     except Exception:
-        cores = os.cpu_count()
+        return int(os.cpu_count() or 1)
+
+
+def _boundary_rows(n_g, n_rows, rng):
+    """Group-token rows for the sampled oracle: first, last, both sides of tile boundaries, then random ones."""
+    rows = {0, n_g - 1}
+    for b in (32, 64, 128, 256, n_g // 2, n_g - 32):
+        for r in (b - 1, b):
+            if 0 <= r < n_g:
+                rows.add(r)
+    while len(rows) < min(n_g, n_rows):
+        rows.add(int(rng.integers(0, n_g)))
+    return sorted(rows)
+
+
+def cpu_baseline(w, q, k, v, qw, rule, gpu_pos=None, rows_per_group=64, full_below=40000):
+    """The oracle on the host, as it stands: every group scored and selected in full (scores need no attention), the
+    attention of a sample of groups evaluated in full (short videos) or on sampled rows (first, last, tile-boundary
+    and random rows of each sampled group), and the layer time projected from the measured (row, key) pairs per
+    second. If gpu_pos (the GPU's cache positions of the same layer) is given, the kept sets are compared: per
+    (group, head) identical, excused as a near-tie (every differing index has an oracle score within 1e-5 relative
+    of the k-th), or a mismatch."""
+    import numpy as np
+    from oracle import qp_oracle as O
+    from paper_2505_16175_amd.workload import to_f64
+    cores = _blas_threads()
     k64, v64 = to_f64(k), to_f64(v)
     qw64 = None if qw is None else to_f64(qw)
     t0 = time.perf_counter()
     sel = O.select_all_groups(k64, v64, qw64, w.n_frames, w.tokens_per_frame, w.group_frames, w.retention, rule)
     t_sel = time.perf_counter() - t0
-    bounds = B.group_bounds(w.n_frames, w.tokens_per_frame, w.group_frames)
+    bounds = [(b, n) for b, n, _, _ in sel]
     g = len(bounds)
+    near = None
+    if gpu_pos is not None:
+        lo = identical = excused = mismatched = 0
+        for base, n_g, idx, sc in sel:
+            kk = idx.shape[1]
+            got = gpu_pos[:, lo:lo + kk] - base
+            lo += kk
+            for h in range(idx.shape[0]):
+                if np.array_equal(got[h], idx[h]):
+                    identical += 1
+                    continue
+                diff = np.setxor1d(got[h], idx[h])
+                s_k = np.sort(sc[h])[::-1][kk - 1]
+                ok = diff.min() >= 0 and diff.max() < n_g and (np.abs(sc[h][diff] - s_k) < 1e-5 * abs(s_k)).all()
+                excused += bool(ok)
+                mismatched += not ok
+        near = {"group_heads": g * k64.shape[1], "identical": identical, "near_tie_excused": excused,
+                "mismatched": mismatched, "rule": "relative score gap < 1e-5 to the k-th oracle score"}
     # attention cost is linear in the group index; this sample's mean index equals the full run's
     sample = sorted({0, g - 1} | ({(g - 1) // 3, g - 1 - (g - 1) // 3} if g >= 4 else set())) if g > 1 else [0]
+    rng = np.random.default_rng(7)
+    full = w.n_tokens <= full_below
     t_att, pairs = 0.0, 0.0
     for gi in sample:
         base, n_g = bounds[gi]
+        rows = None if full else _boundary_rows(n_g, rows_per_group, rng)
         ck, cv, _ = O.gather_cache(k64, v64, sel, gi)
         qg = to_f64(q[base:base + n_g])
         t0 = time.perf_counter()
-        O.attend_group(qg, k64[base:base + n_g], v64[base:base + n_g], ck, cv)
+        O.attend_group(qg, k64[base:base + n_g], v64[base:base + n_g], ck, cv, rows=rows)
         t_att += time.perf_counter() - t0
-        pairs += n_g * ck.shape[1] + n_g * (n_g + 1) / 2.0
-    total_pairs = 0.0
-    c = 0
+        c = ck.shape[1]
+        pairs += (n_g * c + n_g * (n_g + 1) / 2.0) if rows is None else float(sum(c + r + 1 for r in rows))
+    total_pairs, c = 0.0, 0
     for (base, n_g), (_, _, idx, _) in zip(bounds, sel):
         total_pairs += n_g * c + n_g * (n_g + 1) / 2.0
         c += idx.shape[1]
     projected = t_sel + t_att * total_pairs / pairs
-    return {"value": w.n_tokens / projected, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"fp64 numpy oracle: all {g} groups scored+selected ({t_sel:.2f} s), groups {sample} attended "
-                      f"in full ({t_att:.2f} s); layer time projected by visible (row,key) pairs "
-                      f"({pairs:.3g} of {total_pairs:.3g})",
-            "projected_layer_seconds": projected}
+    what = "attended in full" if full else f"attended on {rows_per_group} sampled rows each (first, last, tile-boundary, random)"
+    out = {"value": w.n_tokens / projected, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+           "sample": f"fp64 numpy oracle, one layer: all {g} groups scored+selected ({t_sel:.2f} s), groups {sample} {what} "
+                     f"({t_att:.2f} s); layer time projected by visible (row,key) pairs ({pairs:.3g} of {total_pairs:.3g})",
+           "projected": True, "projected_layer_seconds": projected, "measured_seconds": t_sel + t_att}
+    return out, near
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="cfg2_7b_32k")
-    ap.add_argument("--rule", default=None)
-    ap.add_argument("--layers", type=int, default=None,
-                    help="layers of a stacked config to run per step (default: all of the config's; inputs and the "
-                         "pruned cache of every layer stay resident in HBM)")
-    ap.add_argument("--group-frames", type=int, default=None,
-                    help="frames per group instead of the config's (the group-size axis of the paper's Table 2 grid)")
-    ap.add_argument("--retention", type=float, default=None,
-                    help="KV retention ratio rho instead of the config's (the other axis of that grid)")
-    ap.add_argument("--graph", action="store_true",
-                    help="capture one step (every layer's qp_prefill_video, library streams included) into a HIP graph "
-                         "and time its replays: removes the host's launch cost, which bounds configs of many small groups")
-    ap.add_argument("--stack", type=int, default=None, metavar="LAYERS",
-                    help="instead of the headline path, run the config's video through a stack of this many decoder "
-                         "layers around the path (group-major, each layer feeding the next) and print that line")
-    ap.add_argument("--feed", type=float, nargs=2, default=None, metavar=("FIRST_MS", "GROUP_MS"),
-                    help="with --stack: also run the stack fed group by group from host memory by a stand-in loader "
-                         "(first group after FIRST_MS, one more every GROUP_MS) and report the overlapped run time")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--mfma-probe", action="store_true",
-                    help="run the stand-alone matrix-pipe probe (bf16 MFMA rate with constant / random operands) and exit")
-    args = ap.parse_args()
-    if args.mfma_probe:
-        import subprocess
-        from paper_2505_16175_amd.build import PROBE_PATH
-        sys.exit(subprocess.run([PROBE_PATH]).returncode)
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
-        sys.exit(2)
+def read_traffic_table():
+    """HBM bytes per launch of the attention kernel per config, from the rocprofv3 counter summary kept under
+    profiles/ (written by paper_2505_16175_amd/profile_summary.py from FETCH_SIZE / WRITE_SIZE runs of this file)."""
+    path = os.path.join(ROOT, "profiles", "attend_hbm_traffic.txt")
+    table = {}
+    if os.path.exists(path):
+        for line in open(path):
+            parts = line.split("|")
+            if len(parts) >= 2 and not line.startswith("#"):
+                try:
+                    table[parts[0].strip()] = float(parts[1])
+                except ValueError:
+                    pass
+    return table
 
-    import torch
-    from paper_2505_16175_amd import binding as B
-    from paper_2505_16175_amd.workload import CONFIGS, make_layer
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
-    torch.cuda.set_device(0)
-    w = CONFIGS[args.config]
-    if args.group_frames is not None or args.retention is not None:
-        import dataclasses
-        w = dataclasses.replace(w, group_frames=args.group_frames or w.group_frames,
-                                retention=args.retention or w.retention)
-    rule = args.rule or w.rules[0]
-    if args.stack is not None:
-        run_stack(torch, B, w, rule, args.stack, min(args.steps, 3), min(args.warmup, 1), args.feed)
-        return
-    n_layers = args.layers or w.n_layers
+def measure_config(torch, B, w, rule, steps, warmup, n_layers, replay_steps, graph=False, traffic=None):
+    """Timed steps of the whole path on one config (every layer's inputs and pruned cache resident in HBM), then an
+    instrumented serial replay of layer 0 with HIP events around every launch group. Returns (result, keep) where
+    keep holds what the CPU-baseline leg needs (layer 0's inputs and cache positions)."""
+    from paper_2505_16175_amd.workload import make_layer
     layers = [make_layer(w, layer=l, device="cuda") for l in range(n_layers)]
     q, k, v, qw = layers[0]
     layout = B.make_layout(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
     cap = B.cache_capacity(w.n_frames, w.tokens_per_frame, w.group_frames, w.retention)
     caches = [B.Cache(layout, cap) for _ in range(n_layers)]   # every layer's pruned cache stays resident
     cache = caches[0]
-    ws = B.make_workspace(layout, w.group_tokens, w.n_window)
+    ws = B.make_workspace(layout, min(w.group_tokens, w.n_tokens), w.n_window)
     out = torch.empty_like(q)                                  # the layer output is consumed and overwritten
-    qwin = qw if rule.startswith("window") else None
+    windowed = rule.startswith("window")
+    qwin = qw if windowed else None
 
     def step():
         for (lq, lk, lv, lqw), c in zip(layers, caches):
             c.reset()
             B.prefill_video(layout, w.n_frames, w.tokens_per_frame, w.group_frames, w.retention, rule, lq, lk, lv,
-                            lqw if rule.startswith("window") else None, c, out, ws)
+                            lqw if windowed else None, c, out, ws)
 
-    for _ in range(args.warmup):
+    print(f"[bench] {w.name} ({rule}): {n_layers} layer(s) generated, warm-up", file=sys.stderr, flush=True)
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    if args.graph:
+    if graph:
         eager_step = step
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
+        gobj = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gobj):
             eager_step()
-        step = graph.replay
+        step = gobj.replay
         step()
         torch.cuda.synchronize()
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t0 = time.perf_counter()
     marks[0].record()
-    for i in range(args.steps):
+    for i in range(steps):
         step()
         marks[i + 1].record()     # on the caller's stream, which every step rejoins before it returns
+        if n_layers > 1:          # long steps: say where the run is (the host runs at most a queue's depth ahead)
+            print(f"[bench] {w.name}: step {i + 1}/{steps} enqueued, {time.perf_counter() - t0:.1f} s", file=sys.stderr,
+                  flush=True)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
-    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
-    value = w.n_tokens * n_layers * args.steps / elapsed      # tokens per second per layer
+    ms_per_step = elapsed / steps * 1e3
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
+    value = w.n_tokens * n_layers * steps / elapsed           # tokens per second per layer
+    pos_layer0 = cache.pos[:, :cache.len].cpu().numpy()
+    final_len = cache.len
     resident_cache_bytes = sum(c.nbytes() for c in caches)
+    cache_bytes_per_layer = cache.nbytes()
 
-    # ---- instrumented replay of the same steps: HIP events around every launch group of the path
+    # ---- instrumented replay of layer 0, one launch group after the other on one stream: HIP events around each
     bounds = B.group_bounds(w.n_frames, w.tokens_per_frame, w.group_frames)
     score_bufs = {n: torch.empty(w.n_kv_heads, n, dtype=torch.float32, device="cuda") for _, n in set(bounds)}
     ev = []
-    for _ in range(args.steps):
+    for _ in range(replay_steps):
         cache.reset()
         for base, n_g in bounds:
             sl = slice(base, base + n_g)
@@ -584,57 +608,217 @@ def main():
         tb += topk_bytes(w, n_g, keep)
     n_launch = len(ev)
     achieved = fl / t_att / 1e12
+    flops_per_layer = fl / replay_steps
+    whole_step = flops_per_layer * n_layers / (ms_per_step * 1e-3) / 1e12
     roofline = {"kernel": "attend_mfma_kernel (qp_group_attend)", "bound": "mfma", "achieved": achieved,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                "traffic": MEASURED_TRAFFIC.get(w.name) if w == CONFIGS[args.config] else None,
-                "launches": n_launch, "avg_launch_us": t_att / n_launch * 1e6,
-                "flops_per_launch_avg": fl / n_launch}
+                "traffic": None if traffic is None else traffic.get(w.name),
+                "traffic_source": "profiles/attend_hbm_traffic.txt (rocprofv3 FETCH_SIZE + WRITE_SIZE per launch, scaled "
+                                  "by a plain copy; a snapshot taken with the committed kernels, not measured in this run)",
+                "launches": n_launch, "avg_launch_us": t_att / n_launch * 1e6, "flops_per_launch_avg": fl / n_launch,
+                "measured": f"HIP events around every qp_group_attend launch of a serial replay of layer 0 ({replay_steps} "
+                            "step(s), one stream, after the timed steps); the timed steps overlap consecutive groups' "
+                            "launches on two streams, so whole_step_frac (all layers' attention flops / ms_per_step) "
+                            "can exceed frac",
+                "whole_step_achieved": whole_step, "whole_step_frac": whole_step / PEAK_BF16_TFLOPS}
     if w.dtype == "f32":
         roofline.update({"kernel": "attend_scalar_kernel (qp_group_attend)", "bound": "alu", "peak": 157.3,
-                         "frac": achieved / 157.3})
+                         "frac": achieved / 157.3, "whole_step_frac": whole_step / 157.3})
     stages = {
-        "attend_ms_per_step": t_att / args.steps * 1e3,
-        "score_ms_per_step": t_sc / args.steps * 1e3,
-        "topk_compact_ms_per_step": t_tk / args.steps * 1e3,
+        "attend_ms_per_step": t_att / replay_steps * 1e3 * n_layers,
+        "score_ms_per_step": t_sc / replay_steps * 1e3 * n_layers,
+        "topk_compact_ms_per_step": t_tk / replay_steps * 1e3 * n_layers,
         "score": {"bound": "mfma" if rule.startswith("window_attn") else "hbm", "avg_launch_us": t_sc / n_launch * 1e6,
                   "algorithmic_GBps": sb / t_sc / 1e9, "frac_of_hbm_peak": sb / t_sc / 1e9 / PEAK_HBM_GBS},
         "topk_compact": {"bound": "hbm", "avg_launch_us": t_tk / n_launch * 1e6,
                          "algorithmic_GBps": tb / t_tk / 1e9, "frac_of_hbm_peak": tb / t_tk / 1e9 / PEAK_HBM_GBS},
-        "note": "score/top-k figures are at the real per-group shapes (a few MB per launch: latency-bound)",
+        "note": "serial replay of layer 0 scaled to the config's layers; score/top-k figures are at the real per-group "
+                "shapes (a few MB per launch: latency-bound; the bandwidth figures are under hbm_characterisation)",
     }
-
-    if rule.startswith("window_attn"):   # two passes of 2 H_q W N_g d flops each
-        wf = sum(2 * 2.0 * w.n_q_heads * w.n_window * n_g * w.head_dim for _, _, n_g, _ in ev)
-        stages["score"].update({"TFLOPs": wf / t_sc / 1e12, "frac_of_mfma_peak": wf / t_sc / 1e12 / PEAK_BF16_TFLOPS})
-
+    if rule.startswith("window_attn"):   # the method's one-pass minimum 2 H_q W N_g d; the kernels do two passes
+        wf = sum(2.0 * w.n_q_heads * w.n_window * n_g * w.head_dim for _, _, n_g, _ in ev)
+        stages["score"].update({"one_pass_TFLOPs": wf / t_sc / 1e12,
+                                "frac_of_mfma_peak_one_pass": wf / t_sc / 1e12 / PEAK_BF16_TFLOPS})
     result = {
-        "metric": "video tokens prefilled/sec per layer (attend+score+prune)",
-        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "ms_per_step_median": per_step[len(per_step) // 2],
-        "ms_per_step_min": per_step[0], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype, "data": "synthetic", "launch": "hip_graph_replay" if args.graph else "eager",
+        "ms_per_step": ms_per_step, "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
+        "value": value, "steps": steps, "warmup": warmup, "dtype": w.dtype,
         "config": {"workload": f"{w.name}: {w.n_q_heads}q/{w.n_kv_heads}kv heads x d{w.head_dim}, "
                                f"{w.n_frames} frames x {w.tokens_per_frame} tokens, group {w.group_frames} frames, "
-                               f"retention {w.retention}, rule {rule}, window {w.n_window if qwin is not None else 0}",
+                               f"retention {w.retention}, rule {rule}, window {w.n_window if windowed else 0}",
                    "n_tokens": w.n_tokens, "groups": len(bounds), "layers": n_layers,
-                   "final_cache_len_per_head": cache.len, "cache_bytes_per_layer": cache.nbytes(),
+                   "final_cache_len_per_head": final_len, "cache_bytes_per_layer": cache_bytes_per_layer,
                    "resident_cache_bytes": resident_cache_bytes},
         "roofline": roofline, "stages": stages,
     }
+    keep_for_cpu = dict(q=q, k=k, v=v, qw=qwin, pos=pos_layer0, layout=layout, cache=cache, ws=ws)
+    return result, keep_for_cpu
+
+
+TABLE2_GROUP_FRAMES = (4, 8, 16, 32, 64, 128)       # Table 2, "Varying Group Size" (rho 0.5)
+TABLE2_RETENTION = (1.0, 0.1, 0.2, 0.4, 0.6, 0.8, 0.9)  # Table 2, "Varying Retention Ratio" (groups of 16 frames)
+
+
+def table2_grid(torch, B, base_w, steps=10, warmup=2):
+    """The points of the paper's Table 2 ablation (Key Norms (small); group size 4-128 frames at rho 0.5, rho
+    0.1-1.0 at 16 frames) as throughput on config 2's synthetic video: what the grid costs, not what it scores
+    (the accuracies need the benchmark datasets and trained weights)."""
+    import dataclasses
+    points = [(g, 0.5) for g in TABLE2_GROUP_FRAMES] + [(16, r) for r in TABLE2_RETENTION]
+    out = []
+    for gf, rho in points:
+        w = dataclasses.replace(base_w, group_frames=gf, retention=rho)
+        res, keep = measure_config(torch, B, w, "key_norm_small", steps, warmup, 1, 1)
+        out.append({"group_frames": gf, "group_tokens": w.group_tokens, "retention": rho,
+                    "ms_per_layer": res["ms_per_step"], "tokens_per_s_per_layer": res["value"],
+                    "final_cache_len_per_head": res["config"]["final_cache_len_per_head"],
+                    "attend_frac_of_mfma_peak": res["roofline"]["frac"],
+                    "whole_step_frac_of_mfma_peak": res["roofline"]["whole_step_frac"]})
+        del keep
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default=None,
+                    help="run this config only (default: the headline on cfg5_7b_hour_stack, the largest config, plus a "
+                         "`configs` array with all five)")
+    ap.add_argument("--rule", default=None)
+    ap.add_argument("--layers", type=int, default=None,
+                    help="layers of a stacked config to run per step (default: all of the config's; inputs and the "
+                         "pruned cache of every layer stay resident in HBM)")
+    ap.add_argument("--group-frames", type=int, default=None,
+                    help="frames per group instead of the config's (the group-size axis of the paper's Table 2 grid)")
+    ap.add_argument("--retention", type=float, default=None,
+                    help="KV retention ratio rho instead of the config's (the other axis of that grid)")
+    ap.add_argument("--grid", action="store_true",
+                    help="run the points of the paper's Table 2 grid (group 4-128 frames at rho 0.5; rho 0.1-1.0 at 16 "
+                         "frames; Key Norms (small)) on config 2's video and print them as one JSON line")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step (every layer's qp_prefill_video, library streams included) into a HIP graph "
+                         "and time its replays: removes the host's launch cost, which bounds configs of many small groups")
+    ap.add_argument("--stack", type=int, default=None, metavar="LAYERS",
+                    help="instead of the headline path, run the config's video through a stack of this many decoder "
+                         "layers around the path (group-major, each layer feeding the next) and print that line")
+    ap.add_argument("--feed", type=float, nargs=2, default=None, metavar=("FIRST_MS", "GROUP_MS"),
+                    help="with --stack: also run the stack fed group by group from host memory by a stand-in loader "
+                         "(first group after FIRST_MS, one more every GROUP_MS) and report the overlapped run time")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip the other configs, the characterisation stages and the grid (profiling runs)")
+    ap.add_argument("--mfma-probe", action="store_true",
+                    help="run the stand-alone matrix-pipe probe (bf16 MFMA rate with constant / random operands) and exit")
+    args = ap.parse_args()
+    if args.mfma_probe:
+        import subprocess
+        from paper_2505_16175_amd.build import PROBE_PATH
+        sys.exit(subprocess.run([PROBE_PATH]).returncode)
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2505_16175_amd import binding as B
+    from paper_2505_16175_amd.workload import CONFIG_ORDER, CONFIGS
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    headline_name = args.config or "cfg5_7b_hour_stack"
+    w = CONFIGS[headline_name]
+    if args.group_frames is not None or args.retention is not None:
+        import dataclasses
+        w = dataclasses.replace(w, group_frames=args.group_frames or w.group_frames,
+                                retention=args.retention or w.retention)
+    rule = args.rule or w.rules[0]
+    if args.stack is not None:
+        run_stack(torch, B, w, rule, args.stack, min(args.steps, 3), min(args.warmup, 1), args.feed)
+        return
+    if args.grid:
+        print(json.dumps({"metric": "video tokens prefilled/sec per layer over the Table 2 grid (Key Norms (small))",
+                          "unit": "tokens/s", "n_gpus": 1, "data": "synthetic", "dtype": "bf16",
+                          "config": {"workload": "cfg2_7b_32k video, group size and retention varied"},
+                          "table2_grid": table2_grid(torch, B, CONFIGS["cfg2_7b_32k"])}))
+        return
+    traffic = read_traffic_table() if w == CONFIGS[headline_name] else None
+    all_configs = args.config is None and not args.headline_only and args.group_frames is None and args.retention is None
+
+    # the other configs first (small), so that the headline's 119 GB of inputs is not resident beside them
+    configs = []
+    if all_configs:
+        for name in CONFIG_ORDER:
+            if name == headline_name:
+                configs.append(None)
+                continue
+            cw = CONFIGS[name]
+            for crule in cw.rules:
+                res, keep = measure_config(torch, B, cw, crule, 10, 2, cw.n_layers, 2, traffic=traffic)
+                entry = _config_entry(name, crule, res)
+                if not args.no_cpu_baseline:
+                    entry["cpu_baseline"], entry["near_tie"] = cpu_baseline(cw, keep["q"], keep["k"], keep["v"], keep["qw"],
+                                                                            crule, keep["pos"], rows_per_group=48)
+                configs.append(entry)
+                del keep
+            torch.cuda.empty_cache()
+
+    n_layers = args.layers or w.n_layers
+    res, keep = measure_config(torch, B, w, rule, args.steps, args.warmup, n_layers, 1 if n_layers > 1 else min(args.steps, 10),
+                               graph=args.graph, traffic=traffic)
+    result = {
+        "metric": "video tokens prefilled/sec per layer (attend+score+prune)",
+        "value": res["value"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "ms_per_step_median": res["ms_per_step_median"],
+        "ms_per_step_min": res["ms_per_step_min"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic", "launch": "hip_graph_replay" if args.graph else "eager",
+        "config": res["config"], "roofline": res["roofline"], "stages": res["stages"],
+    }
+    if not args.no_cpu_baseline:
+        print(f"[bench] {w.name}: timed steps done, oracle on the host", file=sys.stderr, flush=True)
+        result["cpu_baseline"], near = cpu_baseline(w, keep["q"], keep["k"], keep["v"], keep["qw"], rule, keep["pos"])
+        if near is not None:
+            near["layers_checked"] = "layer 0 of %d (the GPU tests check every layer)" % n_layers
+        result["near_tie"] = near
+    if all_configs:
+        head_entry = _config_entry(headline_name, rule, res)
+        head_entry["cpu_baseline"] = result.get("cpu_baseline")
+        head_entry["near_tie"] = result.get("near_tie")
+        result["configs"] = [head_entry if c is None else c for c in configs]
     # calibration copy for the HBM counters: a plain device-to-device copy of known size (outside all timing)
     cal_src = torch.empty(CAL_COPY_BYTES // 4, dtype=torch.float32, device="cuda").normal_()
     cal_dst = torch.empty_like(cal_src)
     cal_dst.copy_(cal_src)
     torch.cuda.synchronize()
-    result["stages"]["hbm_characterisation"] = characterise_hbm(torch, B)
-    if w.dtype == "bf16":
-        result["stages"]["after_prefill"] = characterise_after_prefill(torch, B, w, layout, cache, ws)
-        layer = characterise_layer(torch, B, w, rule, cache.len // 2)
-        if layer is not None:
-            result["stages"]["decoder_layer"] = layer
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, q, k, v, qwin, rule)
+    del cal_src, cal_dst
+    if not args.headline_only:
+        print("[bench] characterisation stages", file=sys.stderr, flush=True)
+        layout, cache, ws = keep["layout"], keep["cache"], keep["ws"]
+        result["stages"]["hbm_characterisation"] = characterise_hbm(torch, B)
+        if w.dtype == "bf16":
+            result["stages"]["after_prefill"] = characterise_after_prefill(torch, B, w, layout, cache, ws)
+            layer = characterise_layer(torch, B, w, rule, cache.len // 2)
+            if layer is not None:
+                result["stages"]["decoder_layer"] = layer
+        if all_configs:
+            del keep
+            torch.cuda.empty_cache()
+            result["table2_grid"] = table2_grid(torch, B, CONFIGS["cfg2_7b_32k"], steps=5, warmup=1)
     print(json.dumps(result))
+
+
+def _config_entry(name, rule, res):
+    """One line of the `configs` array: what the benchmark definition asks to be reported per config."""
+    rf, st = res["roofline"], res["stages"]
+    return {"name": name, "rule": rule, "workload": res["config"]["workload"], "layers": res["config"]["layers"],
+            "ms_per_step": res["ms_per_step"], "tokens_per_s_per_layer": res["value"], "dtype": res["dtype"],
+            "attend": {"bound": rf["bound"], "TFLOPs": rf["achieved"], "frac": rf["frac"],
+                       "whole_step_frac": rf["whole_step_frac"], "avg_launch_us": rf["avg_launch_us"],
+                       "traffic": rf["traffic"]},
+            "score": st["score"], "topk_compact": st["topk_compact"],
+            "final_cache_len_per_head": res["config"]["final_cache_len_per_head"],
+            "resident_cache_bytes": res["config"]["resident_cache_bytes"]}
 
 
 if __name__ == "__main__":

@@ -55,14 +55,31 @@ __global__ __launch_bounds__(512) void overlap_loop(float* out, int iters, int m
     for (int r = 0; r < 16; ++r) acc[n][r] = 0.f;
   float v[16];
   for (int i = 0; i < 16; ++i) v[i] = seed * (lane + i);
+  // mode bit 16: wavefronts 4..7 run their vector block BEFORE their MFMAs (opposite phase order to wavefronts 0..3);
+  // mode bit 32: a workgroup barrier per iteration (what a shared tile ring imposes)
+  const bool valu_first = (mode & 16) && !lo;
+  const bool barrier = mode & 32;
+  const int barrier_every = (mode & 64) ? 2 : ((mode & 128) ? 4 : 1);  // with bit 32: a barrier every that many iterations
   for (int it = 0; it < iters; ++it) {
+    if (do_valu && valu_first) {
+#pragma unroll
+      for (int rep = 0; rep < 2; ++rep)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          float x = fmaf(v[i], 0.999f, -0.25f);
+          x = __builtin_amdgcn_exp2f(x);
+          v[i] = fmaxf(x, v[(i + 1) & 15]) * 0.5f + 0.125f;
+        }
+      __builtin_amdgcn_sched_barrier(0);
+    }
     if (do_mfma) {
 #pragma unroll
       for (int k = 0; k < 8; ++k)
 #pragma unroll
         for (int n = 0; n < 4; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[n], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (do_valu) {
+    if (do_valu && !valu_first) {
 #pragma unroll
       for (int rep = 0; rep < 2; ++rep)
 #pragma unroll
@@ -73,6 +90,7 @@ __global__ __launch_bounds__(512) void overlap_loop(float* out, int iters, int m
         }
     }
     __builtin_amdgcn_sched_barrier(0);
+    if (barrier && (it + 1) % barrier_every == 0) __syncthreads();
   }
   float s = 0.f;
   for (int n = 0; n < 4; ++n)
@@ -127,12 +145,18 @@ int main() {
            flops / ms / 1e9 / 25.0);
   }
   // co-execution of MFMA and vector work on one SIMD
-  const int modes[] = {1, 2, 3, 5, 10, 9, 15};
+  const int modes[] = {1, 2, 3, 5, 10, 9, 15, 15 | 32, 15 | 32 | 64, 15 | 32 | 128, 15 | 16, 15 | 16 | 32, 15 | 16 | 32 | 64};
   const char* what[] = {"wavefronts 0-3: MFMAs, 4-7 idle", "wavefronts 4-7: vector block, 0-3 idle",
                         "wavefronts 0-3: MFMAs, 4-7: vector block", "all 8: MFMAs", "all 8: vector block",
-                        "wavefronts 0-3: MFMAs then vector block, 4-7 idle", "all 8: MFMAs then vector block"};
+                        "wavefronts 0-3: MFMAs then vector block, 4-7 idle", "all 8: MFMAs then vector block",
+                        "all 8: MFMAs then vector block, barrier per iteration",
+                        "all 8: MFMAs then vector block, barrier every 2nd",
+                        "all 8: MFMAs then vector block, barrier every 4th",
+                        "0-3: MFMAs then vector, 4-7: vector then MFMAs",
+                        "0-3: MFMAs then vector, 4-7: vector then MFMAs, barrier",
+                        "0-3: MFMAs then vector, 4-7: vector then MFMAs, barrier every 2nd"};
   const int it2 = 20000;
-  for (int m = 0; m < 7; ++m) {
+  for (int m = 0; m < 13; ++m) {
     hipEvent_t e0, e1;
     CHECK(hipEventCreate(&e0));
     CHECK(hipEventCreate(&e1));

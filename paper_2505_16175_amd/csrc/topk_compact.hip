@@ -33,7 +33,8 @@ constexpr int TOPK_WAVES = TOPK_THREADS / 64;
 constexpr int SEL_BITS = 11;
 constexpr int SEL_NB = 1 << SEL_BITS;  // buckets per round, two per thread
 constexpr int SEL_LIST = 256;          // a bucket of at most this many keys is ranked directly
-constexpr int SEL_UNROLL = 2;          // independent loads per thread and loop trip
+constexpr int SEL_UNROLL = 2;          // independent LDS reads per thread and loop trip
+constexpr int LOAD_UNROLL = 8;         // score loads per thread in flight while the keys are brought in
 constexpr int SEL_MAX_ROUNDS = 4;      // 3 suffice for 32-bit keys; the bound makes termination explicit
 constexpr int GATHER_UNROLL = 4;       // rows per lane group in flight in the copy
 constexpr int SLICE_MAX = 4096;        // tokens per slice at most (their survivors' indices sit in LDS)
@@ -61,12 +62,12 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_compact_kernel(TopkArgs a, 
   uint32_t* sl_idx = keys + n;
   const float* s = a.scores + (size_t)h * n;
   uint32_t kmin = 0xffffffffu, kmax = 0u;
-  for (int j0 = tid; j0 < n; j0 += SEL_UNROLL * TOPK_THREADS) {
-    float f[SEL_UNROLL];
+  for (int j0 = tid; j0 < n; j0 += LOAD_UNROLL * TOPK_THREADS) {
+    float f[LOAD_UNROLL];
 #pragma unroll
-    for (int u = 0; u < SEL_UNROLL; ++u) f[u] = j0 + u * TOPK_THREADS < n ? s[j0 + u * TOPK_THREADS] : 0.f;
+    for (int u = 0; u < LOAD_UNROLL; ++u) f[u] = j0 + u * TOPK_THREADS < n ? s[j0 + u * TOPK_THREADS] : 0.f;
 #pragma unroll
-    for (int u = 0; u < SEL_UNROLL; ++u)
+    for (int u = 0; u < LOAD_UNROLL; ++u)
       if (j0 + u * TOPK_THREADS < n) {
         const uint32_t key = order_key(f[u]);
         keys[j0 + u * TOPK_THREADS] = key;
@@ -301,11 +302,15 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_compact_kernel(TopkArgs a, 
 
 size_t topk_workspace_bytes(int h_kv, int keep) { return ((size_t)h_kv * keep * sizeof(int32_t) + 255) / 256 * 256; }
 
-// Tokens per slice: about SLICE_WANT_KEEP survivors each, at most SLICES_MAX slices, at most SLICE_MAX tokens, whole
-// batches of 64.
-static int slice_tokens_for(int n_g, int keep) {
+// Tokens per slice: about SLICE_WANT_KEEP survivors each, at most SLICES_MAX slices and about one workgroup per
+// compute unit over all heads, at most SLICE_MAX tokens, whole batches of 64.
+static int slice_tokens_for(int n_g, int keep, int h_kv) {
   int slices = (keep + SLICE_WANT_KEEP - 1) / SLICE_WANT_KEEP;
   if (slices > SLICES_MAX) slices = SLICES_MAX;
+  // every workgroup repeats the head's threshold search: with many heads there are enough workgroups without
+  // slicing, and more than one per compute unit only multiplies that search
+  const int per_head = device_cu_count() / h_kv;
+  if (slices > per_head) slices = per_head;
   const int at_least = (n_g + SLICE_MAX - 1) / SLICE_MAX;
   if (slices < at_least) slices = at_least;
   if (slices < 1) slices = 1;
@@ -314,7 +319,7 @@ static int slice_tokens_for(int n_g, int keep) {
 
 template <typename T, int D>
 static hipError_t launch_fused(const TopkArgs& a, int32_t* kept_out, hipStream_t s) {
-  const int slice_tokens = slice_tokens_for(a.n_g, a.keep);
+  const int slice_tokens = slice_tokens_for(a.n_g, a.keep, a.h_kv);
   const int slices = (a.n_g + slice_tokens - 1) / slice_tokens;
   const size_t lds_bytes = ((size_t)a.n_g + slice_tokens) * sizeof(uint32_t);
   static bool attr_set[QP_MAX_DEVICES] = {};
