@@ -63,15 +63,17 @@ def counter(directory, name):
     return per_kernel
 
 
-def calibration(per_kernel):
-    """Average reading of the counter for the 256 MiB calibration copy. Other plain copies of the run (the input
-    generator clones tensors of hundreds of MB to GB) are told apart by size: only dispatches that read between 0.3
-    and 1.5 times the copy's own KiB count are taken (a copy of exactly the same size reads the same)."""
-    vals = [x for k, v in per_kernel.items() if "copyBuffer" in k for x in v]
-    near = [x for x in vals if 0.3 * CAL_KIB <= x <= 1.5 * CAL_KIB]
-    if not near:
-        raise SystemExit("the calibration copy is not in the counter output")
-    return sum(near) / len(near)
+def calibration(fetch, write):
+    """Readings of the two counters for the 256 MiB calibration copy. The run holds other plain copies (the input
+    generator clones tensors of tens of MB to GB). WRITE_SIZE counts a plain copy's KiB one for one, so the
+    calibration copy (and any other copy of exactly its size, which reads the same) is found there by value; the
+    FETCH_SIZE run issued the same copies in the same order, so its reading is taken at the same positions."""
+    wv = [x for k, v in write.items() if "copyBuffer" in k for x in v]
+    fv = [x for k, v in fetch.items() if "copyBuffer" in k for x in v]
+    at = [i for i, x in enumerate(wv) if abs(x - CAL_KIB) <= 0.005 * CAL_KIB]
+    if not at or len(fv) != len(wv):
+        raise SystemExit("the calibration copy is not in the counter output (or the two runs differ in their copies)")
+    return sum(fv[i] for i in at) / len(at), sum(wv[i] for i in at) / len(at)
 
 
 def main():
@@ -117,7 +119,7 @@ def main():
 
     if args.fetch and args.write:
         f, w = counter(args.fetch, "FETCH_SIZE"), counter(args.write, "WRITE_SIZE")
-        cf, cw = calibration(f), calibration(w)
+        cf, cw = calibration(f, w)
         sf, sw = CAL_KIB / cf, CAL_KIB / cw
         out = [f"rocprofv3 HBM-side counters per dispatch (KiB), workload {args.name}, MI355X",
                "commands (from the repo root, TMPDIR=/tmp), one counter per run:",
