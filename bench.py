@@ -149,6 +149,7 @@ def characterise_after_prefill(torch, B, w, layout, cache, ws, reps=50):
     kernel) and a second launch merges; without scratch a single workgroup per row block walks the whole cache."""
     out = {}
     d, esz = w.head_dim, 2
+    cesz = cache.k.element_size()          # 1 for an 8-bit cache
     c = cache.len
     for name, n_g in (("decode_1_token", 1), ("text_prefill_%d_tokens" % max(w.n_window, 64), max(w.n_window, 64))):
         q = torch.randn(n_g, w.n_q_heads, d, device="cuda").to(torch.bfloat16) / d ** 0.5
@@ -167,7 +168,7 @@ def characterise_after_prefill(torch, B, w, layout, cache, ws, reps=50):
             e1.record()
             torch.cuda.synchronize()
             res[label] = e0.elapsed_time(e1) * 1e3 / reps
-        nbytes = 2 * w.n_kv_heads * (c + n_g) * d * esz + 2 * n_g * w.n_q_heads * d * esz
+        nbytes = 2 * w.n_kv_heads * (c * cesz + n_g * esz) * d + 2 * n_g * w.n_q_heads * d * esz
         flops = 4.0 * d * w.n_q_heads * (n_g * c + n_g * (n_g + 1) / 2)
         t = res["us"] * 1e-6
         res.update({"cache_len": c, "bytes": nbytes, "GBps": nbytes / t / 1e9,
@@ -523,7 +524,7 @@ def read_traffic_table():
     return table
 
 
-def measure_config(torch, B, w, rule, steps, warmup, n_layers, replay_steps, graph=False, traffic=None):
+def measure_config(torch, B, w, rule, steps, warmup, n_layers, replay_steps, graph=False, traffic=None, cache_fmt=0):
     """Timed steps of the whole path on one config (every layer's inputs and pruned cache resident in HBM), then an
     instrumented serial replay of layer 0 with HIP events around every launch group. Returns (result, keep) where
     keep holds what the CPU-baseline leg needs (layer 0's inputs and cache positions)."""
@@ -532,7 +533,7 @@ def measure_config(torch, B, w, rule, steps, warmup, n_layers, replay_steps, gra
     q, k, v, qw = layers[0]
     layout = B.make_layout(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
     cap = B.cache_capacity(w.n_frames, w.tokens_per_frame, w.group_frames, w.retention)
-    caches = [B.Cache(layout, cap) for _ in range(n_layers)]   # every layer's pruned cache stays resident
+    caches = [B.Cache(layout, cap, fmt=cache_fmt) for _ in range(n_layers)]   # every layer's pruned cache stays resident
     cache = caches[0]
     ws = B.make_workspace(layout, min(w.group_tokens, w.n_tokens), w.n_window)
     out = torch.empty_like(q)                                  # the layer output is consumed and overwritten
@@ -644,7 +645,8 @@ def measure_config(torch, B, w, rule, steps, warmup, n_layers, replay_steps, gra
         "value": value, "steps": steps, "warmup": warmup, "dtype": w.dtype,
         "config": {"workload": f"{w.name}: {w.n_q_heads}q/{w.n_kv_heads}kv heads x d{w.head_dim}, "
                                f"{w.n_frames} frames x {w.tokens_per_frame} tokens, group {w.group_frames} frames, "
-                               f"retention {w.retention}, rule {rule}, window {w.n_window if windowed else 0}",
+                               f"retention {w.retention}, rule {rule}, window {w.n_window if windowed else 0}"
+                               + (", pruned cache in 8-bit E4M3" if cache_fmt else ""),
                    "n_tokens": w.n_tokens, "groups": len(bounds), "layers": n_layers,
                    "final_cache_len_per_head": final_len, "cache_bytes_per_layer": cache_bytes_per_layer,
                    "resident_cache_bytes": resident_cache_bytes},
@@ -705,6 +707,8 @@ def main():
     ap.add_argument("--feed", type=float, nargs=2, default=None, metavar=("FIRST_MS", "GROUP_MS"),
                     help="with --stack: also run the stack fed group by group from host memory by a stand-in loader "
                          "(first group after FIRST_MS, one more every GROUP_MS) and report the overlapped run time")
+    ap.add_argument("--cache-format", choices=("same", "fp8_e4m3"), default="same",
+                    help="element format of the pruned cache: the inputs' own (default) or 8-bit E4M3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--headline-only", action="store_true",
                     help="skip the other configs, the characterisation stages and the grid (profiling runs)")
@@ -765,8 +769,11 @@ def main():
             torch.cuda.empty_cache()
 
     n_layers = args.layers or w.n_layers
+    cache_fmt = B.QP_CACHE_FP8_E4M3 if args.cache_format == "fp8_e4m3" else B.QP_CACHE_SAME
+    if cache_fmt:
+        traffic, args.no_cpu_baseline = None, True     # the counter table and the oracle leg are for the default format
     res, keep = measure_config(torch, B, w, rule, args.steps, args.warmup, n_layers, 1 if n_layers > 1 else min(args.steps, 10),
-                               graph=args.graph, traffic=traffic)
+                               graph=args.graph, traffic=traffic, cache_fmt=cache_fmt)
     result = {
         "metric": "video tokens prefilled/sec per layer (attend+score+prune)",
         "value": res["value"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -805,6 +812,14 @@ def main():
             del keep
             torch.cuda.empty_cache()
             result["table2_grid"] = table2_grid(torch, B, CONFIGS["cfg2_7b_32k"], steps=5, warmup=1)
+            # the 8-bit cache variant on config 2: same path, kept rows stored in E4M3 and widened when read
+            w2 = CONFIGS["cfg2_7b_32k"]
+            r8, k8 = measure_config(torch, B, w2, w2.rules[0], 10, 2, 1, 2, cache_fmt=B.QP_CACHE_FP8_E4M3)
+            result["stages"]["fp8_cache_variant"] = {
+                "workload": r8["config"]["workload"], "ms_per_step": r8["ms_per_step"],
+                "tokens_per_s_per_layer": r8["value"], "attend_frac_of_mfma_peak": r8["roofline"]["frac"],
+                "resident_cache_bytes": r8["config"]["resident_cache_bytes"],
+                "after_prefill": characterise_after_prefill(torch, B, w2, k8["layout"], k8["cache"], k8["ws"])}
     print(json.dumps(result))
 
 

@@ -54,6 +54,15 @@ typedef enum {
 
 typedef enum { QP_F32 = 0, QP_BF16 = 1 } qp_dtype;
 
+/* Element format of the pruned cache's K~ and V~. Sec. 3.2 prunes the cache to cut its memory; its bytes are
+ * 2 * L * tokens * n_h * d_h * bytes-per-element (the KV-cache memory equation of App. D.2). QP_CACHE_FP8_E4M3
+ * halves the last factor against bf16: kept rows are rounded to the 8-bit E4M3 format (OCP 8-bit floating point:
+ * 4 exponent bits with bias 7, 3 mantissa bits, no infinities, largest value 448; nearest, ties to even, values
+ * beyond +-448 saturate, NaN stays NaN) when qp_topk_compact stores them, and qp_group_attend widens them exactly
+ * when it reads them. The group's own K, V (attended to before pruning) and the scores are unaffected.
+ * Supported with bf16 layouts of head_dim 128. */
+typedef enum { QP_CACHE_SAME = 0, QP_CACHE_FP8_E4M3 = 1 } qp_cache_format;
+
 /* The three importance functions listed under Eq. 2 (Sec. 3.2). Larger score = kept first. */
 typedef enum {
   QP_SCORE_KEY_NORM_SMALL = 0, /* s = -||K_g[j,h,:]||_2  (the paper's default)                  */
@@ -92,11 +101,12 @@ typedef struct {
 /* The pruned KV cache of one layer (Sec. 3.2, "store the corresponding KV cache"):
  * the same number of entries `len` for every KV head, in ascending token order. */
 typedef struct {
-  void* k;          /* device, [n_kv_heads][capacity][head_dim], layout dtype            */
+  void* k;          /* device, [n_kv_heads][capacity][head_dim], layout dtype (or 1 byte per element, see format) */
   void* v;          /* device, [n_kv_heads][capacity][head_dim]                          */
   int32_t* pos;     /* device, [n_kv_heads][capacity]: video-token index of each entry   */
   int32_t capacity; /* entries per head the buffers can hold                             */
   int32_t len;      /* host: entries per head currently valid; updated by qp_topk_compact */
+  int32_t format;   /* qp_cache_format of k and v; 0 (QP_CACHE_SAME) = the layout's dtype */
 } qp_cache;
 
 /* ---- host arithmetic (no device work) ------------------------------------------------ */
@@ -115,6 +125,12 @@ int64_t qp_cache_capacity(int32_t n_frames, int32_t tokens_per_frame, int32_t gr
  * min(G, max_groups) entries of each HOST array that is not NULL. -1 on bad arguments. */
 int32_t qp_group_bounds(int32_t n_frames, int32_t tokens_per_frame, int32_t group_frames, int32_t* first_token,
                         int32_t* n_tokens, int32_t max_groups);
+
+/* The conversions of the 8-bit cache format (qp_cache_format) on the host, bit patterns in and out: the E4M3 code
+ * of a bf16 value (nearest, ties to even, saturating at +-448, NaN to the NaN code 0x7f | sign) -- the same routine
+ * the compaction kernel runs -- and a code's value as bf16 (exact). */
+uint8_t qp_e4m3_from_bf16(uint16_t bf16_bits);
+uint16_t qp_bf16_from_e4m3(uint8_t code);
 
 /* Bytes of workspace that every entry point accepts for groups of at most max_group_tokens
  * tokens and a query window of n_window rows (includes 2 x 32 MiB of key-split scratch for the

@@ -32,7 +32,10 @@ class qp_layout(ctypes.Structure):
 
 class qp_cache(ctypes.Structure):
     _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p), ("pos", ctypes.c_void_p),
-                ("capacity", ctypes.c_int32), ("len", ctypes.c_int32)]
+                ("capacity", ctypes.c_int32), ("len", ctypes.c_int32), ("format", ctypes.c_int32)]
+
+
+QP_CACHE_SAME, QP_CACHE_FP8_E4M3 = 0, 1
 
 
 class qp_attend_plan_info(ctypes.Structure):
@@ -82,6 +85,8 @@ SIGNATURES = {
     "qp_keep_count": (_i64, [_i64, _f64]),
     "qp_cache_capacity": (_i64, [_i32, _i32, _i32, _f64]),
     "qp_debug_fail_after": (_i32, [_i32]),
+    "qp_e4m3_from_bf16": (ctypes.c_uint8, [ctypes.c_uint16]),
+    "qp_bf16_from_e4m3": (ctypes.c_uint16, [ctypes.c_uint8]),
     "qp_group_attend_noalloc": (_i32, [_LP, _vp, _vp, _vp, _i32, _CP, _vp, _vp, _vp]),
     "qp_group_bounds": (_i32, [_i32, _i32, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32), _i32]),
     "qp_workspace_bytes": (_sz, [_LP, _i32, _i32]),
@@ -161,12 +166,15 @@ def make_layout(n_q_heads, n_kv_heads, head_dim, dtype, softmax_scale=0.0) -> qp
 class Cache:
     """Owner of the device buffers behind a qp_cache (torch allocates; the library only fills)."""
 
-    def __init__(self, layout: qp_layout, capacity: int, device="cuda"):
+    def __init__(self, layout: qp_layout, capacity: int, device="cuda", fmt=QP_CACHE_SAME):
+        """fmt = QP_CACHE_FP8_E4M3: K~ and V~ hold one E4M3 byte per element (torch.float8_e4m3fn is that format)."""
         dt = torch.float32 if layout.dtype == QP_F32 else torch.bfloat16
+        if fmt == QP_CACHE_FP8_E4M3:
+            dt = torch.float8_e4m3fn
         self.k = torch.zeros(layout.n_kv_heads, capacity, layout.head_dim, dtype=dt, device=device)
         self.v = torch.zeros_like(self.k)
         self.pos = torch.full((layout.n_kv_heads, capacity), -1, dtype=torch.int32, device=device)
-        self.c = qp_cache(self.k.data_ptr(), self.v.data_ptr(), self.pos.data_ptr(), capacity, 0)
+        self.c = qp_cache(self.k.data_ptr(), self.v.data_ptr(), self.pos.data_ptr(), capacity, 0, fmt)
 
     @property
     def len(self):

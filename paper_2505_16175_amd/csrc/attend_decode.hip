@@ -265,7 +265,8 @@ __global__ __launch_bounds__(DC_NW * 64) void attend_decode_kernel(AttendArgs a)
 }
 
 bool attend_decode_applies(const AttendArgs& a, int dtype) {
-  return attend_mfma_supported(a, dtype) && a.n_g * (a.h_q / a.h_kv) <= DC_MAX_ROWS;
+  // an 8-bit cache is read by the large kernel only (its key split serves decode-shaped calls then)
+  return attend_mfma_supported(a, dtype) && !a.cache_fp8 && a.n_g * (a.h_q / a.h_kv) <= DC_MAX_ROWS;
 }
 
 // Blocks per workgroup and workgroups per KV head: about one workgroup per compute unit in total, at least one

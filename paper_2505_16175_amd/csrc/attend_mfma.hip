@@ -169,6 +169,11 @@ __device__ __forceinline__ void pv_tile(const unsigned char* vt, const int (&v_a
   }
 }
 
+// F8: the cache's K~ and V~ hold one E4M3 byte per element (the pruned cache's 8-bit format). Their tiles cannot go
+// global -> LDS directly: every wavefront loads its share of a tile into registers one tile ahead (8 bytes per lane
+// and row), widens it exactly to bf16 and writes it to the ring slot in the same swizzled layout, so that everything
+// after the staging is the same code. The group's own tiles are bf16 and staged as usual.
+template <bool F8>
 __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
   constexpr int STAGES = MF_STAGES;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -224,8 +229,9 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
   const int t_begin = chunk * a.split_tiles;
   const int t_end = chunk == a.n_split - 1 ? n_tiles : t_begin + a.split_tiles;
 
-  const unsigned char* ck = (const unsigned char*)a.ck + (size_t)h * a.cap * (MF_D * 2);
-  const unsigned char* cv = (const unsigned char*)a.cv + (size_t)h * a.cap * (MF_D * 2);
+  constexpr int CROW = F8 ? MF_D : MF_D * 2;  // bytes of one cached row
+  const unsigned char* ck = (const unsigned char*)a.ck + (size_t)h * a.cap * CROW;
+  const unsigned char* cv = (const unsigned char*)a.cv + (size_t)h * a.cap * CROW;
   const unsigned char* gk = (const unsigned char*)a.k + (size_t)h * (MF_D * 2);
   const unsigned char* gv = (const unsigned char*)a.v + (size_t)h * (MF_D * 2);
   const unsigned gstride_b = (unsigned)a.h_kv * (MF_D * 2);
@@ -258,6 +264,43 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
     lds_dma16(vsrc_, r1_ + st_vc1, vdst_ + 1024);                                                              \
   }
 
+  // 8-bit cache tiles: this lane's 8-byte pieces of the pending tile (same keys and LDS positions as above; global
+  // chunk c of a row is 8 bytes at c * 8), and their widened form written to a ring slot
+  uint2 f8k0 = make_uint2(0, 0), f8k1 = f8k0, f8v0 = f8k0, f8v1 = f8k0;
+  auto f8_load = [&](int tile_) {
+    const int base_ = tile_ * MF_BN, last_ = a.c - 1;
+    const unsigned r0_ = (unsigned)min(base_ + st_key0, last_) * (unsigned)MF_D;
+    const unsigned r1_ = (unsigned)min(base_ + st_key1, last_) * (unsigned)MF_D;
+    f8k0 = *(const uint2*)(ck + r0_ + (st_kc0 >> 1));
+    f8k1 = *(const uint2*)(ck + r1_ + (st_kc1 >> 1));
+    f8v0 = *(const uint2*)(cv + r0_ + (st_vc0 >> 1));
+    f8v1 = *(const uint2*)(cv + r1_ + (st_vc1 >> 1));
+  };
+  auto widen8 = [](uint2 p) -> u32x4 {  // 8 E4M3 bytes -> 8 bf16 (the f32 values are exact; their high halves are the bf16)
+    const auto a0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)p.x, false), a1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)p.x, true);
+    const auto b0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)p.y, false), b1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)p.y, true);
+    u32x4 o;
+    o.x = (__float_as_uint(a0[0]) >> 16) | (__float_as_uint(a0[1]) & 0xffff0000u);
+    o.y = (__float_as_uint(a1[0]) >> 16) | (__float_as_uint(a1[1]) & 0xffff0000u);
+    o.z = (__float_as_uint(b0[0]) >> 16) | (__float_as_uint(b0[1]) & 0xffff0000u);
+    o.w = (__float_as_uint(b1[0]) >> 16) | (__float_as_uint(b1[1]) & 0xffff0000u);
+    return o;
+  };
+  auto f8_store = [&](int slot_) {
+    unsigned char* kdst_ = smem + slot_ * MF_SLOT + st_lds + lane * 16;
+    unsigned char* vdst_ = kdst_ + MF_TILE;
+    *(u32x4*)(kdst_) = widen8(f8k0);
+    *(u32x4*)(kdst_ + 1024) = widen8(f8k1);
+    *(u32x4*)(vdst_) = widen8(f8v0);
+    *(u32x4*)(vdst_ + 1024) = widen8(f8v1);
+  };
+  // stage tile `tile_` for slot `slot_`: cache tiles of an 8-bit cache go through registers (f8_store follows later)
+#define QP_STAGE(tile_, slot_)                    \
+  {                                               \
+    if (F8 && (tile_) < n_ct) f8_load(tile_);     \
+    else QP_ISSUE(tile_, slot_)                   \
+  }
+
   // fragment read addresses (bytes inside a tile)
   int k_addr[8];  // K fragment of d-step s: key l32 (+32 per block), chunk 2s+g at position (2s+g) ^ (l32 & 15)
 #pragma unroll
@@ -288,8 +331,12 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
   const bool need_mask = in_cache ? (a.c - (tile_)*MF_BN < MF_BN) : (gt0 + MF_BN - 1 > t_w_min);
 
   // each wavefront has 4 loads in flight per requested tile: vmcnt(4) = all but the newest tile have landed
-  QP_ISSUE(t_begin, 0)
-  if (t_begin + 1 < t_end) QP_ISSUE(t_begin + 1, 1)
+  QP_STAGE(t_begin, 0)
+  if (F8 && t_begin < n_ct) f8_store(0);
+  if (t_begin + 1 < t_end) {
+    QP_STAGE(t_begin + 1, 1)
+    if (F8 && t_begin + 1 < n_ct) f8_store(1);
+  }
   // Q^T operand: 8 k-steps of 16 d; this lane holds d = 16 s + 8 g .. + 7 of its row. Requested behind the first
   // tiles so that the two latencies overlap (short key chunks are mostly prologue).
   bf16x8 qf[8];
@@ -305,7 +352,7 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
     int slot = 0, slot2 = 2;  // ring positions of tile and tile + 2
     for (int tile = t_begin; tile < t_end; ++tile) {
       // slot of tile+2 = slot of tile-1: every wavefront finished reading it before the last barrier
-      if (tile + 2 < t_end) QP_ISSUE(tile + 2, slot2)
+      if (tile + 2 < t_end) QP_STAGE(tile + 2, slot2)
       QP_TILE_VIEW(tile)
       if (live) {
         const unsigned char* kt = smem + slot * MF_SLOT;
@@ -315,14 +362,22 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
         softmax_tile(st, need_mask, lim_local, g, c2, lazy, m_run, l_run, o, pf);
         pv_tile(kt + MF_TILE, v_addr, pf, o);
       }
-      // this wavefront's part of the next tile has landed in LDS (the tile after it may still be in flight)
-      if (tile + 2 < t_end) __builtin_amdgcn_s_waitcnt(MF_VMCNT4);
-      else __builtin_amdgcn_s_waitcnt(MF_VMCNT0);
+      if (F8) {
+        // the pending 8-bit tile was requested a whole tile ago: widen it into its slot (last read before the
+        // previous barrier); every request, direct ones included, is awaited here
+        if (tile + 2 < t_end && tile + 2 < n_ct) f8_store(slot2);
+        __builtin_amdgcn_s_waitcnt(MF_VMCNT0);
+      } else {
+        // this wavefront's part of the next tile has landed in LDS (the tile after it may still be in flight)
+        if (tile + 2 < t_end) __builtin_amdgcn_s_waitcnt(MF_VMCNT4);
+        else __builtin_amdgcn_s_waitcnt(MF_VMCNT0);
+      }
       __syncthreads();
       slot = slot == STAGES - 1 ? 0 : slot + 1;
       slot2 = slot2 == STAGES - 1 ? 0 : slot2 + 1;
     }
   }
+#undef QP_STAGE
 #undef QP_ISSUE
 #undef QP_TILE_VIEW
 
@@ -527,7 +582,9 @@ void launch_attend_mfma(const AttendArgs& a_in, void* split_ws, size_t split_ws_
   static bool attr_set[QP_MAX_DEVICES] = {};
   const int dev = current_device();
   if (dev < 0 || !attr_set[dev]) {
-    (void)hipFuncSetAttribute((const void*)attend_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+    (void)hipFuncSetAttribute((const void*)attend_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              MF_STAGES * MF_SLOT);
+    (void)hipFuncSetAttribute((const void*)attend_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                               MF_STAGES * MF_SLOT);
     if (dev >= 0) attr_set[dev] = true;
   }
@@ -543,7 +600,10 @@ void launch_attend_mfma(const AttendArgs& a_in, void* split_ws, size_t split_ws_
     a.part_o = (float*)split_ws;
     a.part_lse = a.part_o + (size_t)p.n_split * rows_total * MF_D;
   }
-  hipLaunchKernelGGL(attend_mfma_kernel, dim3(p.workgroups, p.n_split), dim3(MF_NT), MF_STAGES * MF_SLOT, s, a);
+  if (a.cache_fp8)
+    hipLaunchKernelGGL(attend_mfma_kernel<true>, dim3(p.workgroups, p.n_split), dim3(MF_NT), MF_STAGES * MF_SLOT, s, a);
+  else
+    hipLaunchKernelGGL(attend_mfma_kernel<false>, dim3(p.workgroups, p.n_split), dim3(MF_NT), MF_STAGES * MF_SLOT, s, a);
   if (p.n_split > 1) launch_attend_merge(a, s);
 }
 

@@ -7,6 +7,7 @@
 #include <atomic>
 #include <mutex>
 
+#include "fp8_e4m3.h"
 #include "qp_internal.h"
 
 namespace {
@@ -34,9 +35,11 @@ qp_status check_group(int32_t n_g) {
   return QP_OK;
 }
 
-qp_status check_cache(const qp_cache* c, bool required) {
+qp_status check_cache(const qp_layout* L, const qp_cache* c, bool required) {
   if (c == nullptr) return required ? QP_ERR_INVALID_ARG : QP_OK;
   if (c->capacity < 0 || c->len < 0 || c->len > c->capacity) return QP_ERR_INVALID_ARG;
+  if (c->format != QP_CACHE_SAME && c->format != QP_CACHE_FP8_E4M3) return QP_ERR_INVALID_ARG;
+  if (c->format == QP_CACHE_FP8_E4M3 && (L->dtype != QP_BF16 || L->head_dim != 128)) return QP_ERR_UNSUPPORTED;
   if (c->len > 0 || required) {
     if (c->k == nullptr || c->v == nullptr || !aligned16(c->k) || !aligned16(c->v)) return QP_ERR_INVALID_ARG;
   }
@@ -235,6 +238,10 @@ int32_t qp_group_bounds(int32_t n_frames, int32_t tokens_per_frame, int32_t grou
   return gi;
 }
 
+uint8_t qp_e4m3_from_bf16(uint16_t bf16_bits) { return (uint8_t)qp::bf16_to_e4m3(bf16_bits); }
+
+uint16_t qp_bf16_from_e4m3(uint8_t code) { return (uint16_t)qp::e4m3_to_bf16(code); }
+
 size_t qp_workspace_bytes(const qp_layout* L, int32_t max_group_tokens, int32_t n_window) {
   if (check_layout(L) != QP_OK || check_group(max_group_tokens) != QP_OK || n_window < 0) return 0;
   size_t b = scores_bytes(L, max_group_tokens);
@@ -302,7 +309,7 @@ qp_status qp_group_attend(const qp_layout* L, const void* q_g, const void* k_g, 
   qp_status st = check_layout(L);
   if (st != QP_OK) return st;
   if ((st = check_group(n_g)) != QP_OK) return st;
-  if ((st = check_cache(cache, false)) != QP_OK) return st;
+  if ((st = check_cache(L, cache, false)) != QP_OK) return st;
   if (workspace && (((uintptr_t)workspace) & 255u)) return QP_ERR_INVALID_ARG;
   if (!q_g || !k_g || !v_g || !out_g) return QP_ERR_INVALID_ARG;
   if (!aligned16(q_g) || !aligned16(k_g) || !aligned16(v_g) || !aligned16(out_g)) return QP_ERR_INVALID_ARG;
@@ -323,11 +330,13 @@ qp_status qp_group_attend(const qp_layout* L, const void* q_g, const void* k_g, 
   a.h_kv = L->n_kv_heads;
   a.d = L->head_dim;
   a.scale_log2 = scale_log2_of(L);
+  a.cache_fp8 = cache != nullptr && cache->format == QP_CACHE_FP8_E4M3 && a.c > 0;
 
   hipStream_t s = (hipStream_t)hip_stream;
   const bool mfma_ok = qp::attend_mfma_supported(a, L->dtype);
   const int which = g_attend_kernel.load(std::memory_order_relaxed);
   if (which == QP_ATTEND_MFMA && !mfma_ok) return QP_ERR_UNSUPPORTED;
+  if (a.cache_fp8 && (!mfma_ok || which == QP_ATTEND_SCALAR)) return QP_ERR_UNSUPPORTED;  // only the MFMA kernel reads it
   const size_t ws_bytes = workspace ? workspace_bytes : 0;
   if (mfma_ok && which == QP_ATTEND_AUTO && qp::attend_decode_applies(a, L->dtype))
     qp::launch_attend_decode(a, workspace, ws_bytes, s);
@@ -407,7 +416,7 @@ qp_status qp_topk_compact(const qp_layout* L, const float* scores, const void* k
   qp_status st = check_layout(L);
   if (st != QP_OK) return st;
   if ((st = check_group(n_g)) != QP_OK) return st;
-  if ((st = check_cache(cache, true)) != QP_OK) return st;
+  if ((st = check_cache(L, cache, true)) != QP_OK) return st;
   if (!scores || (((uintptr_t)scores) & 3u) || !k_g || !v_g || !aligned16(k_g) || !aligned16(v_g))
     return QP_ERR_INVALID_ARG;
   if (kept_idx && (((uintptr_t)kept_idx) & 3u)) return QP_ERR_INVALID_ARG;
@@ -430,6 +439,7 @@ qp_status qp_topk_compact(const qp_layout* L, const float* scores, const void* k
   a.base = group_token_base;
   a.cap = cache->capacity;
   a.len = cache->len;
+  a.cache_fp8 = cache->format == QP_CACHE_FP8_E4M3;
   st = finish(qp::launch_topk_compact(a, L->dtype, kept_idx, (hipStream_t)hip_stream));
   if (st == QP_OK) cache->len += keep;
   return st;
@@ -450,7 +460,7 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
   if (n_total > INT32_MAX) return QP_ERR_UNSUPPORTED;
   const int64_t max_group = (int64_t)(group_frames < n_frames ? group_frames : n_frames) * tokens_per_frame;
   if (max_group > QP_MAX_GROUP_TOKENS) return QP_ERR_UNSUPPORTED;
-  if ((st = check_cache(cache, true)) != QP_OK) return st;
+  if ((st = check_cache(L, cache, true)) != QP_OK) return st;
   if (!q || !k || !v || !out || !aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
     return QP_ERR_INVALID_ARG;
   if (window_rule && (!q_win || !aligned16(q_win) || n_window <= 0)) return QP_ERR_INVALID_ARG;

@@ -102,6 +102,7 @@ struct AttendArgs {
   void* out;          // [n_g][h_q][d]
   float* lse;         // [h_q][n_g] or nullptr
   int n_g, h_q, h_kv, d, c, cap;
+  int cache_fp8;      // 1: ck / cv hold one E4M3 byte per element (MFMA kernel only)
   float scale_log2;   // softmax scale * log2(e)
   // Key split of the MFMA kernel (few rows against a long cache): the cache tiles are dealt to n_split chunks of
   // split_tiles tiles, the last chunk also takes the group's own tiles; every chunk leaves a normalised partial
@@ -171,6 +172,7 @@ struct TopkArgs {
   void* cv;
   int32_t* pos;         // [h_kv][cap]
   int n_g, h_kv, d, keep, base, cap, len;
+  int cache_fp8;        // 1: ck / cv take one E4M3 byte per element (bf16 inputs only)
 };
 size_t topk_workspace_bytes(int h_kv, int keep);
 hipError_t launch_topk_compact(const TopkArgs& a, int dtype, int32_t* kept_ws, hipStream_t s);

@@ -24,6 +24,7 @@
 //     (greater, equal) keys before its slice, which fixes where the slice's survivors start; inside the slice
 //     wavefront w owns a contiguous run of tokens and walks it 64 at a time, ballots give every survivor its rank
 //     inside the batch, running counts its slot.
+#include "fp8_e4m3.h"
 #include "qp_internal.h"
 
 namespace qp {
@@ -277,6 +278,9 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_compact_kernel(TopkArgs a, 
   const T* gv = (const T*)a.v;
   T* ck = (T*)a.ck + ((size_t)h * a.cap + a.len + out_base) * D;
   T* cv = (T*)a.cv + ((size_t)h * a.cap + a.len + out_base) * D;
+  const bool to_fp8 = sizeof(T) == 2 && a.cache_fp8;  // 8-bit cache rows: one byte per element, 8 bytes per lane
+  unsigned char* ck8 = (unsigned char*)a.ck + ((size_t)h * a.cap + a.len + out_base) * D;
+  unsigned char* cv8 = (unsigned char*)a.cv + ((size_t)h * a.cap + a.len + out_base) * D;
   for (int r0 = tid / LPR; r0 < n_copy; r0 += ROWS_PER_ITER * GATHER_UNROLL) {
     u32x4 kk[GATHER_UNROLL], vv[GATHER_UNROLL];
 #pragma unroll
@@ -293,8 +297,22 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_compact_kernel(TopkArgs a, 
       const int r = r0 + u * ROWS_PER_ITER;
       if (r < n_copy) {
         const size_t dst = (size_t)r * D + sub * PER;
-        *(u32x4*)(ck + dst) = kk[u];
-        *(u32x4*)(cv + dst) = vv[u];
+        if (to_fp8) {
+          uint2 k8, v8;
+          k8.x = bf16_to_e4m3(kk[u].x & 0xffffu) | (bf16_to_e4m3(kk[u].x >> 16) << 8) |
+                 (bf16_to_e4m3(kk[u].y & 0xffffu) << 16) | (bf16_to_e4m3(kk[u].y >> 16) << 24);
+          k8.y = bf16_to_e4m3(kk[u].z & 0xffffu) | (bf16_to_e4m3(kk[u].z >> 16) << 8) |
+                 (bf16_to_e4m3(kk[u].w & 0xffffu) << 16) | (bf16_to_e4m3(kk[u].w >> 16) << 24);
+          v8.x = bf16_to_e4m3(vv[u].x & 0xffffu) | (bf16_to_e4m3(vv[u].x >> 16) << 8) |
+                 (bf16_to_e4m3(vv[u].y & 0xffffu) << 16) | (bf16_to_e4m3(vv[u].y >> 16) << 24);
+          v8.y = bf16_to_e4m3(vv[u].z & 0xffffu) | (bf16_to_e4m3(vv[u].z >> 16) << 8) |
+                 (bf16_to_e4m3(vv[u].w & 0xffffu) << 16) | (bf16_to_e4m3(vv[u].w >> 16) << 24);
+          *(uint2*)(ck8 + dst) = k8;  // dst counts elements = bytes here
+          *(uint2*)(cv8 + dst) = v8;
+        } else {
+          *(u32x4*)(ck + dst) = kk[u];
+          *(u32x4*)(cv + dst) = vv[u];
+        }
       }
     }
   }

@@ -219,3 +219,29 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                        timeout=120)
     assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_e4m3_conversions_match_the_oracle_for_every_input():
+    """The library's bf16 -> E4M3 conversion (the routine its compaction kernel runs, here through its host entry
+    point) against the oracle's rounding for all 65536 bf16 bit patterns, and the decode for all 256 codes."""
+    import numpy as np
+    import torch
+    lib = B.lib()
+    bits = np.arange(65536, dtype=np.uint32)
+    with np.errstate(invalid="ignore"):                       # signalling-NaN patterns are among the inputs
+        vals = (bits << 16).astype(np.uint32).view(np.float32).astype(np.float64)
+    codes = np.array([lib.qp_e4m3_from_bf16(int(b)) for b in bits], dtype=np.uint32)
+    back = np.array([lib.qp_bf16_from_e4m3(int(c)) for c in range(256)], dtype=np.uint32)
+    decoded = (back << 16).astype(np.uint32).view(np.float32).astype(np.float64)          # value of every code
+    # decode: the format's definition, and the library format torch implements
+    want_dec = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    np.testing.assert_array_equal(np.isnan(decoded), np.isnan(want_dec))
+    ok = ~np.isnan(want_dec)
+    np.testing.assert_array_equal(decoded[ok], want_dec[ok])
+    assert (np.signbit(decoded) == (np.arange(256) >= 128)).all()
+    # encode: equals the oracle's rounding (nearest, ties to even, saturating), sign carried, NaN to the NaN code
+    nan = np.isnan(vals)
+    assert ((codes[nan] & 0x7f) == 0x7f).all()
+    got = decoded[codes[~nan]]
+    np.testing.assert_array_equal(got, O.fp8_e4m3_round(vals[~nan]))
+    np.testing.assert_array_equal(np.signbit(got), np.signbit(vals[~nan]))

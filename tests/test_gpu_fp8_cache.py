@@ -1,0 +1,146 @@
+"""GPU parity of the 8-bit (E4M3) pruned-cache variant: what the compaction stores, what the attention reads, and the
+whole path, against the fp64 oracle's cache_format="fp8_e4m3"."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import assert_attn_close, compare_kept
+from oracle import qp_oracle as O
+from paper_2505_16175_amd import binding as B
+from paper_2505_16175_amd.workload import CONFIGS, make_layer, scaled, to_f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+FP8 = B.QP_CACHE_FP8_E4M3
+
+
+def _decoded(t):
+    """An E4M3 cache tensor as float64 (torch.float8_e4m3fn is the same format)."""
+    return t.to(torch.float32).to(torch.float64).cpu().numpy()
+
+
+def test_compaction_stores_the_oracles_roundings():
+    """Kept rows enter the 8-bit cache rounded exactly as the oracle rounds them: ordinary activations, exact ties,
+    values beyond the format's range (saturating), the subnormal range and zeros."""
+    n_g, h_kv, keep = 300, 3, 111
+    g = torch.Generator().manual_seed(5)
+    k = torch.randn(n_g, h_kv, 128, generator=g) * 10.0 ** torch.randint(-4, 3, (n_g, h_kv, 1), generator=g).float()
+    v = torch.randn(n_g, h_kv, 128, generator=g)
+    special = torch.tensor([1.0625, 1.1875, 248.0, 448.0, 464.0, 1000.0, -7e4, 2.0 ** -9, 2.0 ** -10, 1.5 * 2.0 ** -9,
+                            7.5 * 2.0 ** -9, 0.0, -0.0, 3.0e-5, -1.1, 0.00098])
+    k[:, 0, :16] = special
+    v[:, 1, 16:32] = -special
+    k, v = k.to(torch.bfloat16), v.to(torch.bfloat16)
+    s = torch.randn(h_kv, n_g, generator=g)
+    layout = B.make_layout(h_kv, h_kv, 128, "bf16")
+    cache = B.Cache(layout, keep + 7, fmt=FP8)
+    assert cache.k.element_size() == 1
+    cache.c.len = 7                                            # appended behind existing entries
+    kept = torch.empty(h_kv, keep, dtype=torch.int32, device=DEV)
+    B.topk_compact(layout, s.to(DEV), k.to(DEV), v.to(DEV), keep, 40, cache, kept)
+    torch.cuda.synchronize()
+    want = O.topk_select(s.double().numpy(), keep)
+    np.testing.assert_array_equal(kept.cpu().numpy(), want)
+    np.testing.assert_array_equal(cache.pos.cpu().numpy()[:, 7:7 + keep], 40 + want)
+    k64, v64 = to_f64(k), to_f64(v)
+    for h in range(h_kv):
+        np.testing.assert_array_equal(_decoded(cache.k[h, 7:7 + keep]), O.fp8_e4m3_round(k64[want[h], h]))
+        np.testing.assert_array_equal(_decoded(cache.v[h, 7:7 + keep]), O.fp8_e4m3_round(v64[want[h], h]))
+    assert (cache.k[:, :7].view(torch.uint8) == 0).all()       # earlier entries untouched
+    assert cache.nbytes() * 2 == 2 * h_kv * cache.len * 128 * 2  # half the bytes of a bf16 cache of the same length
+
+
+@pytest.mark.parametrize("n_g,h_q,h_kv,c", [(300, 28, 4, 1000), (64, 28, 4, 5000), (1, 28, 4, 9840), (7, 8, 8, 77),
+                                            (2048, 28, 4, 4920), (130, 64, 8, 0)])
+def test_group_attend_reads_an_e4m3_cache(n_g, h_q, h_kv, c):
+    """The attention over an 8-bit cache equals the oracle's attention over the cache's decoded values: large groups,
+    key-split calls (text chunk, a single token), an empty cache."""
+    print(f"case n_g={n_g} h_q={h_q} h_kv={h_kv} c={c}", flush=True)
+    g = torch.Generator().manual_seed(n_g * 7 + c)
+    bf = lambda *s: torch.randn(*s, generator=g).to(torch.bfloat16)
+    q, k, v = bf(n_g, h_q, 128), bf(n_g, h_kv, 128), bf(n_g, h_kv, 128)
+    layout = B.make_layout(h_q, h_kv, 128, "bf16")
+    cache = B.Cache(layout, max(c, 1) + 3, fmt=FP8)
+    ck = (torch.randn(h_kv, max(c, 1) + 3, 128, generator=g) * 2.0).to(torch.float8_e4m3fn)
+    cv = (torch.randn(h_kv, max(c, 1) + 3, 128, generator=g) * 2.0).to(torch.float8_e4m3fn)
+    cache.k.copy_(ck)
+    cache.v.copy_(cv)
+    cache.c.len = c
+    ws = B.make_workspace(layout, max(n_g, 64), 0)
+    out = torch.full((n_g, h_q, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    lse = torch.full((h_q, n_g), float("nan"), dtype=torch.float32, device=DEV)
+    B.group_attend(layout, q.to(DEV), k.to(DEV), v.to(DEV), cache, out, lse, ws)
+    torch.cuda.synchronize()
+    want, want_lse = O.attend_group(to_f64(q), to_f64(k), to_f64(v), _decoded(ck)[:, :c], _decoded(cv)[:, :c],
+                                    return_lse=True)
+    assert_attn_close(to_f64(out), want, "bf16", f"fp8 cache n_g={n_g} c={c}")
+    np.testing.assert_allclose(to_f64(lse), want_lse, atol=2e-3)
+
+
+@pytest.mark.parametrize("rule", ["key_norm_small", "window_attn"])
+def test_whole_path_with_an_e4m3_cache(rule):
+    """qp_prefill_video with the 8-bit cache on a reduced config-2 shape: kept sets as the oracle's, the cache the
+    oracle's rounded rows exactly, every output element against the oracle's run with cache_format="fp8_e4m3"."""
+    w = scaled(CONFIGS["cfg2_7b_32k"], n_frames=14, tokens_per_frame=48, group_frames=4)    # ragged last group
+    q, k, v, qw = make_layer(w, sharp=True)
+    layout = B.make_layout(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype)
+    cap = B.cache_capacity(w.n_frames, w.tokens_per_frame, w.group_frames, w.retention)
+    cache = B.Cache(layout, cap, fmt=FP8)
+    ws = B.make_workspace(layout, w.group_tokens, w.n_window)
+    out = torch.full_like(q, float("nan"), device=DEV)
+    B.prefill_video(layout, w.n_frames, w.tokens_per_frame, w.group_frames, w.retention, rule, q.to(DEV), k.to(DEV),
+                    v.to(DEV), qw.to(DEV) if rule.startswith("window") else None, cache, out, ws)
+    torch.cuda.synchronize()
+    q64, k64, v64, qw64 = to_f64(q), to_f64(k), to_f64(v), to_f64(qw)
+    want, wck, wcv, wpos, sel = O.prefill_video(q64, k64, v64, qw64, w.n_frames, w.tokens_per_frame, w.group_frames,
+                                                w.retention, rule, cache_format="fp8_e4m3")
+    assert cache.len == wpos.shape[1]
+    pos = cache.pos.cpu().numpy()[:, :cache.len]
+    lo = near = 0
+    sel_valid = []
+    for base, n_g, idx, s in sel:
+        kk = idx.shape[1]
+        got = pos[:, lo:lo + kk] - base
+        near += compare_kept(got, idx, s)
+        sel_valid.append((base, n_g, got.astype(np.int64), s))
+        lo += kk
+    # the cache holds the rounded kept rows, bit for bit
+    for h in range(w.n_kv_heads):
+        np.testing.assert_array_equal(_decoded(cache.k[h, :cache.len]), O.fp8_e4m3_round(k64[pos[h], h]))
+        np.testing.assert_array_equal(_decoded(cache.v[h, :cache.len]), O.fp8_e4m3_round(v64[pos[h], h]))
+    if near:                                                   # the oracle attends over the validated choice
+        want = np.zeros_like(q64)
+        for gi, (base, n_g, _, _) in enumerate(sel_valid):
+            gk, gv, _ = O.gather_cache(k64, v64, sel_valid, gi, cache_format="fp8_e4m3")
+            sl = slice(base, base + n_g)
+            want[sl] = O.attend_group(q64[sl], k64[sl], v64[sl], gk, gv)
+    assert_attn_close(to_f64(out), want, "bf16", f"fp8 cache whole path {rule}")
+    # and it differs from the bf16-cache run where the cache is visible (the rounding is really applied)
+    full, *_ = O.prefill_video(q64, k64, v64, qw64, w.n_frames, w.tokens_per_frame, w.group_frames, w.retention, rule)
+    assert np.abs(full[w.group_tokens:] - want[w.group_tokens:]).max() > 1e-3
+
+
+def test_e4m3_cache_is_refused_where_no_kernel_reads_it():
+    l32 = B.make_layout(4, 2, 128, "f32")
+    with pytest.raises(B.QPError) as e:
+        c = B.Cache(B.make_layout(4, 2, 128, "bf16"), 8, fmt=FP8)
+        B.topk_compact(l32, torch.zeros(2, 16, device=DEV), torch.zeros(16, 2, 128, device=DEV),
+                       torch.zeros(16, 2, 128, device=DEV), 4, 0, c, None)
+    assert e.value.status == B.QP_ERR_UNSUPPORTED
+    layout = B.make_layout(4, 2, 128, "bf16")
+    cache = B.Cache(layout, 8, fmt=FP8)
+    cache.c.len = 8
+    q = torch.zeros(4, 4, 128, dtype=torch.bfloat16, device=DEV)
+    kv = torch.zeros(4, 2, 128, dtype=torch.bfloat16, device=DEV)
+    B.select_attend_kernel(B.QP_ATTEND_SCALAR)
+    try:
+        with pytest.raises(B.QPError) as e:
+            B.group_attend(layout, q, kv, kv, cache, torch.empty_like(q))
+        assert e.value.status == B.QP_ERR_UNSUPPORTED
+    finally:
+        B.select_attend_kernel(B.QP_ATTEND_AUTO)
+    bad = B.Cache(layout, 8)
+    bad.c.format = 9
+    with pytest.raises(B.QPError) as e:
+        B.group_attend(layout, q, kv, kv, bad, torch.empty_like(q))
+    assert e.value.status == B.QP_ERR_INVALID_ARG
