@@ -763,7 +763,7 @@ def main():
                 entry = _config_entry(name, crule, res)
                 if not args.no_cpu_baseline:
                     entry["cpu_baseline"], entry["near_tie"] = cpu_baseline(cw, keep["q"], keep["k"], keep["v"], keep["qw"],
-                                                                            crule, keep["pos"], rows_per_group=48)
+                                                                            crule, keep["pos"], rows_per_group=96)
                 configs.append(entry)
                 del keep
             torch.cuda.empty_cache()
@@ -784,7 +784,8 @@ def main():
     }
     if not args.no_cpu_baseline:
         print(f"[bench] {w.name}: timed steps done, oracle on the host", file=sys.stderr, flush=True)
-        result["cpu_baseline"], near = cpu_baseline(w, keep["q"], keep["k"], keep["v"], keep["qw"], rule, keep["pos"])
+        result["cpu_baseline"], near = cpu_baseline(w, keep["q"], keep["k"], keep["v"], keep["qw"], rule, keep["pos"],
+                                                    rows_per_group=384)
         if near is not None:
             near["layers_checked"] = "layer 0 of %d (the GPU tests check every layer)" % n_layers
         result["near_tie"] = near
