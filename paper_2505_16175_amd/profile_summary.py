@@ -1,15 +1,15 @@
 """Turns rocprofv3 CSV output of bench.py runs into the short text summaries kept under profiles/.
 
     python -m paper_2505_16175_amd.profile_summary --name cfg5_7b_hour_stack \\
-        --kernel-trace gpurun_out/prof_kt --fetch gpurun_out/prof_fetch --write gpurun_out/prof_write \\
-        --bench-json gpurun_out/prof_kt.json --command "<the bench.py arguments the three runs used>"
+        --kernel-trace prof/kt --fetch prof/fetch --write prof/write \\
+        --bench-json prof/kt.json --command "<the bench.py arguments the three runs used>"
 
 The three directories come from three runs of the SAME bench.py command (one counter per run; rocprofv3 does not
 split counters over passes), from the repo root with TMPDIR=/tmp:
 
-    rocprofv3 --kernel-trace --stats -d gpurun_out/prof_kt    -o run --output-format csv -- python3 bench.py <args>
-    rocprofv3 --pmc FETCH_SIZE       -d gpurun_out/prof_fetch -o run --output-format csv -- python3 bench.py <args>
-    rocprofv3 --pmc WRITE_SIZE       -d gpurun_out/prof_write -o run --output-format csv -- python3 bench.py <args>
+    rocprofv3 --kernel-trace --stats -d prof/kt    -o run --output-format csv -- python3 bench.py <args>
+    rocprofv3 --pmc FETCH_SIZE       -d prof/fetch -o run --output-format csv -- python3 bench.py <args>
+    rocprofv3 --pmc WRITE_SIZE       -d prof/write -o run --output-format csv -- python3 bench.py <args>
 
 Writes profiles/<name>_kernel_trace.txt (per-kernel times beside bench.py's own figures of the same run),
 profiles/<name>_hbm_traffic.txt (per-kernel HBM-side bytes) and the row of <name> in profiles/attend_hbm_traffic.txt,

@@ -289,6 +289,29 @@ def test_topk_compact_exact(dtype, h_kv, d, n_g, keep, ties):
         assert (ck[h, :pre] == 0).all() and (ck[h, pre + keep:] == 0).all()
 
 
+@pytest.mark.parametrize("h_kv,n_g,keep", [(70, 2048, 615), (300, 513, 77), (112, 8192, 820)])
+def test_topk_compact_many_heads(h_kv, n_g, keep):
+    """Many KV heads (the bandwidth-characterisation shape of bench.py folds layers into heads): the slices per head
+    are capped by the head count, down to one workgroup per head; kept sets, positions and rows stay bit-exact."""
+    print(f"case h_kv={h_kv} n_g={n_g} keep={keep}", flush=True)
+    g = torch.Generator().manual_seed(h_kv + n_g)
+    s = torch.round(torch.randn(h_kv, n_g, generator=g) * 64) / 64          # some ties
+    k = torch.randn(n_g, h_kv, 128, generator=g).to(torch.bfloat16)
+    v = torch.randn(n_g, h_kv, 128, generator=g).to(torch.bfloat16)
+    layout = B.make_layout(h_kv, h_kv, 128, "bf16")
+    cache = B.Cache(layout, keep + 2)
+    cache.c.len = 2
+    B.topk_compact(layout, s.to(DEV), k.to(DEV), v.to(DEV), keep, 1000, cache, None)
+    torch.cuda.synchronize()
+    want = O.topk_select(s.double().numpy(), keep)
+    np.testing.assert_array_equal(cache.pos.cpu().numpy()[:, 2:2 + keep], 1000 + want)
+    ck, cv = cache.k.cpu(), cache.v.cpu()
+    for h in range(0, h_kv, 7):
+        idx = torch.from_numpy(want[h])
+        assert torch.equal(ck[h, 2:2 + keep], k[idx, h]) and torch.equal(cv[h, 2:2 + keep], v[idx, h])
+        assert (ck[h, :2] == 0).all()
+
+
 def _score_families(n_g, g):
     """Score vectors that drive the selection through each of its routes (one KV head per family)."""
     base = torch.rand(n_g, generator=g)
