@@ -15,6 +15,12 @@
 // At the end the wavefronts' partial (max, sum, O) meet in LDS; the workgroup either writes the rows' final output
 // (one workgroup per KV head) or a normalised partial + log2-sum-exp per chunk, merged by attend_merge_kernel like
 // the key split of the large kernel. The group's own keys (causal among themselves) form the last block.
+//
+// F8 (the pruned cache in 8-bit E4M3): a cache block cannot go global -> LDS directly. The wavefront loads it into
+// registers one block ahead with ordinary loads (8 bytes per lane, key and tensor: half the bytes of a bf16 block),
+// widens it exactly to bf16 and writes it to its own LDS buffer in the same swizzled layout, so that the products
+// and the softmax are the same code; the group's own block is bf16 and still loaded directly. The call is bound by
+// the cache's bytes, which this halves.
 #include "qp_internal.h"
 
 #include <algorithm>
@@ -113,6 +119,7 @@ __device__ __forceinline__ void decode_pv(const unsigned char* vt, const int (&v
     }
 }
 
+template <bool F8>
 __global__ __launch_bounds__(DC_NW * 64) void attend_decode_kernel(AttendArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ float sm_m[DC_NW][DC_MAX_ROWS], sm_l[DC_NW][DC_MAX_ROWS];
@@ -130,8 +137,9 @@ __global__ __launch_bounds__(DC_NW * 64) void attend_decode_kernel(AttendArgs a)
 #pragma unroll
   for (int s = 0; s < 8; ++s) qf[s] = __builtin_bit_cast(bf16x8, *(const u32x4*)(qrow + 16 * s + 8 * g));
 
-  const unsigned char* ck = (const unsigned char*)a.ck + (size_t)h * a.cap * (DC_D * 2);
-  const unsigned char* cv = (const unsigned char*)a.cv + (size_t)h * a.cap * (DC_D * 2);
+  constexpr int CROW = F8 ? DC_D : DC_D * 2;  // bytes of one cached row
+  const unsigned char* ck = (const unsigned char*)a.ck + (size_t)h * a.cap * CROW;
+  const unsigned char* cv = (const unsigned char*)a.cv + (size_t)h * a.cap * CROW;
   const unsigned char* gk = (const unsigned char*)a.k + (size_t)h * (DC_D * 2);
   const unsigned char* gv = (const unsigned char*)a.v + (size_t)h * (DC_D * 2);
   const unsigned gstride_b = (unsigned)a.h_kv * (DC_D * 2);
@@ -180,6 +188,57 @@ __global__ __launch_bounds__(DC_NW * 64) void attend_decode_kernel(AttendArgs a)
     }                                                                                                    \
   }
 
+  if constexpr (F8) {
+    // 8-bit cache blocks through registers: 16 pieces of 8 bytes per lane and block (keys 4i + (lane >> 4), the
+    // global chunk that belongs at LDS position lane & 15), requested one block ahead
+    uint2 rk[8], rv[8];
+    auto load_block = [&](int b_) {
+      const int key0 = b_ * DC_BK, last = a.c - 1;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int kl = 4 * i + st_sub;
+        const unsigned row = (unsigned)min(key0 + kl, last) * (unsigned)DC_D;  // keys past the end are clamped: masked below
+        rk[i] = *(const uint2*)(ck + row + ((st_pos ^ (kl & 15)) << 3));
+        rv[i] = *(const uint2*)(cv + row + ((st_pos ^ ((kl & 7) << 1)) << 3));
+      }
+    };
+    auto widen8 = [](uint2 p) -> u32x4 {  // 8 E4M3 bytes -> 8 bf16 (the f32 values are exact; their high halves are the bf16)
+      const auto a0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)p.x, false), a1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)p.x, true);
+      const auto b0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)p.y, false), b1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)p.y, true);
+      u32x4 o4;
+      o4.x = (__float_as_uint(a0[0]) >> 16) | (__float_as_uint(a0[1]) & 0xffff0000u);
+      o4.y = (__float_as_uint(a1[0]) >> 16) | (__float_as_uint(a1[1]) & 0xffff0000u);
+      o4.z = (__float_as_uint(b0[0]) >> 16) | (__float_as_uint(b0[1]) & 0xffff0000u);
+      o4.w = (__float_as_uint(b1[0]) >> 16) | (__float_as_uint(b1[1]) & 0xffff0000u);
+      return o4;
+    };
+    int b = chunk * a.split_tiles + wave;
+    int cur = 0;
+    if (b < b_end && b < n_cb) load_block(b);
+    while (b < b_end) {
+      unsigned char* buf = vbuf + cur * DC_BUF;
+      const bool has1 = b + DC_NW < b_end;
+      if (b < n_cb) {
+        // this block's pieces have arrived (requested a block ago): widen them into the buffer, then request the next
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          *(u32x4*)(buf + i * 1024 + lane * 16) = widen8(rk[i]);
+          *(u32x4*)(buf + DC_TILE + i * 1024 + lane * 16) = widen8(rv[i]);
+        }
+        if (has1 && b + DC_NW < n_cb) load_block(b + DC_NW);
+      } else {
+        QP_DC_REQUEST(b, cur, false)  // the group's own keys and values: bf16, loaded directly
+        QP_DC_REQUEST(b, cur, true)
+        wait_vmcnt<0>();
+      }
+      bf16x8 pf[2];
+      decode_qk_softmax(buf, k_addr, qf, b == n_cb, b == n_cb ? a.n_g : min(DC_BK, a.c - b * DC_BK), t_lane, g, c2, lazy,
+                        m_run, l_run, o, pf);
+      decode_pv(buf + DC_TILE, v_addr, pf, o);
+      b += DC_NW;
+      cur ^= 1;
+    }
+  } else {
   // The Q fragments (ordinary loads) must have arrived before the first request: from here on only untracked
   // operations are in flight, and the counts in the waits are exact.
   wait_vmcnt<0>();
@@ -214,6 +273,7 @@ __global__ __launch_bounds__(DC_NW * 64) void attend_decode_kernel(AttendArgs a)
     if (has2) QP_DC_REQUEST(b + 2 * DC_NW, cur, true)
     b += DC_NW;
     cur ^= 1;
+  }
   }
 #undef QP_DC_REQUEST
 
@@ -265,8 +325,7 @@ __global__ __launch_bounds__(DC_NW * 64) void attend_decode_kernel(AttendArgs a)
 }
 
 bool attend_decode_applies(const AttendArgs& a, int dtype) {
-  // an 8-bit cache is read by the large kernel only (its key split serves decode-shaped calls then)
-  return attend_mfma_supported(a, dtype) && !a.cache_fp8 && a.n_g * (a.h_q / a.h_kv) <= DC_MAX_ROWS;
+  return attend_mfma_supported(a, dtype) && a.n_g * (a.h_q / a.h_kv) <= DC_MAX_ROWS;
 }
 
 // Blocks per workgroup and workgroups per KV head: about one workgroup per compute unit in total, at least one
@@ -297,7 +356,9 @@ void launch_attend_decode(const AttendArgs& a_in, void* split_ws, size_t split_w
   static bool attr_set[QP_MAX_DEVICES] = {};
   const int dev = current_device();
   if (dev < 0 || !attr_set[dev]) {
-    (void)hipFuncSetAttribute((const void*)attend_decode_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+    (void)hipFuncSetAttribute((const void*)attend_decode_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              DC_NW * DC_WAVE_LDS);
+    (void)hipFuncSetAttribute((const void*)attend_decode_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                               DC_NW * DC_WAVE_LDS);
     if (dev >= 0) attr_set[dev] = true;
   }
@@ -313,7 +374,10 @@ void launch_attend_decode(const AttendArgs& a_in, void* split_ws, size_t split_w
     a.part_o = (float*)split_ws;
     a.part_lse = a.part_o + (size_t)p.n_split * rows_total * DC_D;
   }
-  hipLaunchKernelGGL(attend_decode_kernel, dim3(p.n_split, a.h_kv), dim3(DC_NW * 64), DC_NW * DC_WAVE_LDS, s, a);
+  if (a.cache_fp8)
+    hipLaunchKernelGGL(attend_decode_kernel<true>, dim3(p.n_split, a.h_kv), dim3(DC_NW * 64), DC_NW * DC_WAVE_LDS, s, a);
+  else
+    hipLaunchKernelGGL(attend_decode_kernel<false>, dim3(p.n_split, a.h_kv), dim3(DC_NW * 64), DC_NW * DC_WAVE_LDS, s, a);
   if (p.n_split > 1) launch_attend_merge(a, s);
 }
 

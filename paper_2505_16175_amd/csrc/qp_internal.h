@@ -102,7 +102,7 @@ struct AttendArgs {
   void* out;          // [n_g][h_q][d]
   float* lse;         // [h_q][n_g] or nullptr
   int n_g, h_q, h_kv, d, c, cap;
-  int cache_fp8;      // 1: ck / cv hold one E4M3 byte per element (MFMA kernel only)
+  int cache_fp8;      // 1: ck / cv hold one E4M3 byte per element (MFMA and decode kernels)
   float scale_log2;   // softmax scale * log2(e)
   // Key split of the MFMA kernel (few rows against a long cache): the cache tiles are dealt to n_split chunks of
   // split_tiles tiles, the last chunk also takes the group's own tiles; every chunk leaves a normalised partial

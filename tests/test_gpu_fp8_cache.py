@@ -51,10 +51,12 @@ def test_compaction_stores_the_oracles_roundings():
 
 
 @pytest.mark.parametrize("n_g,h_q,h_kv,c", [(300, 28, 4, 1000), (64, 28, 4, 5000), (1, 28, 4, 9840), (7, 8, 8, 77),
-                                            (2048, 28, 4, 4920), (130, 64, 8, 0)])
+                                            (2048, 28, 4, 4920), (130, 64, 8, 0), (1, 64, 8, 40000), (4, 28, 4, 31),
+                                            (3, 28, 4, 32), (1, 28, 4, 129), (2, 28, 4, 0), (4, 64, 8, 2051)])
 def test_group_attend_reads_an_e4m3_cache(n_g, h_q, h_kv, c):
     """The attention over an 8-bit cache equals the oracle's attention over the cache's decoded values: large groups,
-    key-split calls (text chunk, a single token), an empty cache."""
+    key-split calls (text chunk), decode-shaped calls (a few rows per KV head: the small kernel widens the cache blocks
+    itself; block counts below, at and above one block, ragged tails), an empty cache."""
     print(f"case n_g={n_g} h_q={h_q} h_kv={h_kv} c={c}", flush=True)
     g = torch.Generator().manual_seed(n_g * 7 + c)
     bf = lambda *s: torch.randn(*s, generator=g).to(torch.bfloat16)
