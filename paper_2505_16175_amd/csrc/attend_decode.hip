@@ -76,7 +76,7 @@ __device__ __forceinline__ void decode_qk_softmax(const unsigned char* kt, const
   float mx = st[0];
 #pragma unroll
   for (int r = 1; r < 16; ++r) mx = fmaxf(mx, st[r]);
-  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));  // finite: key 0 of every block is visible to every row
+  mx = max_halves(mx);  // finite: key 0 of every block is visible to every row
   const float m_new = (mx > m_run + lazy) ? mx : m_run;
   const float mc = m_new * c2;
   bf16x2 ones;
@@ -280,7 +280,7 @@ __global__ __launch_bounds__(DC_NW * 64) void attend_decode_kernel(AttendArgs a)
   // the wavefronts' partial results meet in LDS (the start of each wavefront's buffers becomes its 32 x 128 f32 slab)
   wait_vmcnt<0>();
   __syncthreads();
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float l_tot = sum_halves(l_run);
   if (row_ok) {
     float* slab = (float*)vbuf + l32 * DC_D;
 #pragma unroll

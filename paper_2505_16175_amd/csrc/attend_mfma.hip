@@ -122,7 +122,7 @@ __device__ __forceinline__ void softmax_tile(f32x16 (&st)[2], bool need_mask, in
   for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) mx = fmaxf(mx, st[kb][r]);
-  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  mx = max_halves(mx);
   // first tile: m_run = -inf, so the max is adopted; key 0 is visible to every row, so it is finite
   const float m_new = (mx > m_run + lazy) ? mx : m_run;
   const float mc = m_new * c2;
@@ -382,7 +382,7 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
 #undef QP_TILE_VIEW
 
   if (!wave_live) return;
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float l_tot = sum_halves(l_run);
   if (!row_ok) return;
   const float inv = 1.f / l_tot;
   if (a.n_split > 1) {

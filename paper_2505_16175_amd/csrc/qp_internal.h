@@ -71,6 +71,19 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+// max / sum of x over the lane pair (l, l ^ 32), i.e. over the two halves of the wavefront, by v_permlane32_swap:
+// afterwards one register holds the lower half's values in both halves and the other the upper half's. A vector-ALU
+// operation, where a shuffle through the LDS crossbar (ds_bpermute) would also make the wavefront wait for all of
+// its pending LDS reads.
+__device__ __forceinline__ float max_halves(float x) {
+  const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
+__device__ __forceinline__ float sum_halves(float x) {
+  const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+}
+
 // 64 lanes x 16 bytes global -> LDS without passing through registers: lane L's chunk lands at
 // lds_dst + 16 L (lds_dst is wave-uniform). Written as inline assembly so that the compiler does not
 // treat it as an LDS store it must drain (vmcnt(0)) before every later LDS read; the kernel waits for

@@ -176,14 +176,14 @@ __global__ __launch_bounds__(WIN_NT) void window_kernel(WindowArgs a, float2* __
         for (int b = 0; b < 2; ++b)
 #pragma unroll
           for (int r = 0; r < 16; ++r) mx = fmaxf(mx, st[b][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        mx = max_halves(mx);
         const float mc = mx * c2;  // finite: key kbase exists
         float psum = 0.f;
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
           for (int r = 0; r < 16; ++r) psum += __builtin_amdgcn_exp2f(fmaf(st[b][r], c2, -mc));
-        psum += __shfl_xor(psum, 32, 64);
+        psum = sum_halves(psum);
         const float m_new = fmaxf(m_run, mc);
         l_run = l_run * __builtin_amdgcn_exp2f(m_run - m_new) + psum * __builtin_amdgcn_exp2f(mc - m_new);
         m_run = m_new;
@@ -227,7 +227,7 @@ __global__ __launch_bounds__(WIN_NT) void window_kernel(WindowArgs a, float2* __
 #pragma unroll
   for (int kb = 0; kb < WIN_MAX_KB; ++kb) {
     if (kb < n_kb) {
-      const float c = colsum[kb] + __shfl_xor(colsum[kb], 32, 64);
+      const float c = sum_halves(colsum[kb]);
       if (g == 0) red[wave * kc_keys + kb * 32 + l32] = c;
     }
   }
