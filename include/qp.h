@@ -133,7 +133,7 @@ uint8_t qp_e4m3_from_bf16(uint16_t bf16_bits);
 uint16_t qp_bf16_from_e4m3(uint8_t code);
 
 /* Bytes of workspace that every entry point accepts for groups of at most max_group_tokens
- * tokens and a query window of n_window rows (includes 2 x 32 MiB of key-split scratch for the
+ * tokens and a query window of n_window rows (includes 2 x 128 MiB of key-split scratch for the
  * attention launches of qp_prefill_video). 0 on bad arguments. */
 size_t qp_workspace_bytes(const qp_layout* layout, int32_t max_group_tokens, int32_t n_window);
 
@@ -235,17 +235,21 @@ qp_status qp_prefill_video(const qp_layout* layout, int32_t n_frames, int32_t to
 
 /* How qp_group_attend would lay out a call (host arithmetic only, nothing is launched): which kernel,
  * how many workgroups, whether the cache is split over key chunks (key_chunks > 1: two launches, the
- * second merges the chunks' partial results; tiles_per_chunk counts 64-key cache tiles), whether rows
- * are dealt to workgroups as mirrored early/late half blocks (launches of at most one workgroup per
- * compute unit) or consecutively, and how much of the offered workspace the split would use.
+ * second merges the chunks' partial results; tiles_per_chunk counts 64-key cache tiles) and for how many
+ * row blocks of 256 stacked rows per KV head (split_row_blocks: all of them when few rows meet a long
+ * cache; only those of the launch's last, partly filled round of workgroups when there are several
+ * rounds, so that their chunks fill the compute units evenly), whether rows are dealt to workgroups as
+ * mirrored early/late half blocks (launches of at most one workgroup per compute unit) or consecutively,
+ * and how much of the offered workspace the split would use.
  * For the scalar kernel only `kernel` and key_chunks = 1 are meaningful. */
 typedef struct {
   int32_t kernel;          /* QP_ATTEND_SCALAR, QP_ATTEND_MFMA or QP_ATTEND_MFMA_DECODE */
-  int32_t workgroups;      /* per key chunk, including idle padding workgroups */
+  int32_t workgroups;      /* of the first launch, all chunks and idle padding workgroups included */
   int32_t key_chunks;
   int32_t tiles_per_chunk; /* 0 when key_chunks == 1 */
   int32_t mirrored_rows;
   size_t scratch_bytes;
+  int32_t split_row_blocks; /* 0 when key_chunks == 1 (MFMA kernel; the decode kernel splits all of its rows) */
 } qp_attend_plan_info;
 qp_status qp_attend_plan(const qp_layout* layout, int32_t n_group_tokens, int32_t cache_len,
                          size_t workspace_bytes, qp_attend_plan_info* out);

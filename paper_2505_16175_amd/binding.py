@@ -41,7 +41,7 @@ QP_CACHE_SAME, QP_CACHE_FP8_E4M3 = 0, 1
 class qp_attend_plan_info(ctypes.Structure):
     _fields_ = [("kernel", ctypes.c_int32), ("workgroups", ctypes.c_int32), ("key_chunks", ctypes.c_int32),
                 ("tiles_per_chunk", ctypes.c_int32), ("mirrored_rows", ctypes.c_int32),
-                ("scratch_bytes", ctypes.c_size_t)]
+                ("scratch_bytes", ctypes.c_size_t), ("split_row_blocks", ctypes.c_int32)]
 
 
 class qp_layer_shape(ctypes.Structure):

@@ -346,6 +346,7 @@ AttendPlan plan_attend_decode(const AttendArgs& a, size_t split_ws_bytes) {
   }
   p.workgroups = chunks;
   p.n_split = chunks;
+  p.split_rb = 0;
   p.split_tiles = bpw;
   p.mirrored = 0;
   p.scratch_bytes = chunks > 1 ? (size_t)chunks * per_chunk : 0;
@@ -366,6 +367,8 @@ void launch_attend_decode(const AttendArgs& a_in, void* split_ws, size_t split_w
   const AttendPlan p = plan_attend_decode(a, split_ws != nullptr ? split_ws_bytes : 0);
   a.n_split = p.n_split;
   a.split_tiles = p.split_tiles;
+  a.split_rb = 0;
+  a.part_rows = a.n_g * (a.h_q / a.h_kv);  // the merge covers every row
   a.mirrored = 0;
   a.part_o = nullptr;
   a.part_lse = nullptr;

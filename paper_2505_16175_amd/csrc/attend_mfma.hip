@@ -80,6 +80,9 @@ constexpr int MF_VMCNT0 = 0x0f70;       // s_waitcnt vmcnt(0), other counters un
 constexpr int MF_VMCNT4 = 0x0f74;       // s_waitcnt vmcnt(4)
 constexpr int MF_SPLIT_BELOW = 128;     // launches of fewer workgroups split the cache over chunks
 constexpr int MF_MAX_SPLIT = 128;       // chunks at most
+constexpr size_t MF_SPLIT_ALL_BYTES = (size_t)32 << 20;  // scratch that a split of every row block takes at most
+constexpr int MF_TAIL_SPLIT_MAX = 8;    // chunks per row block when only the last round's row blocks are split
+constexpr int MF_TAIL_MIN_TILES = 16;   // ... whose chunks hold at least this many cache tiles
 
 // S^T (64 keys x 32 rows, two 32-key blocks) = K tile . Q^T. All 16 K fragments are read before the
 // first MFMA (a scheduling barrier keeps the compiler from sinking each read next to its use,
@@ -177,30 +180,42 @@ template <bool F8>
 __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
   constexpr int STAGES = MF_STAGES;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform for the compiler too: scalar address and branch work
   const int l32 = lane & 31, g = lane >> 5;
   const int r_heads = a.h_q / a.h_kv;
   const int n_rows = a.n_g * r_heads;
   const int n_hb = (n_rows + MF_HB - 1) / MF_HB;  // half blocks of 128 rows
   const int n_rb = (n_hb + 1) / 2;                // workgroups per KV head (256 rows or a pair of half blocks)
-  // workgroup id -> (KV head, row block): ids go round-robin over the 8 XCDs
-  int h, rbi;
+  // Work items of a KV head: the row blocks that one workgroup serves whole (longest first), then the chunks of the
+  // split row blocks (the shortest ones), chunk by chunk.
+  const int n_whole = n_rb - (a.n_split > 1 ? a.split_rb : 0);
+  const int n_items = n_whole + (n_rb - n_whole) * a.n_split;
+  // workgroup id -> (KV head, item): ids go round-robin over the 8 XCDs
+  int h, item;
   {
     const int wg = blockIdx.x, xcd = wg & 7, idx = wg >> 3;
     if (8 % a.h_kv == 0) {
       const int per = 8 / a.h_kv;  // XCDs per KV head
       h = xcd / per;
-      rbi = idx * per + (xcd % per);
+      item = idx * per + (xcd % per);
     } else if (a.h_kv % 8 == 0) {
       const int hp = a.h_kv / 8;  // KV heads per XCD
       h = (idx % hp) * 8 + xcd;
-      rbi = idx / hp;
+      item = idx / hp;
     } else {
       h = wg % a.h_kv;
-      rbi = wg / a.h_kv;
+      item = wg / a.h_kv;
     }
   }
-  if (rbi >= n_rb) return;        // padding workgroups of the XCD mapping (whole workgroup, before any barrier)
+  if (item >= n_items) return;    // padding workgroups of the XCD mapping (whole workgroup, before any barrier)
+  int rbi = item, chunk = 0, my_split = 1;  // row block (0 = latest tokens), key chunk, chunks of this row block
+  if (item >= n_whole) {
+    const int e = item - n_whole, n_sp = n_rb - n_whole;
+    chunk = e / n_sp;
+    rbi = n_whole + (e - chunk * n_sp);
+    my_split = a.n_split;
+  }
   // Mirrored mapping: the workgroup owns half block rbi (early tokens, short key range) and its mirror
   // n_hb-1-rbi (late tokens, long key range). Wavefronts 0..3 take the early half block and 4..7 the late one:
   // wavefronts w and w+4 share a SIMD, so each SIMD keeps one wavefront busy after the early rows have reached
@@ -224,10 +239,9 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
   const bool wave_live = row0 < n_rows && !unpaired;
   const int n_ct = (a.c + MF_BN - 1) / MF_BN;       // cache tiles
   const int n_tiles = n_ct + t_wg_max / MF_BN + 1;  // + group tiles
-  // key split: chunk blockIdx.y walks cache tiles [t_begin, t_end); the last chunk goes on through the group tiles
-  const int chunk = blockIdx.y;
+  // key split: a chunk walks cache tiles [t_begin, t_end); the last chunk goes on through the group tiles
   const int t_begin = chunk * a.split_tiles;
-  const int t_end = chunk == a.n_split - 1 ? n_tiles : t_begin + a.split_tiles;
+  const int t_end = chunk == my_split - 1 ? n_tiles : t_begin + a.split_tiles;
 
   constexpr int CROW = F8 ? MF_D : MF_D * 2;  // bytes of one cached row
   const unsigned char* ck = (const unsigned char*)a.ck + (size_t)h * a.cap * CROW;
@@ -385,9 +399,9 @@ __global__ __launch_bounds__(MF_NT, 2) void attend_mfma_kernel(AttendArgs a) {
   const float l_tot = sum_halves(l_run);
   if (!row_ok) return;
   const float inv = 1.f / l_tot;
-  if (a.n_split > 1) {
+  if (my_split > 1) {
     // partial result of this chunk: every chunk starts on a cache tile, whose keys all rows see, so l_tot > 0
-    const size_t prow = (size_t)chunk * ((size_t)a.h_kv * n_rows) + (size_t)h * n_rows + row;
+    const size_t prow = (size_t)chunk * ((size_t)a.h_kv * a.part_rows) + (size_t)h * a.part_rows + row;
     float* po = a.part_o + prow * MF_D;
 #pragma unroll
     for (int n = 0; n < 4; ++n)
@@ -423,7 +437,7 @@ __global__ __launch_bounds__(MG_WAVES * 64) void attend_merge_kernel(AttendArgs 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int r_heads = a.h_q / a.h_kv;
-  const int n_rows = a.n_g * r_heads;
+  const int n_rows = a.part_rows;  // rows per KV head that were split
   const long total = (long)a.h_kv * n_rows;
   const long grow = blockIdx.x;
   const int h = (int)(grow / n_rows), row = (int)(grow - (long)h * n_rows);
@@ -491,7 +505,7 @@ constexpr int MR_WAVES = 4;
 __global__ __launch_bounds__(MR_WAVES * 64) void attend_merge_rows_kernel(AttendArgs a) {
   const int lane = threadIdx.x & 63;
   const int r_heads = a.h_q / a.h_kv;
-  const int n_rows = a.n_g * r_heads;
+  const int n_rows = a.part_rows;  // rows per KV head that were split
   const long total = (long)a.h_kv * n_rows;
   const long grow = (long)blockIdx.x * MR_WAVES + (threadIdx.x >> 6);
   if (grow >= total) return;
@@ -540,40 +554,77 @@ bool attend_mfma_supported(const AttendArgs& a, int dtype) {
          (long long)a.n_g * a.h_kv * (MF_D * 2) < (1ll << 31) && a.cap < (1 << 24);
 }
 
+// Chunk length (cache tiles) for `want` chunks of a row block whose rows see at most n_gt group tiles: the last chunk
+// also walks those, so chunks are made just long enough that its cache tiles plus the group tiles do not exceed the
+// others' length by more than one tile (all chunks end together). Every chunk starts on a cache tile.
+static int chunk_tiles(int n_ct, int want, int n_gt) {
+  int st = (n_ct + want - 1) / want;
+  while (st < n_ct - 1 && n_ct - ((n_ct + st - 1) / st - 1) * st + n_gt > st + 1) ++st;
+  return st;
+}
+
 AttendPlan plan_attend_mfma(const AttendArgs& a, size_t split_ws_bytes) {
   AttendPlan p;
-  const int n_rows = a.n_g * (a.h_q / a.h_kv);
+  const int r_heads = a.h_q / a.h_kv;
+  const int n_rows = a.n_g * r_heads;
   const int n_rb = ((n_rows + MF_HB - 1) / MF_HB + 1) / 2;
   const int n_wg = n_rb * a.h_kv;
-  p.mirrored = n_wg <= device_cu_count();  // all workgroups resident at once: balance them; otherwise longest first
-  // Few rows against a long cache (text prefill, decode, small groups): split the cache over chunks so that the
-  // launch still covers the chip, at most one workgroup per CU, at least two tiles per chunk.
+  const int cus = device_cu_count();
+  p.mirrored = n_wg <= cus;  // all workgroups resident at once: balance them; otherwise longest first
   p.n_split = 1;
+  p.split_rb = 0;
   p.split_tiles = 0;
   p.scratch_bytes = 0;
   const int n_ct = (a.c + MF_BN - 1) / MF_BN;
-  const size_t per_split = (size_t)a.h_kv * n_rows * (MF_D + 1) * sizeof(float);
+  const size_t per_row = (size_t)(MF_D + 1) * sizeof(float);  // a partial row and its log-sum-exp
   if (split_ws_bytes > 0 && n_wg < MF_SPLIT_BELOW && n_ct >= 4) {
-    long want = device_cu_count() / n_wg;  // rounded down: all chunks' workgroups resident at once, one round
+    // Few rows against a long cache (text prefill, decode, small groups): split the cache of every row block over
+    // chunks so that the launch still covers the chip, at most one workgroup per CU, at least two tiles per chunk.
+    const size_t per_split = (size_t)a.h_kv * n_rows * per_row;
+    long want = cus / n_wg;  // rounded down: all chunks' workgroups resident at once, one round
     want = std::min<long>(want, n_ct / 2);
     want = std::min<long>(want, MF_MAX_SPLIT);
-    want = std::min<long>(want, (long)(split_ws_bytes / per_split));
+    want = std::min<long>(want, (long)(std::min(split_ws_bytes, MF_SPLIT_ALL_BYTES) / per_split));
     if (want >= 2) {
-      // The last chunk also walks the group's own tiles (up to n_gt of them for the latest rows). Chunks are made
-      // just long enough that its cache tiles plus those do not exceed the others' length by more than one tile, so
-      // that all chunks end together.
-      const int n_gt = (a.n_g + MF_BN - 1) / MF_BN;
-      int st = (n_ct + (int)want - 1) / (int)want;
-      while (st < n_ct - 1 && n_ct - ((n_ct + st - 1) / st - 1) * st + n_gt > st + 1) ++st;
-      p.split_tiles = st;
-      p.n_split = (n_ct + p.split_tiles - 1) / p.split_tiles;  // every chunk starts on a cache tile
+      p.split_tiles = chunk_tiles(n_ct, (int)want, (a.n_g + MF_BN - 1) / MF_BN);
+      p.n_split = (n_ct + p.split_tiles - 1) / p.split_tiles;
+      p.split_rb = n_rb;
       p.scratch_bytes = (size_t)p.n_split * per_split;
     }
+  } else if (split_ws_bytes > 0 && !p.mirrored && (8 % a.h_kv == 0 || a.h_kv % 8 == 0)) {
+    // Several rounds of workgroups, one per CU at a time. The workgroups of a KV head run on the CUs of that head's
+    // XCDs (`pool` CUs serve `heads` KV heads); when the last round would fill only part of them, its row blocks (the
+    // shortest: earliest tokens, started last) are split into chunks so that the chunks fill the pool evenly: t row
+    // blocks in s chunks each take ceil(t s / pool) / s of a round instead of a whole one.
+    const int heads = 8 % a.h_kv == 0 ? 1 : a.h_kv / 8;
+    const int pool = 8 % a.h_kv == 0 ? cus / a.h_kv : cus / 8;
+    const int items = n_rb * heads;
+    const int tail = (items % pool) / heads;  // row blocks per KV head in the partial round
+    if (pool > 0 && tail > 0) {
+      const int part_rows = std::min(n_rows, tail * 2 * MF_HB);
+      const int n_gt = (part_rows - 1) / r_heads / MF_BN + 1;  // group tiles the split rows see at most
+      double best = 0.9;  // of a round: a split must save at least a tenth of one
+      for (int want = 2; want <= MF_TAIL_SPLIT_MAX; ++want) {
+        const int st = chunk_tiles(n_ct, want, n_gt);
+        const int ns = st > 0 ? (n_ct + st - 1) / st : 0;  // the group tiles of the last chunk can make it fewer than wanted
+        if (ns < 2 || st < MF_TAIL_MIN_TILES || (size_t)ns * a.h_kv * part_rows * per_row > split_ws_bytes) continue;
+        // a chunk costs its share of the row block plus a prologue (~3 % of a row block of this length and more)
+        const double cost = (double)((tail * heads * ns + pool - 1) / pool) / ns + 0.03 * (ns - 1);
+        if (cost < best - 1e-9) {
+          best = cost;
+          p.n_split = ns;
+          p.split_tiles = st;
+          p.split_rb = tail;
+          p.scratch_bytes = (size_t)ns * a.h_kv * part_rows * per_row;
+        }
+      }
+    }
   }
-  p.workgroups = n_wg;
+  const int n_items = (n_rb - p.split_rb) + p.split_rb * p.n_split;  // workgroups per KV head
+  p.workgroups = n_items * a.h_kv;
   if (8 % a.h_kv == 0) {
     const int per = 8 / a.h_kv;
-    p.workgroups = (n_rb + per - 1) / per * 8;
+    p.workgroups = (n_items + per - 1) / per * 8;
   }
   return p;
 }
@@ -593,22 +644,23 @@ void launch_attend_mfma(const AttendArgs& a_in, void* split_ws, size_t split_ws_
   a.mirrored = p.mirrored;
   a.n_split = p.n_split;
   a.split_tiles = p.split_tiles;
+  a.split_rb = p.split_rb;
+  a.part_rows = std::min(a.n_g * (a.h_q / a.h_kv), p.split_rb * 2 * MF_HB);
   a.part_o = nullptr;
   a.part_lse = nullptr;
   if (p.n_split > 1) {
-    const size_t rows_total = (size_t)a.h_kv * a.n_g * (a.h_q / a.h_kv);
     a.part_o = (float*)split_ws;
-    a.part_lse = a.part_o + (size_t)p.n_split * rows_total * MF_D;
+    a.part_lse = a.part_o + (size_t)p.n_split * a.h_kv * a.part_rows * MF_D;
   }
   if (a.cache_fp8)
-    hipLaunchKernelGGL(attend_mfma_kernel<true>, dim3(p.workgroups, p.n_split), dim3(MF_NT), MF_STAGES * MF_SLOT, s, a);
+    hipLaunchKernelGGL(attend_mfma_kernel<true>, dim3(p.workgroups), dim3(MF_NT), MF_STAGES * MF_SLOT, s, a);
   else
-    hipLaunchKernelGGL(attend_mfma_kernel<false>, dim3(p.workgroups, p.n_split), dim3(MF_NT), MF_STAGES * MF_SLOT, s, a);
+    hipLaunchKernelGGL(attend_mfma_kernel<false>, dim3(p.workgroups), dim3(MF_NT), MF_STAGES * MF_SLOT, s, a);
   if (p.n_split > 1) launch_attend_merge(a, s);
 }
 
 void launch_attend_merge(const AttendArgs& a, hipStream_t s) {
-  const long total = (long)a.h_kv * a.n_g * (a.h_q / a.h_kv);
+  const long total = (long)a.h_kv * a.part_rows;
   // few rows, many chunks (decode, text chunks): a workgroup of 8 wavefronts per row; many rows, few chunks (small
   // video groups): a wavefront per row
   if (total > 1024 && a.n_split <= 16)

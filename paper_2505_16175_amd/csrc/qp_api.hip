@@ -97,7 +97,7 @@ qp_status static_scratch(void** out) {
 
 // Scratch that qp_group_attend's key split may use (partial outputs of the chunks); qp_prefill_video keeps one
 // area per attention stream, so that two groups' attention launches in flight never share one.
-constexpr size_t kAttendSplitBytes = (size_t)32 << 20;
+constexpr size_t kAttendSplitBytes = (size_t)128 << 20;
 
 // Library-owned streams of qp_prefill_video (created once per device, default priority):
 //   score   scoring and top-k/compaction of a group depend only on the group's K/V (and the query window),
@@ -279,6 +279,7 @@ qp_status qp_attend_plan(const qp_layout* L, int32_t n_g, int32_t cache_len, siz
     out->tiles_per_chunk = p.split_tiles;
     out->mirrored_rows = p.mirrored;
     out->scratch_bytes = p.scratch_bytes;
+    out->split_row_blocks = p.split_rb;
   } else {
     out->kernel = QP_ATTEND_SCALAR;
     out->key_chunks = 1;

@@ -117,13 +117,17 @@ struct AttendArgs {
   int n_g, h_q, h_kv, d, c, cap;
   int cache_fp8;      // 1: ck / cv hold one E4M3 byte per element (MFMA and decode kernels)
   float scale_log2;   // softmax scale * log2(e)
-  // Key split of the MFMA kernel (few rows against a long cache): the cache tiles are dealt to n_split chunks of
-  // split_tiles tiles, the last chunk also takes the group's own tiles; every chunk leaves a normalised partial
-  // output and its log2-sum-exp, merged by a second launch. n_split == 1: no split, nothing below is used.
+  // Key split of the MFMA kernel: the cache tiles of a split row block are dealt to n_split chunks of split_tiles
+  // tiles, the last chunk also takes the group's own tiles; every chunk leaves a normalised partial output and its
+  // log2-sum-exp, merged by a second launch. n_split == 1: no split, nothing below is used. The split_rb row blocks
+  // with the EARLIEST tokens are split (rows 0 .. part_rows-1 of every KV head), the others are served by one
+  // workgroup each: all of them for few rows against a long cache, the last partial round of workgroups otherwise.
   int n_split, split_tiles;
+  int split_rb;       // row blocks (256 rows) that are split, counted from the group's first token
+  int part_rows;      // rows per KV head that have partials: min(n_g * R, 256 * split_rb)
   int mirrored;       // MFMA kernel's row mapping: 1 = mirrored half blocks (balanced), 0 = consecutive, longest first
-  float* part_o;      // [n_split][h_kv * n_g * R][d] f32
-  float* part_lse;    // [n_split][h_kv * n_g * R]    f32, log2 units
+  float* part_o;      // [n_split][h_kv * part_rows][d] f32
+  float* part_lse;    // [n_split][h_kv * part_rows]    f32, log2 units
 };
 
 // Launchers (defined next to their kernels). They only enqueue; hipGetLastError is checked by the caller.
@@ -132,7 +136,8 @@ bool attend_mfma_supported(const AttendArgs& a, int dtype);
 // How launch_attend_mfma lays a call out: grid (workgroups x key_chunks), row mapping, scratch it takes.
 struct AttendPlan {
   int workgroups;       // grid.x, including the padding workgroups of the XCD mapping
-  int n_split;          // grid.y: key chunks (1 = no split)
+  int n_split;          // key chunks of a split row block (1 = no split)
+  int split_rb;         // row blocks per KV head that are split (all of them, or the launch's last partial round)
   int split_tiles;      // cache tiles per chunk
   int mirrored;         // row mapping, see AttendArgs
   size_t scratch_bytes; // bytes of the split scratch used (0 without split)

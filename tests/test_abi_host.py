@@ -117,6 +117,45 @@ def test_host_arithmetic_matches_oracle_and_golden():
     assert B.cache_capacity(0, 1, 1, 0.5) == -1
 
 
+def test_attend_plan_splits_only_the_last_round_of_a_long_launch():
+    """Launches of more workgroups than compute units: when the last round of workgroups would fill only part of a KV
+    head's compute units, exactly that round's row blocks are split, into as many chunks as make them fill the units
+    evenly; full rounds, short caches and calls without scratch are left alone."""
+    offered = 128 << 20
+    L7 = B.make_layout(28, 4, 128, "bf16")                                  # 64 compute units per KV head
+    p = B.attend_plan(L7, 8192, 24000, offered)                             # 224 row blocks per head: 3.5 rounds
+    assert (p["split_row_blocks"], p["key_chunks"], p["mirrored_rows"]) == (32, 2, 0)
+    assert p["workgroups"] == (192 + 32 * 2) * 4 and p["scratch_bytes"] == 2 * 4 * 8192 * 129 * 4
+    assert p["tiles_per_chunk"] * 2 >= 375 > p["tiles_per_chunk"]
+    p = B.attend_plan(L7, 4096, 24000, offered)                             # 112 per head: 1.75 rounds
+    assert (p["split_row_blocks"], p["key_chunks"]) == (48, 4) and p["workgroups"] == (64 + 48 * 4) * 4
+    assert p["scratch_bytes"] == 4 * 4 * 48 * 256 * 129 * 4
+    assert B.attend_plan(L7, 8192, 24000, 32 << 20)["key_chunks"] == 1      # scratch too small for the partials
+    assert B.attend_plan(L7, 8192, 24000, 0)["key_chunks"] == 1
+    assert B.attend_plan(L7, 8192, 700, offered)["key_chunks"] == 1         # chunks would be shorter than 16 tiles
+    assert B.attend_plan(L7, 9362, 24000, offered)["key_chunks"] == 1       # 256 per head: four full rounds
+    L72 = B.make_layout(64, 8, 128, "bf16")                                 # 32 compute units per KV head
+    assert B.attend_plan(L72, 4096, 16384, offered)["key_chunks"] == 1      # 128 per head: four full rounds
+    assert B.attend_plan(L72, 3000, 16384, offered)["key_chunks"] == 1      # 94 per head: the last round is 30 / 32 full
+    p = B.attend_plan(L72, 1100, 2100, offered)                             # 35 per head: 3 row blocks over 32 units
+    assert p["split_row_blocks"] == 3 and p["key_chunks"] == 2
+    for n_g in (2300, 2350, 3000, 4096, 5000, 8192, 20000, 32768):
+        for c in (0, 1000, 1024, 2047, 2048, 5000, 9840, 46125, 200000):
+            for L, r, h_kv, pool in ((L7, 7, 4, 64), (L72, 8, 8, 32)):
+                p = B.attend_plan(L, n_g, c, offered)
+                n_rb = -(-n_g * r // 256)
+                s, per, rb = p["key_chunks"], p["tiles_per_chunk"], p["split_row_blocks"]
+                if n_rb * h_kv <= 256 or s == 1:
+                    assert s == 1 or rb == n_rb or p["mirrored_rows"] == 1
+                    continue
+                n_ct = -(-c // 64)
+                assert 2 <= s <= 8 and rb == n_rb % pool and per >= 16
+                assert (s - 1) * per < n_ct <= s * per                      # every chunk starts on an existing cache tile
+                assert p["scratch_bytes"] == s * h_kv * min(n_g * r, rb * 256) * 129 * 4 <= offered
+                assert -(-rb * s // pool) / s < 0.9                         # the split round is shorter than a whole one
+                assert p["workgroups"] >= (n_rb - rb + rb * s) * h_kv
+
+
 def test_attend_plan_chunks_cover_the_cache_exactly():
     """Host arithmetic of the attention launch: when the cache is split over key chunks, every chunk is non-empty,
     the chunks tile the cache's 64-key tiles exactly, the scratch fits what was offered, and big launches never split."""

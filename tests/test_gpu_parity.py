@@ -99,6 +99,60 @@ def test_group_attend_key_split_matches_oracle(h_q, h_kv, n_g, c):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("h_q,h_kv,n_g,c,fp8", [(28, 4, 2400, 2100, False), (64, 8, 1100, 2100, False),
+                                                (16, 16, 4400, 2100, False), (28, 4, 8192, 24000, False),
+                                                (28, 4, 4096, 24000, False), (28, 4, 2400, 2100, True),
+                                                (28, 4, 2350, 4099, False)])
+def test_group_attend_last_round_split(h_q, h_kv, n_g, c, fp8):
+    """Launches of several rounds of workgroups whose last round is only partly filled: with scratch, the row blocks
+    of that round (the group's earliest tokens) are split over key chunks and merged, the others are not. Rows at both
+    ends of the split region, at its boundary and sampled elsewhere against the oracle; every row against the launch
+    without scratch (no split) at bf16 level."""
+    print(f"case heads={h_q}/{h_kv} n_g={n_g} c={c} fp8={fp8}", flush=True)
+    d, r = 128, h_q // h_kv
+    g = torch.Generator(device=DEV).manual_seed(n_g + c)
+    mk = lambda *s: torch.randn(*s, generator=g, device=DEV).bfloat16()
+    q, k, v = mk(n_g, h_q, d), mk(n_g, h_kv, d), mk(n_g, h_kv, d)
+    layout = B.make_layout(h_q, h_kv, d, "bf16")
+    cache = B.Cache(layout, c + 5, fmt=B.QP_CACHE_FP8_E4M3 if fp8 else B.QP_CACHE_SAME)
+    if fp8:
+        cache.k.copy_((2.0 * torch.randn(h_kv, c + 5, d, generator=g, device=DEV)).to(torch.float8_e4m3fn))
+        cache.v.copy_((2.0 * torch.randn(h_kv, c + 5, d, generator=g, device=DEV)).to(torch.float8_e4m3fn))
+        ck64, cv64 = (t.float().double().cpu().numpy()[:, :c] for t in (cache.k, cache.v))
+    else:
+        cache.k.copy_(mk(h_kv, c + 5, d))
+        cache.v.copy_(mk(h_kv, c + 5, d))
+        ck64, cv64 = _f64(cache.k)[:, :c], _f64(cache.v)[:, :c]
+    cache.c.len = c
+    ws = B.make_workspace(layout, n_g, 0)
+    plan = B.attend_plan(layout, n_g, c, ws.numel())
+    n_rb = -(-n_g * r // 256)
+    assert plan["kernel"] == B.QP_ATTEND_MFMA and plan["key_chunks"] >= 2 and plan["mirrored_rows"] == 0
+    assert 0 < plan["split_row_blocks"] < n_rb and n_rb * h_kv > 256
+    assert (plan["key_chunks"] - 1) * plan["tiles_per_chunk"] < -(-c // 64) <= plan["key_chunks"] * plan["tiles_per_chunk"]
+    t_split = plan["split_row_blocks"] * 256 // r                     # first token with an unsplit row
+    rows = sorted(set([0, 1, 63, 64, t_split - 2, t_split - 1, t_split, t_split + 1, n_g - 2, n_g - 1]
+                      + [int(x) for x in sample_rows(n_g, 24, np.random.default_rng(c))]
+                      + [int(x) for x in sample_rows(t_split, 8, np.random.default_rng(n_g))]))
+    rows = np.array([x for x in rows if 0 <= x < n_g])
+    want, want_lse = O.attend_group(_f64(q), _f64(k), _f64(v), ck64, cv64, rows=rows, return_lse=True)
+    outs = []
+    for scratch in (ws, None):
+        out = torch.full_like(q, float("nan"))
+        lse = torch.full((h_q, n_g), float("nan"), dtype=torch.float32, device=DEV)
+        B.group_attend(layout, q, k, v, cache, out, lse, scratch)
+        torch.cuda.synchronize()
+        assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
+        assert_attn_close(_f64(out[rows]), want, "bf16", "last round split" if scratch is not None else "no scratch")
+        np.testing.assert_allclose(_f64(lse)[:, rows], want_lse, rtol=2e-5, atol=2e-3)
+        outs.append((out.float(), lse.clone()))
+    assert (outs[0][0] - outs[1][0]).abs().max().item() <= 2e-2
+    assert (outs[0][1] - outs[1][1]).abs().max().item() <= 2e-3
+    # rows outside the split region do not depend on the scratch at all
+    assert torch.equal(outs[0][0][t_split + 1:], outs[1][0][t_split + 1:])
+
+
+@pytest.mark.gpu
 def test_group_attend_key_split_at_the_chunk_limit():
     """One workgroup's worth of rows against 24566 cache entries: the large kernel splits into its maximum of 128
     chunks, and the merge kernel takes two batches per wavefront."""
