@@ -16,6 +16,10 @@
 // The keys are walked as two segments, cache tiles first and then group tiles starting
 // at group token 0, so a tile never straddles the two sources; only the cache's last tile and the
 // group's diagonal tiles are masked, and a wavefront skips group tiles beyond its causal horizon.
+// Key split: the cache tiles of a row block can be dealt to several workgroups (chunks), each leaving a normalised
+// partial output and its log-sum-exp for a merge launch. The planner splits every row block when few rows meet a
+// long cache (so that the launch covers the chip), and, in launches of several rounds of workgroups, only the row
+// blocks of a partly filled last round (so that their chunks fill the compute units evenly); see plan_attend_mfma.
 //
 // Per wavefront (32 rows), per tile of 64 keys, with v_mfma_f32_32x32x16_bf16:
 //   S^T[key][row] = K_tile . Q^T      (A = K from LDS, 16-byte reads; B = Q held in registers)

@@ -133,9 +133,9 @@ struct AttendArgs {
 // Launchers (defined next to their kernels). They only enqueue; hipGetLastError is checked by the caller.
 void launch_attend_scalar(const AttendArgs& a, int dtype, hipStream_t s);
 bool attend_mfma_supported(const AttendArgs& a, int dtype);
-// How launch_attend_mfma lays a call out: grid (workgroups x key_chunks), row mapping, scratch it takes.
+// How launch_attend_mfma lays a call out: grid (one-dimensional), key split, row mapping, scratch it takes.
 struct AttendPlan {
-  int workgroups;       // grid.x, including the padding workgroups of the XCD mapping
+  int workgroups;       // grid size: whole row blocks and chunks of all KV heads, plus the padding of the XCD mapping
   int n_split;          // key chunks of a split row block (1 = no split)
   int split_rb;         // row blocks per KV head that are split (all of them, or the launch's last partial round)
   int split_tiles;      // cache tiles per chunk
