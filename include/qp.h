@@ -157,6 +157,9 @@ size_t qp_workspace_bytes(const qp_layout* layout, int32_t max_group_tokens, int
  *     live in this scratch. Two kernels do this: calls of at most 32 stacked rows per KV head
  *     (n_group_tokens * H_q/H_kv <= 32: decoding) run a kernel in which every wavefront streams its
  *     own blocks of keys; larger ones split the tiles of the large kernel (at most 128 chunks).
+ *     Launches of several rounds of workgroups use the scratch too: the row blocks of a partly
+ *     filled last round (the group's earliest tokens) are split over up to 8 key chunks, so that
+ *     their chunks fill the compute units evenly (partials for those rows only).
  *     Without scratch nothing is split. Calls that may overlap on different streams need distinct
  *     scratch. qp_attend_plan reports the choice.
  * Errors: INVALID_ARG (NULL/misaligned pointers, n_group_tokens <= 0, bad layout),
@@ -219,7 +222,8 @@ qp_status qp_topk_compact(const qp_layout* layout, const float* scores, const vo
  * depend on its attention, and the attention of group g+1 depends on the compaction of group g but
  * not on the attention of group g; the call uses two library-owned streams per device (created on
  * first use on the current device, default priority) for the scoring/compaction chain and for every
- * other group's attention. They are forked from hip_stream at entry and joined back into it before
+ * other group's attention (the latter only when a group's attention launch is under two rounds of
+ * workgroups; larger launches all run on hip_stream). They are forked from hip_stream at entry and joined back into it before
  * the call returns: work the caller enqueues on hip_stream afterwards is ordered after all of this
  * call's work. The call only enqueues (it never waits for the GPU); calls from several host threads
  * are serialised while they enqueue, because they share those streams.
