@@ -239,41 +239,41 @@ __global__ __launch_bounds__(DC_NW * 64) void attend_decode_kernel(AttendArgs a)
       cur ^= 1;
     }
   } else {
-  // The Q fragments (ordinary loads) must have arrived before the first request: from here on only untracked
-  // operations are in flight, and the counts in the waits are exact.
-  wait_vmcnt<0>();
-  // Each half of a buffer is refilled as soon as its block has been consumed: K(i+2) right after the QK product of
-  // block i, V(i+2) after its PV product, so that up to three halves beyond the current block are in flight.
-  // Requests in issue order: K(i) V(i) K(i+1) V(i+1) | K(i+2) after QK(i) | V(i+2) after PV(i) ...
-  int b = chunk * a.split_tiles + wave;
-  int cur = 0;
-  if (b < b_end) {
-    QP_DC_REQUEST(b, 0, false)
-    QP_DC_REQUEST(b, 0, true)
-    if (b + DC_NW < b_end) {
-      QP_DC_REQUEST(b + DC_NW, 1, false)
-      QP_DC_REQUEST(b + DC_NW, 1, true)
+    // The Q fragments (ordinary loads) must have arrived before the first request: from here on only untracked
+    // operations are in flight, and the counts in the waits are exact.
+    wait_vmcnt<0>();
+    // Each half of a buffer is refilled as soon as its block has been consumed: K(i+2) right after the QK product of
+    // block i, V(i+2) after its PV product, so that up to three halves beyond the current block are in flight.
+    // Requests in issue order: K(i) V(i) K(i+1) V(i+1) | K(i+2) after QK(i) | V(i+2) after PV(i) ...
+    int b = chunk * a.split_tiles + wave;
+    int cur = 0;
+    if (b < b_end) {
+      QP_DC_REQUEST(b, 0, false)
+      QP_DC_REQUEST(b, 0, true)
+      if (b + DC_NW < b_end) {
+        QP_DC_REQUEST(b + DC_NW, 1, false)
+        QP_DC_REQUEST(b + DC_NW, 1, true)
+      }
     }
-  }
-  while (b < b_end) {
-    const bool has1 = b + DC_NW < b_end, has2 = b + 2 * DC_NW < b_end;
-    unsigned char* buf = vbuf + cur * DC_BUF;
-    // K(i) has landed: V(i) and block i+1 (16 requests) may still be in flight
-    if (has1) wait_vmcnt<24>();
-    else wait_vmcnt<8>();
-    bf16x8 pf[2];
-    decode_qk_softmax(buf, k_addr, qf, b == n_cb, b == n_cb ? a.n_g : min(DC_BK, a.c - b * DC_BK), t_lane, g, c2, lazy,
-                      m_run, l_run, o, pf);
-    if (has2) QP_DC_REQUEST(b + 2 * DC_NW, cur, false)  // the K fragments of block i are in registers
-    // V(i) has landed: block i+1 and K(i+2) may still be in flight
-    if (has2) wait_vmcnt<24>();
-    else if (has1) wait_vmcnt<16>();
-    else wait_vmcnt<0>();
-    decode_pv(buf + DC_TILE, v_addr, pf, o);
-    if (has2) QP_DC_REQUEST(b + 2 * DC_NW, cur, true)
-    b += DC_NW;
-    cur ^= 1;
-  }
+    while (b < b_end) {
+      const bool has1 = b + DC_NW < b_end, has2 = b + 2 * DC_NW < b_end;
+      unsigned char* buf = vbuf + cur * DC_BUF;
+      // K(i) has landed: V(i) and block i+1 (16 requests) may still be in flight
+      if (has1) wait_vmcnt<24>();
+      else wait_vmcnt<8>();
+      bf16x8 pf[2];
+      decode_qk_softmax(buf, k_addr, qf, b == n_cb, b == n_cb ? a.n_g : min(DC_BK, a.c - b * DC_BK), t_lane, g, c2, lazy,
+                        m_run, l_run, o, pf);
+      if (has2) QP_DC_REQUEST(b + 2 * DC_NW, cur, false)  // the K fragments of block i are in registers
+      // V(i) has landed: block i+1 and K(i+2) may still be in flight
+      if (has2) wait_vmcnt<24>();
+      else if (has1) wait_vmcnt<16>();
+      else wait_vmcnt<0>();
+      decode_pv(buf + DC_TILE, v_addr, pf, o);
+      if (has2) QP_DC_REQUEST(b + 2 * DC_NW, cur, true)
+      b += DC_NW;
+      cur ^= 1;
+    }
   }
 #undef QP_DC_REQUEST
 
