@@ -618,9 +618,9 @@ def measure_config(torch, B, w, rule, steps, warmup, n_layers, replay_steps, gra
                                   "by a plain copy; a snapshot taken with the committed kernels, not measured in this run)",
                 "launches": n_launch, "avg_launch_us": t_att / n_launch * 1e6, "flops_per_launch_avg": fl / n_launch,
                 "measured": f"HIP events around every qp_group_attend launch of a serial replay of layer 0 ({replay_steps} "
-                            "step(s), one stream, after the timed steps); the timed steps overlap consecutive groups' "
-                            "launches on two streams, so whole_step_frac (all layers' attention flops / ms_per_step) "
-                            "can exceed frac",
+                            "step(s), one stream, after the timed steps); for groups of under two rounds of workgroups "
+                            "the timed steps overlap consecutive groups' launches on two streams, so whole_step_frac "
+                            "(all layers' attention flops / ms_per_step) can exceed frac",
                 "whole_step_achieved": whole_step, "whole_step_frac": whole_step / PEAK_BF16_TFLOPS}
     if w.dtype == "f32":
         roofline.update({"kernel": "attend_scalar_kernel (qp_group_attend)", "bound": "alu", "peak": 157.3,

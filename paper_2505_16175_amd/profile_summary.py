@@ -102,9 +102,10 @@ def main():
                     f"  ms_per_step {j['ms_per_step']:.3f}  value {j['value']:.4g} {j['unit']}  roofline.avg_launch_us "
                     f"{rf['avg_launch_us']:.1f}  achieved {rf['achieved']:.1f} TFLOP/s  frac {rf['frac']:.3f}  "
                     f"whole_step_frac {rf['whole_step_frac']:.3f}",
-                    "  (roofline.avg_launch_us is taken with HIP events around the launches of a serial replay; the timed steps",
-                    "   overlap consecutive groups' attention launches on two streams, which stretches each one's begin-to-end",
-                    "   time in this trace: the --stats average below mixes both kinds of launches)"]
+                    "  (roofline.avg_launch_us is taken with HIP events around the qp_group_attend calls of a serial replay. Where the",
+                    "   timed steps alternate consecutive groups' attention launches over two streams (groups of under two rounds of",
+                    "   workgroups: configs 2 and 3) the overlap stretches each launch's begin-to-end time in this trace and the --stats",
+                    "   average below mixes both kinds of launches; where they run on one stream (configs 4 and 5) the two agree)"]
         out += ["", "kernel | calls | total ms | average us | min us | max us | % of GPU time"]
         for k, v in sorted(stats.items(), key=lambda kv: -sum(kv[1]))[:14]:
             out.append(f"{_short(k)} | {len(v)} | {sum(v) / 1e3:.3f} | {sum(v) / len(v):.2f} | {min(v):.2f} | {max(v):.2f} | "
