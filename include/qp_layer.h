@@ -88,9 +88,12 @@ qp_status qp_select_linear_tile(int32_t token_rows);
 
 /* How qp_linear would lay out a call (host arithmetic only, nothing is launched): token rows per workgroup tile,
  * workgroups per k chunk (including idle padding workgroups of the XCD mapping), k chunks (1 = not split) with
- * their 64-wide k-steps, and how much of the offered scratch the partial sums would take. */
+ * their 64-wide k-steps, and how much of the offered scratch the partial sums would take. Calls of at most 2 tokens
+ * (decoding) run a kernel that streams the weights once instead, 4 weight rows per workgroup, never split:
+ * token_rows_per_tile is then 1 or 2 (the tokens it computes) and workgroups = n / 4; a tiling pinned with
+ * qp_select_linear_tile keeps such calls on the tiled kernel. */
 typedef struct {
-  int32_t token_rows_per_tile; /* 128 or 256 */
+  int32_t token_rows_per_tile; /* 128 or 256; 1 or 2 for the weight-streaming kernel */
   int32_t workgroups;
   int32_t k_chunks;
   int32_t k_steps_per_chunk;   /* the last chunk may have fewer */

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libqp_hip.so")
 SOURCES = ["qp_api.hip", "attend_scalar.hip", "attend_mfma.hip", "attend_decode.hip", "score.hip",
-           "score_window_mfma.hip", "topk_compact.hip", "gemm_bf16.hip", "layer_kernels.hip", "layer_api.hip", "feed.hip"]
+           "score_window_mfma.hip", "topk_compact.hip", "gemm_bf16.hip", "gemv_bf16.hip", "layer_kernels.hip", "layer_api.hip", "feed.hip"]
 
 
 def hipcc_command(out=LIB_PATH, extra=()):

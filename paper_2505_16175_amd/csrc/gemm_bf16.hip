@@ -486,7 +486,7 @@ int gemm_tile_rows(const GemmArgs& a) {
 // k-steps to chunks, about one workgroup per CU in all, at least 4 steps per chunk, as many chunks as the scratch holds.
 GemmSplit gemm_plan_split(const GemmArgs& a, int mode, size_t scratch_bytes) {
   GemmSplit p{1, a.k / GM_BK, 0};
-  if (mode == GEMM_SWIGLU || scratch_bytes == 0) return p;
+  if (mode == GEMM_SWIGLU || scratch_bytes == 0 || gemm_uses_gemv(a)) return p;
   const int rows = gemm_tile_rows(a), cus = device_cu_count();
   const long tiles = (long)((a.m + rows - 1) / rows) * ((a.n + GM_BN - 1) / GM_BN);
   const int steps = a.k / GM_BK;
@@ -534,7 +534,14 @@ static hipError_t launch_mode(GemmArgs a, void* scratch, size_t scratch_bytes, h
   return hipSuccess;
 }
 
+// A handful of tokens take the weight-streaming kernel (gemv_bf16.hip) unless a tiling is forced (tests then reach
+// the split contraction of this kernel at those sizes too).
+bool gemm_uses_gemv(const GemmArgs& a) {
+  return gemv_applies(a) && g_forced_tile_rows.load(std::memory_order_relaxed) == 0;
+}
+
 hipError_t launch_gemm_bf16(const GemmArgs& a, int mode, void* scratch, size_t scratch_bytes, hipStream_t s) {
+  if (gemm_uses_gemv(a)) return launch_gemv_bf16(a, mode, s);
   switch (mode) {
     case GEMM_PLAIN: return launch_mode<GEMM_PLAIN>(a, scratch, scratch_bytes, s);
     case GEMM_QKV_ROPE: return launch_mode<GEMM_QKV_ROPE>(a, scratch, scratch_bytes, s);

@@ -137,6 +137,14 @@ qp_status qp_linear_plan(int32_t m, int32_t n, int32_t k, size_t workspace_bytes
   a.m = m, a.n = n, a.k = k;
   if (!qp::gemm_supported(a, qp::GEMM_PLAIN)) return QP_ERR_UNSUPPORTED;
   const qp::GemmSplit sp = qp::gemm_plan_split(a, qp::GEMM_PLAIN, workspace_bytes);
+  if (qp::gemm_uses_gemv(a)) {  // the weight-streaming kernel: 4 weight rows per workgroup, never split
+    out->token_rows_per_tile = m;
+    out->workgroups = n / 4;
+    out->k_chunks = 1;
+    out->k_steps_per_chunk = sp.steps_per_split;
+    out->scratch_bytes = 0;
+    return QP_OK;
+  }
   const int rows = qp::gemm_tile_rows(a);
   const int tiles_m = (m + rows - 1) / rows, tiles_n = (n + 255) / 256;
   const int m_block = tiles_m < 8 ? tiles_m : 8;
@@ -235,9 +243,11 @@ qp_status qp_layer_group(const qp_layout* layout, const qp_layer_shape* shape, c
   } fork(s);
   st = qp_group_attend(layout, ws + c.q, ws + c.k, ws + c.v, n_g, cache, ws + c.attn, nullptr, split_ws, kSplit, s);
   if (st != QP_OK) return st;
-  st = qp_score_kv(layout, rule, ws + c.k, ws + c.v, n_g, q_win, nw, (float*)(ws + c.scores), score_ws, score_bytes,
-                   fork.stream());
-  if (st != QP_OK) return st;
+  if (keep < n_g) {  // with every token kept (the stages after the video) the scores decide nothing
+    st = qp_score_kv(layout, rule, ws + c.k, ws + c.v, n_g, q_win, nw, (float*)(ws + c.scores), score_ws, score_bytes,
+                     fork.stream());
+    if (st != QP_OK) return st;
+  }
   st = qp_topk_compact(layout, (const float*)(ws + c.scores), ws + c.k, ws + c.v, n_g, keep, group_token_base, cache,
                        kept_idx_or_null, score_ws, score_bytes, fork.stream());
   if (st != QP_OK) return st;

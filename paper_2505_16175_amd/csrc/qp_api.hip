@@ -531,10 +531,12 @@ qp_status qp_prefill_video(const qp_layout* L, int32_t n_frames, int32_t tokens_
     if (st != QP_OK) break;
     // 2. score the group's new KV entries; 3. TopK + compaction into the cache (cache->len advances on the host).
     //    The appended rows [len, len+k) are disjoint from the rows [0, len) any attention kernel in flight reads.
-    st = qp_score_kv(L, rule, kg, vg, n_g, q_win, n_window, scores, ws2, ws2_bytes, score_stream);
-    if (st != QP_OK) break;
-    st = qp_topk_compact(L, scores, kg, vg, n_g, (int32_t)qp_keep_count(n_g, retention), base, cache, nullptr, ws2,
-                         ws2_bytes, score_stream);
+    const int32_t keep = (int32_t)qp_keep_count(n_g, retention);
+    if (keep < n_g) {  // at retention 1 every token survives whatever its score
+      st = qp_score_kv(L, rule, kg, vg, n_g, q_win, n_window, scores, ws2, ws2_bytes, score_stream);
+      if (st != QP_OK) break;
+    }
+    st = qp_topk_compact(L, scores, kg, vg, n_g, keep, base, cache, nullptr, ws2, ws2_bytes, score_stream);
     if (st != QP_OK) break;
     if (overlap) QP_HIP_OK(hipEventRecord(g_side.compacted[gi & 1], g_side.score));
   }

@@ -221,6 +221,10 @@ struct GemmSplit {
   size_t scratch_bytes;
 };
 GemmSplit gemm_plan_split(const GemmArgs& a, int mode, size_t scratch_bytes);  // host arithmetic only
+// Calls of at most 2 tokens stream the weights once through a kernel of their own (one launch, no partial sums).
+bool gemv_applies(const GemmArgs& a);
+bool gemm_uses_gemv(const GemmArgs& a);   // gemv_applies and no tiling is forced
+hipError_t launch_gemv_bf16(const GemmArgs& a, int mode, hipStream_t s);
 int gemm_tile_rows(const GemmArgs& a);    // token rows per workgroup tile the launcher would use: 128 or 256
 void gemm_force_tile_rows(int rows);      // 0 = choose per launch (default), 128 or 256
 void launch_rms_norm(const void* x, const void* w, void* out, int n_tokens, int d_model, float eps, hipStream_t s);

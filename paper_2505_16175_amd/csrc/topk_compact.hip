@@ -50,6 +50,44 @@ __device__ __forceinline__ uint32_t order_key(float s) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // ascending in s
 }
 
+// 8 bf16 values (16 bytes) as 8 E4M3 codes (the 8-bit cache's rows)
+__device__ __forceinline__ uint2 pack8_e4m3(const u32x4& b) {
+  uint2 r;
+  r.x = bf16_to_e4m3(b.x & 0xffffu) | (bf16_to_e4m3(b.x >> 16) << 8) | (bf16_to_e4m3(b.y & 0xffffu) << 16) |
+        (bf16_to_e4m3(b.y >> 16) << 24);
+  r.y = bf16_to_e4m3(b.z & 0xffffu) | (bf16_to_e4m3(b.z >> 16) << 8) | (bf16_to_e4m3(b.w & 0xffffu) << 16) |
+        (bf16_to_e4m3(b.w >> 16) << 24);
+  return r;
+}
+
+// keep == n_g (retention 1, and the single tokens and text chunks that follow the video, Sec. 2.1): every token
+// survives whatever its score, so the selection is the identity and the compaction a plain append. One lane per 16
+// bytes of a row; grid (row runs, KV heads).
+constexpr int APPEND_THREADS = 256;
+template <typename T, int D>
+__global__ __launch_bounds__(APPEND_THREADS) void append_all_kernel(TopkArgs a, int32_t* __restrict__ kept_out) {
+  constexpr int PER = Elem<T>::kPer16B;
+  constexpr int LPR = D / PER;  // lanes per row
+  const int h = blockIdx.y;
+  const int idx = blockIdx.x * APPEND_THREADS + threadIdx.x;
+  const int j = idx / LPR, sub = idx - j * LPR;
+  if (j >= a.n_g) return;
+  const size_t src = ((size_t)j * a.h_kv + h) * D + sub * PER;
+  const u32x4 kk = *(const u32x4*)((const T*)a.k + src), vv = *(const u32x4*)((const T*)a.v + src);
+  const size_t row = (size_t)h * a.cap + a.len + j;
+  if (sizeof(T) == 2 && a.cache_fp8) {
+    *(uint2*)((unsigned char*)a.ck + row * D + sub * PER) = pack8_e4m3(kk);
+    *(uint2*)((unsigned char*)a.cv + row * D + sub * PER) = pack8_e4m3(vv);
+  } else {
+    *(u32x4*)((T*)a.ck + row * D + sub * PER) = kk;
+    *(u32x4*)((T*)a.cv + row * D + sub * PER) = vv;
+  }
+  if (sub == 0) {
+    a.pos[row] = a.base + j;
+    if (kept_out != nullptr) kept_out[(size_t)h * a.keep + j] = j;
+  }
+}
+
 template <typename T, int D>
 __global__ __launch_bounds__(TOPK_THREADS) void topk_compact_kernel(TopkArgs a, int32_t* __restrict__ kept_out, int slice_tokens) {
   extern __shared__ uint32_t keys[];  // [n_g] keys, then [slice_tokens] kept token indices of this slice
@@ -298,17 +336,8 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_compact_kernel(TopkArgs a, 
       if (r < n_copy) {
         const size_t dst = (size_t)r * D + sub * PER;
         if (to_fp8) {
-          uint2 k8, v8;
-          k8.x = bf16_to_e4m3(kk[u].x & 0xffffu) | (bf16_to_e4m3(kk[u].x >> 16) << 8) |
-                 (bf16_to_e4m3(kk[u].y & 0xffffu) << 16) | (bf16_to_e4m3(kk[u].y >> 16) << 24);
-          k8.y = bf16_to_e4m3(kk[u].z & 0xffffu) | (bf16_to_e4m3(kk[u].z >> 16) << 8) |
-                 (bf16_to_e4m3(kk[u].w & 0xffffu) << 16) | (bf16_to_e4m3(kk[u].w >> 16) << 24);
-          v8.x = bf16_to_e4m3(vv[u].x & 0xffffu) | (bf16_to_e4m3(vv[u].x >> 16) << 8) |
-                 (bf16_to_e4m3(vv[u].y & 0xffffu) << 16) | (bf16_to_e4m3(vv[u].y >> 16) << 24);
-          v8.y = bf16_to_e4m3(vv[u].z & 0xffffu) | (bf16_to_e4m3(vv[u].z >> 16) << 8) |
-                 (bf16_to_e4m3(vv[u].w & 0xffffu) << 16) | (bf16_to_e4m3(vv[u].w >> 16) << 24);
-          *(uint2*)(ck8 + dst) = k8;  // dst counts elements = bytes here
-          *(uint2*)(cv8 + dst) = v8;
+          *(uint2*)(ck8 + dst) = pack8_e4m3(kk[u]);  // dst counts elements = bytes here
+          *(uint2*)(cv8 + dst) = pack8_e4m3(vv[u]);
         } else {
           *(u32x4*)(ck + dst) = kk[u];
           *(u32x4*)(cv + dst) = vv[u];
@@ -337,6 +366,12 @@ static int slice_tokens_for(int n_g, int keep, int h_kv) {
 
 template <typename T, int D>
 static hipError_t launch_fused(const TopkArgs& a, int32_t* kept_out, hipStream_t s) {
+  if (a.keep == a.n_g) {  // nothing to select
+    constexpr int LPR = D / Elem<T>::kPer16B;
+    hipLaunchKernelGGL((append_all_kernel<T, D>), dim3((a.n_g * LPR + APPEND_THREADS - 1) / APPEND_THREADS, a.h_kv),
+                       dim3(APPEND_THREADS), 0, s, a, kept_out);
+    return hipSuccess;
+  }
   const int slice_tokens = slice_tokens_for(a.n_g, a.keep, a.h_kv);
   const int slices = (a.n_g + slice_tokens - 1) / slice_tokens;
   const size_t lds_bytes = ((size_t)a.n_g + slice_tokens) * sizeof(uint32_t);

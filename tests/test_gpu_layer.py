@@ -143,6 +143,67 @@ def test_swiglu_gate_up(n, d_model, d_ff, tile):
     assert_stored_close(to_f64(act), LO.bf16_round(want), "swiglu")
 
 
+@pytest.mark.parametrize("m", [1, 2])
+@pytest.mark.parametrize("d_model,d_ff,h_q,h_kv", [(3584, 18944, 28, 4), (192, 384, 6, 3), (8192, 29568, 64, 8)])
+def test_few_token_projections_stream_the_weights(m, d_model, d_ff, h_q, h_kv):
+    """Calls of at most 2 tokens (decoding through the layer, Sec. 2.1) take the kernel that streams the weights once:
+    all three stores against the oracle at the layer's real sizes, agreement with the tiled kernel at bf16 level, and
+    the plan says which kernel runs."""
+    print(f"case m={m} d_model={d_model} d_ff={d_ff} heads={h_q}/{h_kv}", flush=True)
+    g = torch.Generator().manual_seed(m + d_model + d_ff)
+    dv = lambda t: t.to(DEV)
+    plan = B.linear_plan(m, d_model, d_ff, 32 << 20)
+    assert plan["token_rows_per_tile"] == m and plan["k_chunks"] == 1
+    assert plan["workgroups"] == d_model // 4 and plan["scratch_bytes"] == 0
+    # down projection with residual, o_proj-shaped projection with bias
+    for n, k, bias in ((d_model, d_ff, False), (d_model, h_q * 128, True)):
+        x, w = _bf(m, k, gen=g), _bf(n, k, gen=g, scale=k ** -0.5)
+        b = _bf(n, gen=g, scale=0.5) if bias else None
+        r = _bf(m, n, gen=g)
+        want = LO.linear(to_f64(x), to_f64(w), None if b is None else to_f64(b)) + to_f64(r)
+        out = torch.full((m, n), float("nan"), dtype=torch.bfloat16, device=DEV)
+        B.linear(dv(x), dv(w), None if b is None else dv(b), dv(r), out)
+        torch.cuda.synchronize()
+        assert_stored_close(to_f64(out), LO.bf16_round(want), f"streamed linear k={k}")
+        B.select_linear_tile(256)
+        try:
+            assert B.linear_plan(m, n, k, 0)["token_rows_per_tile"] == 256
+            tiled = torch.full_like(out, float("nan"))
+            B.linear(dv(x), dv(w), None if b is None else dv(b), dv(r), tiled)
+            torch.cuda.synchronize()
+        finally:
+            B.select_linear_tile(0)
+        assert_stored_close(to_f64(tiled), LO.bf16_round(want), f"tiled linear k={k}")
+        out2 = dv(r).clone()                                      # the residual may alias the output
+        B.linear(dv(x), dv(w), None if b is None else dv(b), out2, out2)
+        torch.cuda.synchronize()
+        assert torch.equal(out2, out)
+    # QKV + bias + rotary embedding
+    theta, sections = 1e6, (16, 24, 24)
+    h = _bf(m, d_model, gen=g)
+    nq = (h_q + 2 * h_kv) * 128
+    w, b = _bf(nq, d_model, gen=g, scale=d_model ** -0.5), _bf(nq, gen=g, scale=0.5)
+    pos = W.text_positions(m, 46000)
+    want = _oracle_qkv(to_f64(h), to_f64(w), to_f64(b), pos.numpy(), h_q, h_kv, theta, sections)
+    layout = B.make_layout(h_q, h_kv, 128, "bf16")
+    cs = torch.empty(m, 64, 2, dtype=torch.float32, device=DEV)
+    B.rope_table(pos.to(DEV), 0, m, theta, sections, cs)
+    q = torch.full((m, h_q, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    k = torch.full((m, h_kv, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    v = torch.full((m, h_kv, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    B.qkv_rope(layout, dv(h), dv(w), dv(b), cs, q, k, v)
+    torch.cuda.synchronize()
+    for name, got, ref in zip("qkv", (q, k, v), want):
+        assert_stored_close(to_f64(got), ref, f"streamed {name}")
+    # SwiGLU gate / up
+    w = _bf(2 * d_ff, d_model, gen=g, scale=2.0 * d_model ** -0.5)
+    want = LO.silu(LO.linear(to_f64(h), to_f64(w[:d_ff]))) * LO.linear(to_f64(h), to_f64(w[d_ff:]))
+    act = torch.full((m, d_ff), float("nan"), dtype=torch.bfloat16, device=DEV)
+    B.swiglu_gate_up(dv(h), dv(w), act)
+    torch.cuda.synchronize()
+    assert_stored_close(to_f64(act), LO.bf16_round(want), "streamed swiglu")
+
+
 @pytest.mark.parametrize("m,n,k,bias,res", [(1, 3584, 18944, False, True), (7, 512, 1024, True, True), (64, 3584, 3584, False, True),
                                             (130, 264, 640, True, False), (300, 1024, 4096, False, False)])
 def test_linear_split_contraction(m, n, k, bias, res):
@@ -159,12 +220,18 @@ def test_linear_split_contraction(m, n, k, bias, res):
     dv = lambda t: None if t is None else t.to(DEV)
     scratch = torch.empty(32 << 20, dtype=torch.uint8, device=DEV)
     outs = []
-    for _ in range(2):
-        out = torch.full((m, n), float("nan"), dtype=torch.bfloat16, device=DEV)
-        scratch.fill_(0xff)                                       # NaN patterns: every partial read must have been written
-        B.linear(dv(x), dv(w), dv(b), dv(r), out, scratch)
-        torch.cuda.synchronize()
-        outs.append(out)
+    if m <= 2:
+        B.select_linear_tile(256)      # a handful of tokens would otherwise take the weight-streaming kernel
+    try:
+        assert B.linear_plan(m, n, k, 32 << 20)["k_chunks"] > 1
+        for _ in range(2):
+            out = torch.full((m, n), float("nan"), dtype=torch.bfloat16, device=DEV)
+            scratch.fill_(0xff)                                   # NaN patterns: every partial read must have been written
+            B.linear(dv(x), dv(w), dv(b), dv(r), out, scratch)
+            torch.cuda.synchronize()
+            outs.append(out)
+    finally:
+        B.select_linear_tile(0)
     assert_stored_close(to_f64(outs[0]), LO.bf16_round(want), "split linear")
     assert torch.equal(outs[0], outs[1])
     plain = torch.empty_like(outs[0])
@@ -191,8 +258,13 @@ def test_qkv_rope_split_contraction(n, d_model, h_q, h_kv):
     q = torch.full((n, h_q, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
     k = torch.full((n, h_kv, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
     v = torch.full((n, h_kv, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
-    B.qkv_rope(layout, h.to(DEV), w.to(DEV), b.to(DEV), cs, q, k, v, scratch)
-    torch.cuda.synchronize()
+    if n <= 2:
+        B.select_linear_tile(256)      # a handful of tokens would otherwise take the weight-streaming kernel
+    try:
+        B.qkv_rope(layout, h.to(DEV), w.to(DEV), b.to(DEV), cs, q, k, v, scratch)
+        torch.cuda.synchronize()
+    finally:
+        B.select_linear_tile(0)
     for name, got, ref in zip("qkv", (q, k, v), want):
         assert_stored_close(to_f64(got), ref, name)
 
