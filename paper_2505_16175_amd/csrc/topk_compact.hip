@@ -6,6 +6,7 @@
 // slice of the group's tokens: it ranks the slice's survivors, writes their indices and cache positions, and copies
 // their K and V rows (16-byte vector loads/stores, d*sizeof/16 lanes per row, all loads of a batch in flight before
 // the first store). Copies of early workgroups overlap the searches of later ones.
+// When every token is kept (k = N_g) there is nothing to select: append_all_kernel copies the rows in order.
 //
 // Selection = find the k-th largest key T and how many keys equal to T survive (`need`), then emit.
 //   * While loading, the workgroup takes the minimum and maximum key. A round spreads the current key

@@ -19,10 +19,12 @@ def _decoded(t):
     return t.to(torch.float32).to(torch.float64).cpu().numpy()
 
 
-def test_compaction_stores_the_oracles_roundings():
+@pytest.mark.parametrize("keep", [111, 300])
+def test_compaction_stores_the_oracles_roundings(keep):
     """Kept rows enter the 8-bit cache rounded exactly as the oracle rounds them: ordinary activations, exact ties,
-    values beyond the format's range (saturating), the subnormal range and zeros."""
-    n_g, h_kv, keep = 300, 3, 111
+    values beyond the format's range (saturating), the subnormal range and zeros. keep = 300 keeps every token (the
+    plain append)."""
+    n_g, h_kv = 300, 3
     g = torch.Generator().manual_seed(5)
     k = torch.randn(n_g, h_kv, 128, generator=g) * 10.0 ** torch.randint(-4, 3, (n_g, h_kv, 1), generator=g).float()
     v = torch.randn(n_g, h_kv, 128, generator=g)
