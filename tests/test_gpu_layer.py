@@ -515,6 +515,61 @@ def test_layer_text_chunk_and_decode_steps_after_video():
         assert_layer_close(to_f64(cache.k)[:, :n_tok], ck, f"layer {l} cached K", layers=l + 1)
 
 
+@pytest.mark.parametrize("n_t", [1, 2])
+@pytest.mark.parametrize("dims", [SMALL, W.LayerDims(3584, 18944, 28, 4)], ids=["small", "7b"])
+def test_decode_step_equals_its_parts_bit_for_bit(dims, n_t):
+    """One or two tokens through the layer: the projections stream their weights, and every token is kept, so the
+    compaction is a plain append. The result must be, bit for bit, what the separate calls give: RMSNorm, rotary table, QKV, attention over the cache, o_proj + residual, RMSNorm, SwiGLU,
+    down + residual; and the appended cache rows are the step's own K and V."""
+    c0 = 333
+    layout = B.make_layout(dims.n_q_heads, dims.n_kv_heads, 128, "bf16")
+    shape = B.make_layer_shape(dims.d_model, dims.d_ff, dims.rms_eps, dims.rope_theta, dims.mrope_section)
+    wt = {k_: v_.to(DEV) for k_, v_ in W.make_decoder_layer(dims, 0, seed=3).items()}
+    weights = B.LayerWeights(**wt)
+    g = torch.Generator(device=DEV).manual_seed(n_t)
+    x = W.make_hidden(1, n_t, dims.d_model, seed=8).to(DEV)
+    pos = W.text_positions(n_t, 900).to(DEV)
+    ws = B.make_layer_workspace(layout, shape, n_t, 0)
+    caches = []
+    for _ in range(2):
+        cache = B.Cache(layout, c0 + n_t)
+        gg = torch.Generator(device=DEV).manual_seed(77)
+        cache.k.copy_(torch.randn(cache.k.shape, generator=gg, device=DEV).bfloat16())
+        cache.v.copy_(torch.randn(cache.v.shape, generator=gg, device=DEV).bfloat16())
+        cache.c.len = c0
+        caches.append(cache)
+    # the layer call
+    out = torch.full_like(x, float("nan"))
+    kept = torch.full((dims.n_kv_heads, n_t), -1, dtype=torch.int32, device=DEV)
+    B.layer_group(layout, shape, weights, x, pos, 0, 5000, None, "key_norm_small", n_t, caches[0], out, kept, ws)
+    # the same step from its parts
+    h = torch.empty_like(x)
+    cs = torch.empty(n_t, 64, 2, dtype=torch.float32, device=DEV)
+    q = torch.empty(n_t, dims.n_q_heads, 128, dtype=torch.bfloat16, device=DEV)
+    k = torch.empty(n_t, dims.n_kv_heads, 128, dtype=torch.bfloat16, device=DEV)
+    v = torch.empty_like(k)
+    attn = torch.empty_like(q)
+    x1, act, x2 = torch.empty_like(x), torch.empty(n_t, dims.d_ff, dtype=torch.bfloat16, device=DEV), torch.empty_like(x)
+    split = torch.empty(32 << 20, dtype=torch.uint8, device=DEV)      # what the layer offers the attention
+    B.rms_norm(x, wt["ln1_w"], h, dims.rms_eps)
+    B.rope_table(pos, 0, n_t, dims.rope_theta, dims.mrope_section, cs)
+    B.qkv_rope(layout, h, wt["w_qkv"], wt["b_qkv"], cs, q, k, v)
+    B.group_attend(layout, q, k, v, caches[1], attn, None, split)
+    B.linear(attn.view(n_t, -1), wt["w_o"], None, x, x1)
+    B.rms_norm(x1, wt["ln2_w"], h, dims.rms_eps)
+    B.swiglu_gate_up(h, wt["w_gate_up"], act)
+    B.linear(act, wt["w_down"], None, x1, x2)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    assert torch.equal(out, x2)
+    assert caches[0].len == c0 + n_t
+    for h_ in range(dims.n_kv_heads):
+        assert torch.equal(caches[0].k[h_, c0:c0 + n_t], k[:, h_]) and torch.equal(caches[0].v[h_, c0:c0 + n_t], v[:, h_])
+        assert torch.equal(caches[0].k[h_, :c0], caches[1].k[h_, :c0])
+    np.testing.assert_array_equal(kept.cpu().numpy(), np.tile(np.arange(n_t), (dims.n_kv_heads, 1)))
+    np.testing.assert_array_equal(caches[0].pos.cpu().numpy()[:, c0:c0 + n_t], 5000 + np.tile(np.arange(n_t), (dims.n_kv_heads, 1)))
+
+
 def test_layer_stack_replays_from_a_hip_graph():
     """A caller may capture the layer calls (side-stream fork/join, split projections and their second launches
     included) into a HIP graph: every replay, with eager work and synchronisations in between, reproduces the eager
