@@ -3,6 +3,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from conftest import ROOT, read_golden
@@ -162,6 +163,37 @@ def test_attend_plan_splits_only_the_last_round_of_a_long_launch():
                 assert p["scratch_bytes"] == s * h_kv * min(n_g * r, rb * 256) * 129 * 4 <= offered
                 assert -(-rb * s // pool) / s < 0.9                         # the split round is shorter than a whole one
                 assert p["workgroups"] >= (n_rb - rb + rb * s) * h_kv
+
+
+def test_attend_plan_invariants_on_random_shapes():
+    """Whatever the shape: a split has at least two chunks, every chunk starts on an existing cache tile, the partials
+    of the split rows fit the scratch that was offered, the grid holds every work item, and nothing is split without
+    scratch."""
+    rng = np.random.default_rng(20251128)
+    for _ in range(3000):
+        r = int(rng.choice([1, 2, 4, 7, 8, 16]))
+        h_kv = int(rng.choice([1, 2, 3, 4, 8, 16]))
+        n_g = int(rng.choice([1, 3, 33, 64, 100, 512, 1000, 2048, 2350, 4096, 8192, 20000, 32768]))
+        c = int(rng.choice([0, 1, 63, 64, 65, 500, 1023, 1024, 5000, 24000, 46125, 150000]))
+        offered = int(rng.choice([0, 1 << 20, 8 << 20, 32 << 20, 128 << 20]))
+        L = B.make_layout(r * h_kv, h_kv, 128, "bf16")
+        p = B.attend_plan(L, n_g, c, offered)
+        rows = n_g * r
+        if p["kernel"] == B.QP_ATTEND_MFMA_DECODE:
+            assert rows <= 32
+            continue
+        assert p["kernel"] == B.QP_ATTEND_MFMA
+        n_rb, n_ct = -(-rows // 256), -(-c // 64)
+        s_, per, rb = p["key_chunks"], p["tiles_per_chunk"], p["split_row_blocks"]
+        if s_ == 1:
+            assert (per, rb, p["scratch_bytes"]) == (0, 0, 0)
+        else:
+            assert offered > 0 and 2 <= s_ <= 128 and 1 <= rb <= n_rb
+            assert (s_ - 1) * per < n_ct <= s_ * per
+            assert p["scratch_bytes"] == s_ * h_kv * min(rows, rb * 256) * 129 * 4 <= offered
+            assert rb == n_rb or p["mirrored_rows"] == 0          # a partial split only with consecutive row blocks
+        assert p["workgroups"] >= (n_rb - rb + rb * s_) * h_kv
+        assert p["mirrored_rows"] == (1 if n_rb * h_kv <= 256 else 0)
 
 
 def test_attend_plan_chunks_cover_the_cache_exactly():
